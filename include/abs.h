@@ -1,0 +1,197 @@
+/*
+ * abs.h -- C ABI of the adaptive-batch-size local-gradient hot path for MI355X (gfx950).
+ *
+ * M worker replicas of one MLP live side by side in device memory.  Each call of
+ * abs_local_step() makes every replica take one local optimizer step on its own
+ * mini-batch and leaves behind the statistics that the batch-size tests need;
+ * abs_average_replicas() is the model average that ends a communication round.
+ * The operations are those of the paper "Communication-Efficient Adaptive Batch Size
+ * Strategies for Distributed Local Gradient Methods" (Lau, Li, Xu, Liu, Kolar):
+ * its Sec. 3 (problem, Local SGD), Sec. 4 (norm test, batch-size rule) and Alg. 1 / Alg. 2
+ * of its appendix "Main Algorithm".  All M workers are simulated on one GPU; the average
+ * is an in-device mean, not a collective.
+ *
+ * Conventions
+ *  - Every function returns an abs_status and never throws or aborts across the ABI.
+ *    On error, out-parameters are left untouched and abs_last_error() describes it.
+ *  - "host" / "device" on a pointer says where the memory lives.  The caller owns every
+ *    buffer it passes in (dataset, labels, indices, workspace, stream); the library
+ *    borrows the device pointers for the lifetime of the context and owns only the
+ *    abs_ctx object (plus a few hundred bytes of pinned host memory for the read-back of
+ *    the statistics).  The library allocates no device memory: all of it is carved from
+ *    the caller's workspace (abs_workspace_bytes says how much).
+ *  - abs_local_step and abs_average_replicas are asynchronous on the context's stream.
+ *    The *_test, get/set calls synchronise that stream.
+ *  - One context per host thread and stream; calls on one context are not re-entrant.
+ *  - Parameter vector layout (x0, get/set_params, get_grad): layer-major; for each layer
+ *    the weight W_l row-major [out_l x in_l], then (if has_bias) the bias [out_l].
+ *  - Per-sample loss is softmax cross-entropy of the last layer's outputs (natural log);
+ *    the backprop signals are those of the per-sample loss, not divided by the batch size.
+ */
+#ifndef ABS_H_
+#define ABS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct abs_ctx abs_ctx;
+
+typedef enum {
+  ABS_OK = 0,
+  ABS_EINVAL = 1,       /* bad argument (range, NULL, alignment) */
+  ABS_ENOMEM = 2,       /* workspace too small */
+  ABS_ESTATE = 3,       /* call out of order (e.g. a test before any local step) */
+  ABS_EHIP = 4,         /* a HIP runtime call failed */
+  ABS_EUNSUPPORTED = 5  /* shape the kernels do not cover */
+} abs_status;
+
+enum { ABS_ACT_NONE = 0, ABS_ACT_RELU = 1, ABS_ACT_GELU = 2 };   /* GELU: exact erf form */
+enum { ABS_OPT_SGD = 0, ABS_OPT_SHB = 1, ABS_OPT_ADAMW = 2 };
+enum { ABS_PREC_F32 = 0,    /* fp32 operands and accumulation */
+       ABS_PREC_BF16 = 1 }; /* bf16 operands, fp32 accumulation, fp32 master weights */
+enum { ABS_STATS_NORM = 1,  /* sum_i ||g_i||^2 and ||gbar||^2 (norm test) */
+       ABS_STATS_IP = 2 };  /* also sum_i <g_i,gbar> and its square (inner-product tests) */
+
+typedef struct {
+  int n_layers;            /* L >= 1 linear layers */
+  const int *dims;         /* host, L+1 entries: dims[0] inputs ... dims[L] classes.
+                              In ABS_PREC_BF16 dims[0..L-1] must be multiples of 8. */
+  int act;                 /* ABS_ACT_* applied after every layer but the last */
+  int has_bias;
+  int prec;                /* ABS_PREC_* */
+  int M;                   /* number of worker replicas, >= 1 */
+  int b_cap;               /* largest local batch size any call will use, >= 2 */
+  int opt;                 /* ABS_OPT_* : the inner optimizer ("or other inner optimizers", Alg. 1) */
+  float momentum;          /* SHB:  v <- momentum v + g ; x <- x - lr v */
+  float beta1, beta2, eps, weight_decay;  /* AdamW, decoupled decay, bias-corrected moments */
+  int stats_mask;          /* ABS_STATS_* bits gathered by every local step */
+  void *hip_stream;        /* hipStream_t of the caller (NULL = the null stream) */
+  void *workspace;         /* device, 256-byte aligned, caller-allocated */
+  size_t workspace_bytes;
+} abs_config;
+
+/* One worker's statistics and test outcome for the most recent local step. */
+typedef struct {
+  int b;                   /* local batch size the statistics were gathered on */
+  double sum_sq;           /* S1 = sum_i ||g_i||^2 over the batch (per-sample gradients) */
+  double gbar_sq;          /* S2 = ||gbar||^2, gbar = local batch gradient, eq. (batch_grad) */
+  double sum_q;            /* S4 = sum_i <g_i, gbar>            (0 unless ABS_STATS_IP) */
+  double sum_q2;           /* S3 = sum_i <g_i, gbar>^2          (0 unless ABS_STATS_IP) */
+  double loss_sum;         /* sum_i f_i over the batch */
+  double var;              /* batch variance of the tested quantity, eq. (def_var) */
+  double var_perp;         /* variance of the components orthogonal to gbar (augmented test) */
+  double lhs, rhs;         /* the two sides of the tested inequality */
+  double ratio;            /* the quantity whose ceiling is T */
+  long long T;             /* test statistic, Alg. 1: ceil(ratio) */
+  int pass;                /* 1 if the condition holds (batch size need not grow) */
+} abs_test_result;
+
+/* Device bytes abs_init_replicas needs in cfg->workspace for a dataset of N samples. */
+abs_status abs_workspace_bytes(const abs_config *cfg, int64_t N, size_t *bytes /*host*/);
+
+/*
+ * Create the M replicas, all equal to x0 (Alg. 1, "initial model parameters x_{0,0}^m = x_0").
+ *   x0_host : host, n_params floats in the layout above.
+ *   X_dev   : device, float [N x dims[0]] row-major, the (shared, i.i.d.) training set.
+ *   y_dev   : device, int32 [N] labels in [0, dims[L]).
+ * Both stay borrowed until abs_destroy.  Optimizer state starts at zero.
+ */
+abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const float *X_dev,
+                             const int32_t *y_dev, int64_t N, abs_ctx **out /*host*/);
+
+/*
+ * One local step of all M workers (the body of Alg. 1's inner loop): gather the batch,
+ * forward, per-sample backprop signals, the local batch gradient of eq. (batch_grad), the
+ * statistics selected by stats_mask, then the optimizer update with learning rate lr.
+ * The statistics refer to the gradient at the iterate *before* the update.
+ *   idx_dev : device, int32 [M x b], row m = the sample indices of worker m's batch
+ *             ("sample the local batch uniformly", with replacement; drawn by the caller).
+ *   b       : local batch size, the same for every worker (the paper's practical rule gives
+ *             all workers the maximum), 2 <= b <= b_cap.
+ * Per-sample gradients are never formed: ||g_i||^2 = sum_l ||delta_i^l||^2 (||a_i^{l-1}||^2 + 1)
+ * and <g_i,gbar> = sum_l delta_i^l . (Gbar_l a_i^{l-1} + betabar_l).
+ */
+abs_status abs_local_step(abs_ctx *ctx, const int32_t *idx_dev, int b, float lr);
+
+/*
+ * Approximate local norm test, eqs. (approx_norm_local) and (test_stat), per worker:
+ *   Var = (S1 - b S2)/(b-1)  [eq. (def_var)],  condition Var/b <= eta^2 S2,
+ *   T = ceil(Var / (eta^2 S2)).   0 < eta < 1.   A zero batch gradient gives T = b, pass = 1.
+ *   out : host, M entries.
+ */
+abs_status abs_norm_test(abs_ctx *ctx, double eta, abs_test_result *out);
+
+/*
+ * Inner-product test of the adaptive-sampling literature the paper cites (named at the end
+ * of its Sec. 4.1), applied per worker to its own batch:
+ *   Var_q = sample variance of q_i = <g_i,gbar>;  condition Var_q/b <= theta^2 S2^2;
+ *   T_ip = ceil(Var_q / (theta^2 S2^2)).
+ * With nu > 0 (augmented test) also Var_perp = (S1 - S3/S2)/(b-1), condition
+ * Var_perp/b <= nu^2 S2, and T = max(T_ip, ceil(Var_perp/(nu^2 S2))).  nu <= 0: plain test.
+ * Needs ABS_STATS_IP in stats_mask.   out : host, M entries.
+ */
+abs_status abs_inner_product_test(abs_ctx *ctx, double theta, double nu, abs_test_result *out);
+
+/*
+ * Once-per-round norm test of Alg. 2 from the M local batch gradients of the most recent
+ * local step: Var = b/(M-1) sum_m ||g^m - gbar||^2, T = ceil(Var / (M eta^2 ||gbar||^2)),
+ * gbar the mean over workers.  Needs M >= 2.  out : host, ONE entry (sum_sq = sum_m ||g^m||^2,
+ * gbar_sq = ||gbar||^2).
+ */
+abs_status abs_cross_worker_test(abs_ctx *ctx, double eta, abs_test_result *out);
+
+/*
+ * Batch-size rule, pure host function: b_next^m = min(b_cap, max(T^m, b_cur^m)) (Alg. 1);
+ * with sync_max != 0 every worker gets the maximum over workers (display after eq. test_stat).
+ *   res, b_cur, b_next : host, M entries each.
+ */
+abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_cur, int b_cap,
+                               int sync_max, int *b_next);
+
+/* Model average that ends a round, eq. (local_sgd_alt): x^m <- (1/M) sum_m x^m for all m.
+ * Only the parameters are averaged; optimizer state stays local. */
+abs_status abs_average_replicas(abs_ctx *ctx);
+
+/* Parity helpers (synchronising).  m in [0, M); buffers are host, n_params floats. */
+abs_status abs_get_params(abs_ctx *ctx, int m, float *out_host);
+abs_status abs_set_params(abs_ctx *ctx, int m, const float *in_host);
+abs_status abs_get_grad(abs_ctx *ctx, int m, float *out_host);    /* last local batch gradient */
+/* Per-sample ||g_i||^2 (and <g_i,gbar> if gathered; else q_host may be NULL) of worker m
+ * for the most recent step: host, b floats each. */
+abs_status abs_get_per_sample(abs_ctx *ctx, int m, float *n_host, float *q_host);
+
+/* Number of parameters of cfg's network (host only, no GPU call). */
+abs_status abs_n_params(const abs_config *cfg, int64_t *n /*host*/);
+
+/*
+ * Statistics and averaging alone, on caller-supplied layer inputs and backprop signals
+ * (no model run): for each of M replicas and L stacked linear layers without bias,
+ *   a_dev[l]     : device, bf16 [M x b x in_l],  delta_dev[l] : device, bf16 [M x b x out_l]
+ * computes Gbar_l = delta^T a / b (fp32, into workspace), n_i, S1, S2, q_i, S3, S4 with the
+ * same kernels as abs_local_step.   out : host, M entries (b, sum_sq, gbar_sq, sum_q, sum_q2).
+ *   n_out_dev, q_out_dev : device, float [M x b] (either may be NULL).
+ *   gbar_out_dev : device, float, sum_l out_l*in_l per replica, replica-major (may be NULL).
+ */
+abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M, int b,
+                           const void *const *a_dev, const void *const *delta_dev,
+                           void *workspace, size_t workspace_bytes, void *hip_stream,
+                           abs_test_result *out, float *n_out_dev, float *q_out_dev,
+                           float *gbar_out_dev);
+abs_status abs_layer_stats_workspace_bytes(int L, const int *in_dims, const int *out_dims,
+                                           int M, int b, size_t *bytes);
+
+/* Mean over M replicas of a bf16 parameter block, written back to all M (fp32 sum in
+ * replica order, one rounding):  params_dev : device, bf16 [M x n]; n multiple of 8. */
+abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *hip_stream);
+
+abs_status abs_destroy(abs_ctx *ctx);
+const char *abs_last_error(const abs_ctx *ctx);   /* ctx may be NULL: last error of this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABS_H_ */

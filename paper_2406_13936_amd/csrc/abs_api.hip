@@ -1,0 +1,705 @@
+// C ABI of the library (declared in include/abs.h): context, workspace plan, the call
+// sequence of one local step, host-side tests and the batch-size rule.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/abs.h"
+#include "abs_internal.h"
+
+using namespace absk;
+
+namespace {
+
+thread_local std::string g_err;
+
+constexpr int MAXL = 16;
+
+inline long long rup(long long v, long long a) { return (v + a - 1) / a * a; }
+
+struct Plan {
+  int L = 0;
+  bool bf16 = false, gelu = false, want_ip = false;
+  int esz = 4;                       // bytes per activation element
+  std::vector<int> dims, ld;         // ld[l]: row stride of layer-l activations / signals
+  std::vector<long long> offW, offB; // internal (padded) parameter offsets
+  std::vector<long long> extW, extB; // packed external offsets
+  long long P = 0, Ppad = 0;
+  int M = 0, cap = 0;
+  int qparts[MAXL] = {0};
+  // byte offsets into the workspace
+  size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
+  size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
+  size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0;
+  size_t total = 0;
+};
+
+abs_status fail(abs_status st, const std::string &msg) {
+  g_err = msg;
+  return st;
+}
+
+abs_status check_cfg(const abs_config *c) {
+  if (!c || !c->dims) return fail(ABS_EINVAL, "config or dims is NULL");
+  if (c->n_layers < 1 || c->n_layers > MAXL) return fail(ABS_EINVAL, "n_layers must be in [1,16]");
+  for (int l = 0; l <= c->n_layers; ++l)
+    if (c->dims[l] < 1) return fail(ABS_EINVAL, "layer width < 1");
+  if (c->dims[c->n_layers] < 2) return fail(ABS_EINVAL, "need at least 2 classes");
+  if (c->M < 1) return fail(ABS_EINVAL, "M < 1");
+  if (c->b_cap < 2) return fail(ABS_EINVAL, "b_cap < 2");
+  if (c->act < ABS_ACT_NONE || c->act > ABS_ACT_GELU) return fail(ABS_EINVAL, "unknown activation");
+  if (c->opt < ABS_OPT_SGD || c->opt > ABS_OPT_ADAMW) return fail(ABS_EINVAL, "unknown optimizer");
+  if (c->prec != ABS_PREC_F32 && c->prec != ABS_PREC_BF16) return fail(ABS_EINVAL, "unknown precision");
+  if (!(c->stats_mask & ABS_STATS_NORM)) return fail(ABS_EINVAL, "stats_mask needs ABS_STATS_NORM");
+  if (c->prec == ABS_PREC_BF16)
+    for (int l = 0; l < c->n_layers; ++l)
+      if (c->dims[l] % 8) return fail(ABS_EUNSUPPORTED, "bf16 mode needs dims[0..L-1] to be multiples of 8");
+  if ((long long)c->M * c->b_cap > (1LL << 30)) return fail(ABS_EUNSUPPORTED, "M * b_cap too large");
+  return ABS_OK;
+}
+
+void make_plan(const abs_config *c, long long N, Plan &pl) {
+  pl.L = c->n_layers;
+  pl.bf16 = c->prec == ABS_PREC_BF16;
+  pl.gelu = c->act == ABS_ACT_GELU;
+  pl.want_ip = (c->stats_mask & ABS_STATS_IP) != 0;
+  pl.esz = pl.bf16 ? 2 : 4;
+  pl.M = c->M;
+  pl.cap = c->b_cap;
+  pl.dims.assign(c->dims, c->dims + pl.L + 1);
+  pl.ld.resize(pl.L + 1);
+  for (int l = 0; l <= pl.L; ++l) pl.ld[l] = (int)rup(pl.dims[l], 8);
+  pl.offW.assign(pl.L + 1, 0); pl.offB.assign(pl.L + 1, 0);
+  pl.extW.assign(pl.L + 1, 0); pl.extB.assign(pl.L + 1, 0);
+  long long o = 0, e = 0;
+  for (int l = 1; l <= pl.L; ++l) {
+    const long long w = (long long)pl.dims[l] * pl.dims[l - 1];
+    pl.offW[l] = o; o = rup(o + w, 64);
+    pl.extW[l] = e; e += w;
+    if (c->has_bias) {
+      pl.offB[l] = o; o = rup(o + pl.dims[l], 64);
+      pl.extB[l] = e; e += pl.dims[l];
+    }
+  }
+  pl.P = e;
+  pl.Ppad = rup(o, 256);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off = (size_t)rup((long long)(off + bytes), 256); return r; };
+  const size_t MP = (size_t)pl.M * pl.Ppad;
+  pl.o_xm = take(MP * 4);
+  if (pl.bf16) pl.o_xs = take(MP * 2);
+  pl.o_grad = take(MP * 4);
+  if (pl.bf16 && pl.want_ip) pl.o_gradbf = take(MP * 2);
+  if (c->opt != ABS_OPT_SGD) pl.o_v = take(MP * 4);
+  if (c->opt == ABS_OPT_ADAMW) pl.o_m = take(MP * 4);
+  if (pl.bf16) pl.o_Xbf = take((size_t)N * pl.dims[0] * 2);
+  const size_t MB = (size_t)pl.M * pl.cap;
+  for (int l = 0; l < pl.L; ++l) pl.o_A[l] = take(MB * pl.ld[l] * pl.esz);
+  if (pl.gelu)
+    for (int l = 1; l < pl.L; ++l) pl.o_Dact[l] = take(MB * pl.ld[l] * pl.esz);
+  for (int l = 1; l <= pl.L; ++l) pl.o_Dl[l] = take(MB * pl.ld[l] * pl.esz);
+  pl.o_Z = take(MB * pl.ld[pl.L] * 4);
+  if (!pl.bf16 && pl.want_ip) {
+    int mx = 0;
+    for (int l = 1; l <= pl.L; ++l) mx = pl.ld[l] > mx ? pl.ld[l] : mx;
+    pl.o_U = take(MB * mx * 4);
+  }
+  for (int l = 0; l < pl.L; ++l) pl.o_an[l] = take(MB * 4);
+  for (int l = 1; l <= pl.L; ++l) pl.o_dn[l] = take(MB * 4);
+  pl.o_loss = take(MB * 4);
+  pl.o_nout = take(MB * 4);
+  pl.o_qout = take(MB * 4);
+  if (pl.want_ip) {
+    for (int l = 1; l <= pl.L; ++l) {
+      pl.qparts[l - 1] = pl.bf16 ? gemm_bf16_ipdot_parts(pl.dims[l]) : (l == 1 ? 1 : 0);
+      if (pl.qparts[l - 1]) pl.o_qpart[l - 1] = take(MB * 4 * pl.qparts[l - 1]);
+    }
+  }
+  pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
+  pl.o_stats = take((size_t)pl.M * 8 * 8);
+  pl.o_cw = take((2 * STATS_PBLK + 8) * 8);
+  pl.total = off;
+}
+
+}  // namespace
+
+struct abs_ctx {
+  Plan pl;
+  abs_config cfg;
+  hipStream_t stream = nullptr;
+  unsigned char *ws = nullptr;
+  const float *X = nullptr;
+  const int32_t *y = nullptr;
+  long long N = 0;
+  double *host_stats = nullptr;     // pinned, M*8 + 8 doubles
+  long long t = 0;                  // local steps taken (Adam bias correction)
+  int last_b = 0;
+  bool have_stats = false;
+  std::string err;
+
+  template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
+};
+
+namespace {
+
+abs_status cfail(abs_ctx *c, abs_status st, const std::string &msg) {
+  if (c) c->err = msg;
+  g_err = msg;
+  return st;
+}
+
+#define HIPCHK(ctx, call)                                                                       \
+  do {                                                                                          \
+    hipError_t e_ = (call);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return cfail(ctx, ABS_EHIP, std::string(#call) + ": " + hipGetErrorString(e_));           \
+  } while (0)
+
+// external packed vector <-> internal padded layout
+void to_internal(const Plan &pl, bool has_bias, const float *ext, float *in /*Ppad, zeroed*/) {
+  for (int l = 1; l <= pl.L; ++l) {
+    const long long w = (long long)pl.dims[l] * pl.dims[l - 1];
+    std::memcpy(in + pl.offW[l], ext + pl.extW[l], w * sizeof(float));
+    if (has_bias) std::memcpy(in + pl.offB[l], ext + pl.extB[l], pl.dims[l] * sizeof(float));
+  }
+}
+void to_external(const Plan &pl, bool has_bias, const float *in, float *ext) {
+  for (int l = 1; l <= pl.L; ++l) {
+    const long long w = (long long)pl.dims[l] * pl.dims[l - 1];
+    std::memcpy(ext + pl.extW[l], in + pl.offW[l], w * sizeof(float));
+    if (has_bias) std::memcpy(ext + pl.extB[l], in + pl.offB[l], pl.dims[l] * sizeof(float));
+  }
+}
+
+hipError_t gemm(const abs_ctx *c, const GemmP &p, int epi) {
+  return c->pl.bf16 ? launch_gemm_bf16(p, epi, c->stream) : launch_gemm_f32(p, epi, c->stream);
+}
+
+void fill_result(abs_test_result &r, int b, const double *st) {
+  std::memset(&r, 0, sizeof(r));
+  r.b = b;
+  r.sum_sq = st[0];
+  r.gbar_sq = st[1];
+  r.sum_q2 = st[2];
+  r.sum_q = st[3];
+  r.loss_sum = st[4];
+}
+
+// ratio and its ceiling; a zero batch gradient leaves the batch size unchanged
+void ceil_ratio(double num, double den, int b, double &ratio, long long &T) {
+  if (!(den > 0.0)) { ratio = (double)b; T = b; return; }
+  ratio = num / den;
+  const double c = std::ceil(ratio);
+  T = c > 9.0e18 ? (long long)9e18 : (c < -9.0e18 ? (long long)-9e18 : (long long)c);
+}
+
+abs_status read_stats(abs_ctx *c) {
+  if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
+  HIPCHK(c, hipMemcpyAsync(c->host_stats, c->at<double>(c->pl.o_stats), (size_t)c->pl.M * 8 * sizeof(double),
+                           hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return ABS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *abs_last_error(const abs_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+abs_status abs_n_params(const abs_config *cfg, int64_t *n) {
+  if (!n) return fail(ABS_EINVAL, "n is NULL");
+  abs_status st = check_cfg(cfg);
+  if (st != ABS_OK) return st;
+  Plan pl;
+  make_plan(cfg, 0, pl);
+  *n = pl.P;
+  return ABS_OK;
+}
+
+abs_status abs_workspace_bytes(const abs_config *cfg, int64_t N, size_t *bytes) {
+  if (!bytes) return fail(ABS_EINVAL, "bytes is NULL");
+  if (N < 1) return fail(ABS_EINVAL, "N < 1");
+  abs_status st = check_cfg(cfg);
+  if (st != ABS_OK) return st;
+  Plan pl;
+  make_plan(cfg, N, pl);
+  *bytes = pl.total;
+  return ABS_OK;
+}
+
+abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const float *X_dev,
+                             const int32_t *y_dev, int64_t N, abs_ctx **out) {
+  if (!out || !x0_host || !X_dev || !y_dev) return fail(ABS_EINVAL, "NULL argument");
+  if (N < 1 || N > 0x7fffffffLL) return fail(ABS_EINVAL, "N out of range");
+  abs_status st = check_cfg(cfg);
+  if (st != ABS_OK) return st;
+  if (!cfg->workspace || (reinterpret_cast<uintptr_t>(cfg->workspace) & 255))
+    return fail(ABS_EINVAL, "workspace must be a 256-byte aligned device pointer");
+  if ((reinterpret_cast<uintptr_t>(X_dev) & 15)) return fail(ABS_EINVAL, "X_dev must be 16-byte aligned");
+  abs_ctx *c = new (std::nothrow) abs_ctx();
+  if (!c) return fail(ABS_ENOMEM, "host allocation failed");
+  make_plan(cfg, N, c->pl);
+  if (cfg->workspace_bytes < c->pl.total) {
+    delete c;
+    return fail(ABS_ENOMEM, "workspace too small (see abs_workspace_bytes)");
+  }
+  c->cfg = *cfg;
+  c->cfg.dims = c->pl.dims.data();
+  c->stream = static_cast<hipStream_t>(cfg->hip_stream);
+  c->ws = static_cast<unsigned char *>(cfg->workspace);
+  c->X = X_dev; c->y = y_dev; c->N = N;
+  const Plan &pl = c->pl;
+  auto bail = [&](const std::string &m) { g_err = m; if (c->host_stats) (void)hipHostFree(c->host_stats); delete c; return ABS_EHIP; };
+  hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&c->host_stats), ((size_t)pl.M * 8 + 8) * sizeof(double), hipHostMallocDefault);
+  if (e != hipSuccess) { c->host_stats = nullptr; return bail(std::string("hipHostMalloc: ") + hipGetErrorString(e)); }
+  // zero parameters, gradient and optimizer state (including their padding)
+  const size_t MP = (size_t)pl.M * pl.Ppad;
+  if ((e = launch_fill_zero(c->at<void>(pl.o_xm), MP * 4, c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  if ((e = launch_fill_zero(c->at<void>(pl.o_grad), MP * 4, c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  if (pl.bf16 && pl.want_ip)
+    if ((e = launch_fill_zero(c->at<void>(pl.o_gradbf), MP * 2, c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  if (cfg->opt != ABS_OPT_SGD)
+    if ((e = launch_fill_zero(c->at<void>(pl.o_v), MP * 4, c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  if (cfg->opt == ABS_OPT_ADAMW)
+    if ((e = launch_fill_zero(c->at<void>(pl.o_m), MP * 4, c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  std::vector<float> in(pl.Ppad, 0.0f);
+  to_internal(pl, cfg->has_bias != 0, x0_host, in.data());
+  for (int m = 0; m < pl.M; ++m)
+    if ((e = hipMemcpy(c->at<float>(pl.o_xm) + (size_t)m * pl.Ppad, in.data(), pl.Ppad * sizeof(float), hipMemcpyHostToDevice)) != hipSuccess)
+      return bail(std::string("hipMemcpy x0: ") + hipGetErrorString(e));
+  if (pl.bf16) {
+    if ((e = launch_convert_f32_to_bf16(c->at<float>(pl.o_xm), c->at<bf16_t>(pl.o_xs), (long long)MP, c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+    if ((e = launch_convert_f32_to_bf16(X_dev, c->at<bf16_t>(pl.o_Xbf), (long long)N * pl.dims[0], c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  }
+  if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
+  *out = c;
+  return ABS_OK;
+}
+
+abs_status abs_destroy(abs_ctx *c) {
+  if (!c) return ABS_OK;
+  (void)hipStreamSynchronize(c->stream);
+  if (c->host_stats) (void)hipHostFree(c->host_stats);
+  delete c;
+  return ABS_OK;
+}
+
+abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
+  const Plan &pl = c->pl;
+  if (b < 2 || b > pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
+  if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
+  const int L = pl.L, M = pl.M, isb = pl.bf16 ? 1 : 0;
+  const long long cap = pl.cap;
+  hipStream_t s = c->stream;
+  const bool hb = c->cfg.has_bias != 0;
+  float *xm = c->at<float>(pl.o_xm);
+  float *grad = c->at<float>(pl.o_grad);
+  const void *wts = pl.bf16 ? static_cast<const void *>(c->at<bf16_t>(pl.o_xs)) : static_cast<const void *>(xm);
+  auto wptr = [&](int l) -> const void * {
+    return static_cast<const unsigned char *>(wts) + (size_t)pl.offW[l] * pl.esz;
+  };
+  auto act_ptr = [&](size_t off) -> void * { return c->ws + off; };
+
+  // batch gather (Alg. 1: "sample the local batch")
+  const void *Xsrc = pl.bf16 ? static_cast<const void *>(c->at<bf16_t>(pl.o_Xbf)) : static_cast<const void *>(c->X);
+  HIPCHK(c, launch_gather_rows(isb, Xsrc, pl.dims[0], (int)c->N, idx_dev, M, b, act_ptr(pl.o_A[0]), cap * pl.ld[0],
+                               pl.ld[0], c->at<float>(pl.o_an[0]), cap, s));
+
+  // forward
+  for (int l = 1; l <= L; ++l) {
+    GemmP p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
+    p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1];
+    p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M;
+    if (hb) { p.bias = xm + pl.offB[l]; p.sBiasg = pl.Ppad; }
+    p.act = c->cfg.act;
+    if (l < L) {
+      p.C = act_ptr(pl.o_A[l]); p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l]; p.pad_to_ld = 1;
+      if (pl.gelu) { p.C2 = act_ptr(pl.o_Dact[l]); p.sC2g = cap * pl.ld[l]; p.ldc2 = pl.ld[l]; }
+      HIPCHK(c, gemm(c, p, EPI_FWD_ACT));
+      HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, s));
+    } else {
+      p.C = c->at<float>(pl.o_Z); p.sCg = cap * pl.ld[L]; p.ldc = pl.ld[L];
+      HIPCHK(c, gemm(c, p, EPI_LOGITS));
+    }
+  }
+  // loss head: per-sample backprop signal of the last layer
+  HIPCHK(c, launch_softmax_ce(isb, c->at<float>(pl.o_Z), cap * pl.ld[L], pl.ld[L], pl.dims[L], c->y, (int)c->N, idx_dev, M, b,
+                              act_ptr(pl.o_Dl[L]), cap * pl.ld[L], pl.ld[L], c->at<float>(pl.o_dn[L]),
+                              c->at<float>(pl.o_loss), cap, s));
+  // backward-data
+  for (int l = L; l >= 2; --l) {
+    GemmP p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l];
+    p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1]; p.b_trans = 1;
+    p.Md = b; p.Nd = pl.dims[l - 1]; p.Kd = pl.dims[l]; p.groups = M;
+    p.C = act_ptr(pl.o_Dl[l - 1]); p.sCg = cap * pl.ld[l - 1]; p.ldc = pl.ld[l - 1]; p.pad_to_ld = 1;
+    p.act = c->cfg.act;
+    p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
+    p.sEg = cap * pl.ld[l - 1]; p.lde = pl.ld[l - 1];
+    HIPCHK(c, gemm(c, p, EPI_BWD));
+    HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, s));
+  }
+  // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
+  const float inv_b = 1.0f / (float)b;
+  for (int l = 1; l <= L; ++l) {
+    GemmP p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l]; p.a_trans = 1;
+    p.B = act_ptr(pl.o_A[l - 1]); p.sBg = cap * pl.ld[l - 1]; p.ldb = pl.ld[l - 1]; p.b_trans = 1;
+    p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M;
+    p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
+    p.alpha = inv_b;
+    if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
+    HIPCHK(c, gemm(c, p, EPI_WGRAD));
+    if (hb)
+      HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad, s));
+  }
+  // inner products <g_i, gbar>
+  StatsP sp;
+  std::memset(&sp, 0, sizeof(sp));
+  if (pl.want_ip) {
+    for (int l = 1; l <= L; ++l) {
+      GemmP p;
+      std::memset(&p, 0, sizeof(p));
+      p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
+      p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M;
+      p.ldb = pl.dims[l - 1]; p.sBg = pl.Ppad;
+      if (hb) { p.bias = grad + pl.offB[l]; p.sBiasg = pl.Ppad; }
+      if (pl.bf16) {
+        p.B = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l];
+        p.E = act_ptr(pl.o_Dl[l]); p.sEg = cap * pl.ld[l]; p.lde = pl.ld[l];
+        p.part = c->at<float>(pl.o_qpart[l - 1]);
+        p.sPartg = cap * pl.qparts[l - 1]; p.sPartTile = cap;
+        HIPCHK(c, launch_fill_zero(p.part, (long long)M * cap * pl.qparts[l - 1] * 4, s));
+        HIPCHK(c, gemm(c, p, EPI_IPDOT));
+        sp.qpart[l - 1] = p.part; sp.nparts[l - 1] = pl.qparts[l - 1];
+        sp.sQg[l - 1] = p.sPartg; sp.sQpart[l - 1] = cap;
+      } else {
+        p.B = grad + pl.offW[l];
+        float *U = c->at<float>(pl.o_U);
+        p.C = U; p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l];
+        HIPCHK(c, gemm(c, p, EPI_LOGITS));
+        float *q = c->at<float>(pl.o_qpart[0]);
+        HIPCHK(c, launch_rowdot_f32(static_cast<const float *>(act_ptr(pl.o_Dl[l])), cap * pl.ld[l], pl.ld[l], U,
+                                    cap * pl.ld[l], pl.ld[l], pl.dims[l], M, b, q, cap, l > 1, s));
+        sp.qpart[l - 1] = q; sp.nparts[l - 1] = (l == 1) ? 1 : 0; sp.sQg[l - 1] = cap; sp.sQpart[l - 1] = cap;
+      }
+    }
+  }
+  // statistics
+  sp.L = L; sp.has_bias = hb ? 1 : 0; sp.groups = M; sp.b = b; sp.want_ip = pl.want_ip ? 1 : 0;
+  for (int l = 0; l < L; ++l) { sp.an[l] = c->at<float>(pl.o_an[l]); sp.dn[l] = c->at<float>(pl.o_dn[l + 1]); }
+  sp.sNg = cap;
+  sp.loss = c->at<float>(pl.o_loss);
+  sp.n_out = c->at<float>(pl.o_nout); sp.q_out = c->at<float>(pl.o_qout);
+  sp.grad = grad; sp.Ppad = pl.Ppad;
+  sp.partials = c->at<double>(pl.o_partials); sp.stats = c->at<double>(pl.o_stats);
+  HIPCHK(c, launch_stats(sp, s));
+  // optimizer update (Alg. 1: "local SGD step ... or other inner optimizers")
+  c->t += 1;
+  UpdateP up;
+  std::memset(&up, 0, sizeof(up));
+  up.x = xm; up.g = grad;
+  up.v = c->cfg.opt != ABS_OPT_SGD ? c->at<float>(pl.o_v) : nullptr;
+  up.m = c->cfg.opt == ABS_OPT_ADAMW ? c->at<float>(pl.o_m) : nullptr;
+  up.shadow = pl.bf16 ? c->at<bf16_t>(pl.o_xs) : nullptr;
+  up.n = (long long)M * pl.Ppad;
+  up.opt = c->cfg.opt; up.lr = lr; up.momentum = c->cfg.momentum;
+  up.beta1 = c->cfg.beta1; up.beta2 = c->cfg.beta2; up.eps = c->cfg.eps; up.wd = c->cfg.weight_decay;
+  if (c->cfg.opt == ABS_OPT_ADAMW) {
+    up.c1 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta1, (double)c->t)));
+    up.c2 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta2, (double)c->t)));
+  }
+  HIPCHK(c, launch_update(up, s));
+  c->last_b = b;
+  c->have_stats = true;
+  return ABS_OK;
+}
+
+abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) {
+  if (!c || !out) return fail(ABS_EINVAL, "NULL argument");
+  if (!(eta > 0.0 && eta < 1.0)) return cfail(c, ABS_EINVAL, "eta must be in (0,1)");
+  abs_status st = read_stats(c);
+  if (st != ABS_OK) return st;
+  const int b = c->last_b;
+  for (int m = 0; m < c->pl.M; ++m) {
+    abs_test_result r;
+    fill_result(r, b, c->host_stats + m * 8);
+    r.var = (r.sum_sq - (double)b * r.gbar_sq) / (double)(b - 1);
+    r.lhs = r.var / (double)b;
+    r.rhs = eta * eta * r.gbar_sq;
+    ceil_ratio(r.var, eta * eta * r.gbar_sq, b, r.ratio, r.T);
+    r.pass = (r.lhs <= r.rhs) ? 1 : 0;
+    out[m] = r;
+  }
+  return ABS_OK;
+}
+
+abs_status abs_inner_product_test(abs_ctx *c, double theta, double nu, abs_test_result *out) {
+  if (!c || !out) return fail(ABS_EINVAL, "NULL argument");
+  if (!(theta > 0.0)) return cfail(c, ABS_EINVAL, "theta must be positive");
+  if (!c->pl.want_ip) return cfail(c, ABS_ESTATE, "stats_mask lacks ABS_STATS_IP");
+  abs_status st = read_stats(c);
+  if (st != ABS_OK) return st;
+  const int b = c->last_b;
+  for (int m = 0; m < c->pl.M; ++m) {
+    abs_test_result r;
+    fill_result(r, b, c->host_stats + m * 8);
+    const double S1 = r.sum_sq, S2 = r.gbar_sq, S3 = r.sum_q2, S4 = r.sum_q;
+    r.var = (S3 - S4 * S4 / (double)b) / (double)(b - 1);
+    r.var_perp = S2 > 0.0 ? (S1 - S3 / S2) / (double)(b - 1) : 0.0;
+    r.lhs = r.var / (double)b;
+    r.rhs = theta * theta * S2 * S2;
+    ceil_ratio(r.var, r.rhs, b, r.ratio, r.T);
+    r.pass = (r.lhs <= r.rhs) ? 1 : 0;
+    if (nu > 0.0) {
+      double ro; long long To;
+      ceil_ratio(r.var_perp, nu * nu * S2, b, ro, To);
+      if (To > r.T) r.T = To;
+      if (ro > r.ratio) r.ratio = ro;
+      if (!(r.var_perp / (double)b <= nu * nu * S2)) r.pass = 0;
+    }
+    out[m] = r;
+  }
+  return ABS_OK;
+}
+
+abs_status abs_cross_worker_test(abs_ctx *c, double eta, abs_test_result *out) {
+  if (!c || !out) return fail(ABS_EINVAL, "NULL argument");
+  if (!(eta > 0.0 && eta < 1.0)) return cfail(c, ABS_EINVAL, "eta must be in (0,1)");
+  if (c->pl.M < 2) return cfail(c, ABS_EINVAL, "the cross-worker estimator needs M >= 2");
+  if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
+  const Plan &pl = c->pl;
+  double *cw = c->at<double>(pl.o_cw);
+  HIPCHK(c, launch_cross_worker(c->at<float>(pl.o_grad), pl.M, pl.Ppad, cw + 8, cw, c->stream));
+  double *h = c->host_stats + (size_t)pl.M * 8;
+  HIPCHK(c, hipMemcpyAsync(h, cw, 2 * sizeof(double), hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  abs_test_result r;
+  std::memset(&r, 0, sizeof(r));
+  const int b = c->last_b, M = pl.M;
+  r.b = b; r.sum_sq = h[0]; r.gbar_sq = h[1];
+  r.var = (double)b * (h[0] - (double)M * h[1]) / (double)(M - 1);
+  r.lhs = r.var / ((double)b * M);
+  r.rhs = eta * eta * r.gbar_sq;
+  ceil_ratio(r.var, (double)M * eta * eta * r.gbar_sq, b, r.ratio, r.T);
+  r.pass = (r.lhs <= r.rhs) ? 1 : 0;
+  *out = r;
+  return ABS_OK;
+}
+
+abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_cur, int b_cap, int sync_max,
+                               int *b_next) {
+  if (!res || !b_cur || !b_next) return fail(ABS_EINVAL, "NULL argument");
+  if (M < 1 || b_cap < 1) return fail(ABS_EINVAL, "M or b_cap out of range");
+  long long mx = 0;
+  std::vector<long long> nx(M);
+  for (int m = 0; m < M; ++m) {
+    nx[m] = res[m].T > b_cur[m] ? res[m].T : b_cur[m];
+    if (nx[m] > mx) mx = nx[m];
+  }
+  for (int m = 0; m < M; ++m) {
+    long long v = sync_max ? mx : nx[m];
+    b_next[m] = (int)(v > b_cap ? b_cap : v);
+  }
+  return ABS_OK;
+}
+
+abs_status abs_average_replicas(abs_ctx *c) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  const Plan &pl = c->pl;
+  HIPCHK(c, launch_average_f32(c->at<float>(pl.o_xm), pl.bf16 ? c->at<bf16_t>(pl.o_xs) : nullptr, pl.M, pl.Ppad, c->stream));
+  return ABS_OK;
+}
+
+abs_status abs_get_params(abs_ctx *c, int m, float *out_host) {
+  if (!c || !out_host) return fail(ABS_EINVAL, "NULL argument");
+  if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
+  std::vector<float> in(c->pl.Ppad);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(in.data(), c->at<float>(c->pl.o_xm) + (size_t)m * c->pl.Ppad, c->pl.Ppad * sizeof(float), hipMemcpyDeviceToHost));
+  to_external(c->pl, c->cfg.has_bias != 0, in.data(), out_host);
+  return ABS_OK;
+}
+
+abs_status abs_get_grad(abs_ctx *c, int m, float *out_host) {
+  if (!c || !out_host) return fail(ABS_EINVAL, "NULL argument");
+  if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
+  if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
+  std::vector<float> in(c->pl.Ppad);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(in.data(), c->at<float>(c->pl.o_grad) + (size_t)m * c->pl.Ppad, c->pl.Ppad * sizeof(float), hipMemcpyDeviceToHost));
+  to_external(c->pl, c->cfg.has_bias != 0, in.data(), out_host);
+  return ABS_OK;
+}
+
+abs_status abs_set_params(abs_ctx *c, int m, const float *in_host) {
+  if (!c || !in_host) return fail(ABS_EINVAL, "NULL argument");
+  if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
+  const Plan &pl = c->pl;
+  std::vector<float> in(pl.Ppad, 0.0f);
+  to_internal(pl, c->cfg.has_bias != 0, in_host, in.data());
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(c->at<float>(pl.o_xm) + (size_t)m * pl.Ppad, in.data(), pl.Ppad * sizeof(float), hipMemcpyHostToDevice));
+  if (pl.bf16) {
+    HIPCHK(c, launch_convert_f32_to_bf16(c->at<float>(pl.o_xm) + (size_t)m * pl.Ppad, c->at<bf16_t>(pl.o_xs) + (size_t)m * pl.Ppad, pl.Ppad, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  return ABS_OK;
+}
+
+abs_status abs_get_per_sample(abs_ctx *c, int m, float *n_host, float *q_host) {
+  if (!c || !n_host) return fail(ABS_EINVAL, "NULL argument");
+  if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
+  if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
+  if (q_host && !c->pl.want_ip) return cfail(c, ABS_ESTATE, "stats_mask lacks ABS_STATS_IP");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(n_host, c->at<float>(c->pl.o_nout) + (size_t)m * c->pl.cap, (size_t)c->last_b * sizeof(float), hipMemcpyDeviceToHost));
+  if (q_host)
+    HIPCHK(c, hipMemcpy(q_host, c->at<float>(c->pl.o_qout) + (size_t)m * c->pl.cap, (size_t)c->last_b * sizeof(float), hipMemcpyDeviceToHost));
+  return ABS_OK;
+}
+
+// ---- statistics and averaging alone ---------------------------------------------------------
+
+static abs_status ls_plan(int L, const int *in_dims, const int *out_dims, int M, int b, std::vector<size_t> &off,
+                          std::vector<long long> &woff, long long &Wtot, size_t &total) {
+  if (L < 1 || L > MAXL || !in_dims || !out_dims) return fail(ABS_EINVAL, "bad layer list");
+  if (M < 1 || b < 2) return fail(ABS_EINVAL, "M < 1 or b < 2");
+  woff.assign(L, 0);
+  Wtot = 0;
+  for (int l = 0; l < L; ++l) {
+    if (in_dims[l] < 8 || out_dims[l] < 8 || (in_dims[l] % 8) || (out_dims[l] % 8))
+      return fail(ABS_EUNSUPPORTED, "layer widths must be multiples of 8");
+    woff[l] = Wtot;
+    Wtot += (long long)in_dims[l] * out_dims[l];
+  }
+  Wtot = rup(Wtot, 256);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = (size_t)rup((long long)(o + bytes), 256); return r; };
+  off.clear();
+  off.push_back(take((size_t)M * Wtot * 4));                 // 0: grad f32
+  off.push_back(take((size_t)M * Wtot * 2));                 // 1: grad bf16
+  off.push_back(take((size_t)M * b * 4 * L));                // 2: an
+  off.push_back(take((size_t)M * b * 4 * L));                // 3: dn
+  off.push_back(take((size_t)M * b * 4));                    // 4: loss (zeros)
+  off.push_back(take((size_t)M * b * 4));                    // 5: n_out
+  off.push_back(take((size_t)M * b * 4));                    // 6: q_out
+  off.push_back(take((size_t)M * 5 * STATS_PBLK * 8));       // 7: partials
+  off.push_back(take((size_t)M * 8 * 8));                    // 8: stats
+  for (int l = 0; l < L; ++l) off.push_back(take((size_t)M * b * 4 * gemm_bf16_ipdot_parts(out_dims[l])));  // 9+l
+  total = o;
+  return ABS_OK;
+}
+
+abs_status abs_layer_stats_workspace_bytes(int L, const int *in_dims, const int *out_dims, int M, int b,
+                                           size_t *bytes) {
+  if (!bytes) return fail(ABS_EINVAL, "bytes is NULL");
+  std::vector<size_t> off; std::vector<long long> woff; long long Wtot; size_t total;
+  abs_status st = ls_plan(L, in_dims, out_dims, M, b, off, woff, Wtot, total);
+  if (st != ABS_OK) return st;
+  *bytes = total;
+  return ABS_OK;
+}
+
+abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M, int b, const void *const *a_dev,
+                           const void *const *delta_dev, void *workspace, size_t workspace_bytes, void *hip_stream,
+                           abs_test_result *out, float *n_out_dev, float *q_out_dev, float *gbar_out_dev) {
+  if (!a_dev || !delta_dev || !workspace || !out) return fail(ABS_EINVAL, "NULL argument");
+  std::vector<size_t> off; std::vector<long long> woff; long long Wtot; size_t total;
+  abs_status st = ls_plan(L, in_dims, out_dims, M, b, off, woff, Wtot, total);
+  if (st != ABS_OK) return st;
+  if (workspace_bytes < total) return fail(ABS_ENOMEM, "workspace too small");
+  if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(ABS_EINVAL, "workspace must be 256-byte aligned");
+  for (int l = 0; l < L; ++l)
+    if (!a_dev[l] || !delta_dev[l] || (reinterpret_cast<uintptr_t>(a_dev[l]) & 15) || (reinterpret_cast<uintptr_t>(delta_dev[l]) & 15))
+      return fail(ABS_EINVAL, "layer pointers must be non-NULL and 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  float *grad = reinterpret_cast<float *>(ws + off[0]);
+  bf16_t *gradbf = reinterpret_cast<bf16_t *>(ws + off[1]);
+  float *an = reinterpret_cast<float *>(ws + off[2]);
+  float *dn = reinterpret_cast<float *>(ws + off[3]);
+  float *loss = reinterpret_cast<float *>(ws + off[4]);
+  abs_ctx *nc = nullptr;
+  HIPCHK(nc, launch_fill_zero(loss, (long long)M * b * 4, s));
+  HIPCHK(nc, launch_fill_zero(grad, (long long)M * Wtot * 4, s));
+  StatsP sp;
+  std::memset(&sp, 0, sizeof(sp));
+  const float inv_b = 1.0f / (float)b;
+  for (int l = 0; l < L; ++l) {
+    const long long sa = (long long)b * in_dims[l], sd = (long long)b * out_dims[l];
+    HIPCHK(nc, launch_row_sqnorm(1, a_dev[l], sa, in_dims[l], in_dims[l], M, b, an + (size_t)l * M * b, b, s));
+    HIPCHK(nc, launch_row_sqnorm(1, delta_dev[l], sd, out_dims[l], out_dims[l], M, b, dn + (size_t)l * M * b, b, s));
+    GemmP p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = delta_dev[l]; p.sAg = sd; p.lda = out_dims[l]; p.a_trans = 1;
+    p.B = a_dev[l]; p.sBg = sa; p.ldb = in_dims[l]; p.b_trans = 1;
+    p.Md = out_dims[l]; p.Nd = in_dims[l]; p.Kd = b; p.groups = M;
+    p.C = grad + woff[l]; p.sCg = Wtot; p.ldc = in_dims[l];
+    p.C2 = gradbf + woff[l]; p.sC2g = Wtot; p.ldc2 = in_dims[l];
+    p.alpha = inv_b;
+    HIPCHK(nc, launch_gemm_bf16(p, EPI_WGRAD, s));
+  }
+  for (int l = 0; l < L; ++l) {
+    const long long sa = (long long)b * in_dims[l], sd = (long long)b * out_dims[l];
+    const int np = gemm_bf16_ipdot_parts(out_dims[l]);
+    GemmP p;
+    std::memset(&p, 0, sizeof(p));
+    p.A = a_dev[l]; p.sAg = sa; p.lda = in_dims[l];
+    p.B = gradbf + woff[l]; p.sBg = Wtot; p.ldb = in_dims[l];
+    p.Md = b; p.Nd = out_dims[l]; p.Kd = in_dims[l]; p.groups = M;
+    p.E = delta_dev[l]; p.sEg = sd; p.lde = out_dims[l];
+    p.part = reinterpret_cast<float *>(ws + off[9 + l]); p.sPartg = (long long)b * np; p.sPartTile = b;
+    HIPCHK(nc, launch_fill_zero(p.part, (long long)M * b * np * 4, s));
+    HIPCHK(nc, launch_gemm_bf16(p, EPI_IPDOT, s));
+    sp.qpart[l] = p.part; sp.nparts[l] = np; sp.sQg[l] = p.sPartg; sp.sQpart[l] = b;
+    sp.an[l] = an + (size_t)l * M * b; sp.dn[l] = dn + (size_t)l * M * b;
+  }
+  sp.L = L; sp.has_bias = 0; sp.groups = M; sp.b = b; sp.want_ip = 1; sp.sNg = b;
+  sp.loss = loss;
+  sp.n_out = n_out_dev ? n_out_dev : reinterpret_cast<float *>(ws + off[5]);
+  sp.q_out = q_out_dev ? q_out_dev : reinterpret_cast<float *>(ws + off[6]);
+  sp.grad = grad; sp.Ppad = Wtot;
+  sp.partials = reinterpret_cast<double *>(ws + off[7]);
+  sp.stats = reinterpret_cast<double *>(ws + off[8]);
+  HIPCHK(nc, launch_stats(sp, s));
+  if (gbar_out_dev) {
+    long long Wsum = 0;
+    for (int l = 0; l < L; ++l) Wsum += (long long)in_dims[l] * out_dims[l];
+    for (int m = 0; m < M; ++m)
+      HIPCHK(nc, hipMemcpyAsync(gbar_out_dev + (size_t)m * Wsum, grad + (size_t)m * Wtot, Wsum * sizeof(float), hipMemcpyDeviceToDevice, s));
+  }
+  std::vector<double> h((size_t)M * 8);
+  HIPCHK(nc, hipMemcpyAsync(h.data(), sp.stats, h.size() * sizeof(double), hipMemcpyDeviceToHost, s));
+  HIPCHK(nc, hipStreamSynchronize(s));
+  for (int m = 0; m < M; ++m) {
+    abs_test_result r;
+    fill_result(r, b, h.data() + (size_t)m * 8);
+    r.var = (r.sum_sq - (double)b * r.gbar_sq) / (double)(b - 1);
+    out[m] = r;
+  }
+  return ABS_OK;
+}
+
+abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *hip_stream) {
+  if (!params_dev) return fail(ABS_EINVAL, "params_dev is NULL");
+  if (M < 1 || n < 8 || (n % 8)) return fail(ABS_EINVAL, "M < 1 or n not a positive multiple of 8");
+  if (reinterpret_cast<uintptr_t>(params_dev) & 15) return fail(ABS_EINVAL, "params_dev must be 16-byte aligned");
+  abs_ctx *nc = nullptr;
+  HIPCHK(nc, launch_average_bf16(static_cast<bf16_t *>(params_dev), M, n, static_cast<hipStream_t>(hip_stream)));
+  return ABS_OK;
+}
+
+}  // extern "C"

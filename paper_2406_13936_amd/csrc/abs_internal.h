@@ -1,0 +1,101 @@
+// Internal declarations shared by the translation units of the library
+// (host launchers only; kernels stay private to their .hip file).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace absk {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits in memory
+
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+enum { OPT_SGD = 0, OPT_SHB = 1, OPT_ADAMW = 2 };
+
+// Epilogues of the grouped GEMM  C[g][m][n] = sum_k A[g][m][k] * B[g][n][k].
+enum {
+  EPI_FWD_ACT = 0,  // C = bf16/f32 phi(acc + bias[n]); C2 = phi'(acc + bias[n]) if C2 != null
+  EPI_LOGITS = 1,   // C(f32) = acc + bias[n]
+  EPI_BWD = 2,      // C = acc * E[m][n]   (act == RELU: E > 0 ? 1 : 0 ; GELU: E itself)
+  EPI_WGRAD = 3,    // C(f32) = alpha * acc ; C2(bf16) = same, rounded, if C2 != null
+  EPI_IPDOT = 4     // part[tile_n][m] = sum_{n in tile} E[m][n] * (acc + bias[n])
+};
+
+struct GemmP {
+  const void *A, *B;           // operands (bf16 bits or float, by kernel family)
+  long long sAg, sBg;          // group (replica) strides in elements
+  int lda, ldb;                // leading dimensions in elements
+  int a_trans, b_trans;        // 0: memory is [row][k] (k contiguous); 1: memory is [k][row]
+  int Md, Nd, Kd, groups;
+  void *C;  long long sCg;  int ldc;     // main output
+  void *C2; long long sC2g; int ldc2;    // optional second output
+  const float *bias; long long sBiasg;   // per-column vector (may be null)
+  const void *E; long long sEg; int lde; // elementwise operand of the epilogue
+  float *part; long long sPartg; long long sPartTile; // row partials: part[g][tile_n][m]
+  float alpha;
+  int act;
+  int pad_to_ld;               // also write zeros to columns [Nd, ldc) of C (and C2)
+};
+
+// bf16 MFMA family (gemm_bf16.hip).  Returns the number of column partials that
+// EPI_IPDOT writes per row (tiles along n) for the tile shape it picks.
+hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s);
+int gemm_bf16_ipdot_parts(int Nd);
+// fp32 SIMT family (gemm_f32.hip); EPI_IPDOT is not offered (U is materialised instead).
+hipError_t launch_gemm_f32(const GemmP &p, int epi, hipStream_t s);
+
+// ---- elementwise.hip -------------------------------------------------------
+// T = activation element type: 0 float, 1 bf16
+hipError_t launch_convert_f32_to_bf16(const float *src, bf16_t *dst, long long n, hipStream_t s);
+// A0[g][i][:] = X[idx[g][i]][:]  and  an0[g][i] = ||row||^2
+hipError_t launch_gather_rows(int is_bf16, const void *X, int d, int N, const int32_t *idx, int groups,
+                              int b, void *A0, long long sA0g, int ldo, float *an0, long long sNg,
+                              hipStream_t s);
+// softmax cross-entropy head: delta = p - e_y (stored in T, pad columns zeroed),
+// dn[g][i] = ||stored delta_i||^2, loss[g][i] = f_i
+hipError_t launch_softmax_ce(int is_bf16, const float *Z, long long sZg, int ldz, int K,
+                             const int32_t *y, int N, const int32_t *idx, int groups, int b,
+                             void *D, long long sDg, int ldd, float *dn, float *loss,
+                             long long sNg, hipStream_t s);
+// out[g][i] = sum_j X[g][i][j]^2
+hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, int cols,
+                             int groups, int b, float *out, long long sOg, hipStream_t s);
+// out[g][j] = alpha * sum_i X[g][i][j]   (bias gradients)
+hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups,
+                          int b, float alpha, float *out, long long sOg, hipStream_t s);
+// q[g][i] += sum_j D[g][i][j] * U[g][i][j]  (fp32 path of the inner products)
+hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U,
+                             long long sUg, int ldu, int cols, int groups, int b, float *q,
+                             long long sQg, int accumulate, hipStream_t s);
+
+struct StatsP {
+  int L, has_bias, groups, b, want_ip;
+  const float *an[16];      // [g][i] layer-input squared norms, stride sNg
+  const float *dn[16];      // [g][i] backprop-signal squared norms
+  long long sNg;
+  const float *qpart[16];   // per layer: [g][part][i]
+  int nparts[16];
+  long long sQg[16], sQpart[16];
+  const float *loss;        // [g][i]
+  float *n_out, *q_out;     // [g][i] (stride sNg)
+  const float *grad;        // [g][Ppad]
+  long long Ppad;
+  double *partials;         // scratch: [groups][5][PBLK]
+  double *stats;            // out: [groups][8] = S1, S2, S3, S4, loss, 0,0,0
+};
+enum { STATS_PBLK = 256 };
+hipError_t launch_stats(const StatsP &p, hipStream_t s);
+
+struct UpdateP {
+  float *x; const float *g; float *v; float *m; bf16_t *shadow;
+  long long n;              // total elements (groups * Ppad)
+  int opt; float lr, momentum, beta1, beta2, eps, wd, c1, c2;  // c = 1/(1-beta^t)
+};
+hipError_t launch_update(const UpdateP &p, hipStream_t s);
+hipError_t launch_average_f32(float *x, bf16_t *shadow, int groups, long long Ppad, hipStream_t s);
+hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s);
+// cross-worker statistics: out[0] = sum_m ||g^m||^2, out[1] = ||mean_m g^m||^2
+hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials,
+                               double *out, hipStream_t s);
+hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);
+
+}  // namespace absk

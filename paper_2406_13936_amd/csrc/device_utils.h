@@ -1,0 +1,85 @@
+// Small device helpers shared by the kernel files (conversions, activations,
+// wavefront reductions).  gfx950 only: wavefronts are 64 lanes wide.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "abs_internal.h"
+
+namespace absk {
+
+__device__ __forceinline__ float bf2f(bf16_t h) {
+  return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+// float -> bfloat16, round to nearest even (the hardware conversion of gfx950)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  __bf16 b = static_cast<__bf16>(f);
+  return __builtin_bit_cast(uint16_t, b);
+}
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+  return static_cast<uint32_t>(f2bf(lo)) | (static_cast<uint32_t>(f2bf(hi)) << 16);
+}
+
+template <class T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float ld(const float *p) { return *p; }
+  static __device__ __forceinline__ void st(float *p, float v) { *p = v; }
+  static __device__ __forceinline__ float rnd(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float ld(const bf16_t *p) { return bf2f(*p); }
+  static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f2bf(v); }
+  static __device__ __forceinline__ float rnd(float v) { return bf2f(f2bf(v)); }
+};
+
+// Exact-form GELU phi(z) = z Phi(z) and its derivative Phi(z) + z pdf(z).
+// Phi comes from the rational-times-exponential erfc approximation of Abramowitz & Stegun
+// 7.1.26 (absolute error of erf below 1.5e-7, i.e. fp32 rounding level); it shares its single
+// exponential with the density, so value and derivative cost one v_exp and one v_rcp.
+__device__ __forceinline__ void gelu_fwd(float z, float &a, float &d) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+  const float e = __expf(-x * x);                       // = exp(-z^2/2)
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  const float half_erfc = 0.5f * poly * t * e;          // 0.5 erfc(|z|/sqrt 2)
+  const float cdf = z >= 0.0f ? 1.0f - half_erfc : half_erfc;
+  a = z * cdf;
+  d = fmaf(z * 0.39894228040143268f, e, cdf);
+}
+
+template <int ACT>
+__device__ __forceinline__ void act_fwd(float z, float &a, float &d) {
+  if (ACT == ACT_RELU) { a = z > 0.0f ? z : 0.0f; d = z > 0.0f ? 1.0f : 0.0f; }
+  else if (ACT == ACT_GELU) { gelu_fwd(z, a, d); }
+  else { a = z; d = 1.0f; }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// Sum over a block of NW wavefronts in a fixed order; result valid in thread 0.
+template <int NW>
+__device__ __forceinline__ double block_sum(double v, double *smem /*NW doubles*/) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) smem[w] = v;
+  __syncthreads();
+  double r = 0.0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < NW; ++i) r += smem[i];
+  }
+  __syncthreads();
+  return r;
+}
+
+}  // namespace absk

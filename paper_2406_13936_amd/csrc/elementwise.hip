@@ -1,0 +1,499 @@
+// Bandwidth-bound kernels of the local step: batch gather, softmax cross-entropy head,
+// row / column reductions, the test statistics, the fused optimizer update, the replica
+// average.  All reductions run in a fixed order (no floating-point atomics), so a step is
+// bit-reproducible.  Wavefronts are 64 lanes; rows are read with 16-byte loads.
+#include "abs_internal.h"
+#include "device_utils.h"
+
+namespace absk {
+namespace {
+
+template <class T> struct Vec;                      // 16-byte vector of T
+template <> struct Vec<float> {
+  enum { N = 4 };
+  static __device__ __forceinline__ void load(const float *p, float (&o)[4]) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  }
+};
+template <> struct Vec<bf16_t> {
+  enum { N = 8 };
+  static __device__ __forceinline__ void load(const bf16_t *p, float (&o)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = __uint_as_float(w[i] << 16);
+      o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+
+__global__ void convert_kernel(const float *__restrict__ src, bf16_t *__restrict__ dst, long long n) {
+  long long i = (blockIdx.x * (long long)blockDim.x + threadIdx.x) * 4;
+  const long long stride = (long long)gridDim.x * blockDim.x * 4;
+  for (; i + 3 < n; i += stride) {
+    const float4 v = *reinterpret_cast<const float4 *>(src + i);
+    uint2 o;
+    o.x = pack2bf(v.x, v.y);
+    o.y = pack2bf(v.z, v.w);
+    *reinterpret_cast<uint2 *>(dst + i) = o;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0)
+    for (long long j = n & ~3LL; j < n; ++j) dst[j] = f2bf(src[j]);
+}
+
+// One wavefront per gathered row.  Source rows have d elements (row stride d); the
+// destination row stride is ldo >= d (multiple of 8), pad columns are written as zeros.
+// Indices outside [0, N) are clamped into the range (the kernels never read out of bounds).
+template <class T>
+__global__ void gather_kernel(const T *__restrict__ X, int d, int N, const int32_t *__restrict__ idx, int b,
+                              T *__restrict__ A0, long long sAg, int ldo, float *__restrict__ an0,
+                              long long sNg) {
+  const int g = blockIdx.y;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= b) return;
+  const int lane = threadIdx.x & 63;
+  const int32_t id = min(max(idx[(long long)g * b + i], 0), N - 1);
+  const long long src = (long long)id * d;
+  T *dst = A0 + (long long)g * sAg + (long long)i * ldo;
+  float s = 0.0f;
+  constexpr int V = Vec<T>::N;
+  if ((d % V) == 0) {
+    for (int c = lane * V; c < d; c += 64 * V) {
+      const uint4 raw = *reinterpret_cast<const uint4 *>(X + src + c);
+      float f[V];
+      Vec<T>::load(X + src + c, f);
+#pragma unroll
+      for (int k = 0; k < V; ++k) s = fmaf(f[k], f[k], s);
+      *reinterpret_cast<uint4 *>(dst + c) = raw;
+    }
+  } else {
+    for (int c = lane; c < d; c += 64) {
+      const T raw = X[src + c];
+      const float f = Elem<T>::ld(&raw);
+      s = fmaf(f, f, s);
+      dst[c] = raw;
+    }
+  }
+  for (int c = d + lane; c < ldo; c += 64) Elem<T>::st(dst + c, 0.0f);
+  s = wave_sum(s);
+  if (lane == 0) an0[(long long)g * sNg + i] = s;
+}
+
+// One wavefront per row of logits.
+template <class T>
+__global__ void softmax_ce_kernel(const float *__restrict__ Z, long long sZg, int ldz, int K,
+                                  const int32_t *__restrict__ y, int N, const int32_t *__restrict__ idx,
+                                  int b, T *__restrict__ D, long long sDg, int ldd,
+                                  float *__restrict__ dn, float *__restrict__ loss, long long sNg) {
+  const int g = blockIdx.y;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= b) return;
+  const int lane = threadIdx.x & 63;
+  const float *z = Z + (long long)g * sZg + (long long)i * ldz;
+  const int label = min(max(y[min(max(idx[(long long)g * b + i], 0), N - 1)], 0), K - 1);
+  float mx = -INFINITY;
+  for (int c = lane; c < K; c += 64) mx = fmaxf(mx, z[c]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  float se = 0.0f;
+  for (int c = lane; c < K; c += 64) se += expf(z[c] - mx);
+  se = wave_sum(se);
+  const float inv = 1.0f / se;
+  T *drow = D + (long long)g * sDg + (long long)i * ldd;
+  float sq = 0.0f;
+  for (int c = lane; c < ldd; c += 64) {
+    float dv = 0.0f;
+    if (c < K) dv = expf(z[c] - mx) * inv - (c == label ? 1.0f : 0.0f);
+    const float st = Elem<T>::rnd(dv);
+    Elem<T>::st(drow + c, dv);
+    sq = fmaf(st, st, sq);
+  }
+  sq = wave_sum(sq);
+  if (lane == 0) {
+    dn[(long long)g * sNg + i] = sq;
+    loss[(long long)g * sNg + i] = -(z[label] - mx - logf(se));
+  }
+}
+
+template <class T>
+__global__ void row_sqnorm_kernel(const T *__restrict__ X, long long sXg, int ld, int cols, int b,
+                                  float *__restrict__ out, long long sOg) {
+  const int g = blockIdx.y;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= b) return;
+  const int lane = threadIdx.x & 63;
+  const T *row = X + (long long)g * sXg + (long long)i * ld;
+  constexpr int V = Vec<T>::N;
+  float s = 0.0f;
+  const int cv = cols / V * V;
+  for (int c = lane * V; c < cv; c += 64 * V) {
+    float f[V];
+    Vec<T>::load(row + c, f);
+#pragma unroll
+    for (int k = 0; k < V; ++k) s = fmaf(f[k], f[k], s);
+  }
+  for (int c = cv + lane; c < cols; c += 64) {
+    const float f = Elem<T>::ld(row + c);
+    s = fmaf(f, f, s);
+  }
+  s = wave_sum(s);
+  if (lane == 0) out[(long long)g * sOg + i] = s;
+}
+
+// 64 columns x 4 row-lanes per block; each row-lane strides over the rows, the four
+// partial sums are added in a fixed order.
+template <class T>
+__global__ void col_sum_kernel(const T *__restrict__ X, long long sXg, int ld, int cols, int b,
+                               float alpha, float *__restrict__ out, long long sOg) {
+  __shared__ float red[4][64];
+  const int g = blockIdx.y;
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  float s = 0.0f;
+  if (c < cols) {
+    const T *p = X + (long long)g * sXg + c;
+    for (int i = rl; i < b; i += 4) s += Elem<T>::ld(p + (long long)i * ld);
+  }
+  red[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && c < cols)
+    out[(long long)g * sOg + c] = alpha * (((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
+}
+
+__global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, int ldd,
+                                  const float *__restrict__ U, long long sUg, int ldu, int cols,
+                                  int b, float *__restrict__ q, long long sQg, int accumulate) {
+  const int g = blockIdx.y;
+  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (i >= b) return;
+  const int lane = threadIdx.x & 63;
+  const float *d = D + (long long)g * sDg + (long long)i * ldd;
+  const float *u = U + (long long)g * sUg + (long long)i * ldu;
+  float s = 0.0f;
+  for (int c = lane; c < cols; c += 64) s = fmaf(d[c], u[c], s);
+  s = wave_sum(s);
+  if (lane == 0) {
+    float *o = q + (long long)g * sQg + i;
+    *o = accumulate ? *o + s : s;
+  }
+}
+
+// ---- statistics ---------------------------------------------------------------------------
+// Stage 1a (grid: PBLK x groups): per-sample squared gradient norms
+//   n_i = sum_l ||delta_i^l||^2 (||a_i^{l-1}||^2 + [bias])   and   q_i = sum_l sum_parts ...
+// with block partial sums of n_i, q_i, q_i^2 and the loss, in double.
+__global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p) {
+  __shared__ double red[4];
+  const int g = blockIdx.y;
+  double s1 = 0.0, s3 = 0.0, s4 = 0.0, sl = 0.0;
+  const float hb = p.has_bias ? 1.0f : 0.0f;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < p.b; i += 256 * STATS_PBLK) {
+    const long long o = (long long)g * p.sNg + i;
+    float n = 0.0f;
+    for (int l = 0; l < p.L; ++l) n = fmaf(p.dn[l][o], p.an[l][o] + hb, n);
+    if (p.n_out) p.n_out[o] = n;
+    s1 += (double)n;
+    sl += (double)p.loss[o];
+    if (p.want_ip) {
+      float q = 0.0f;
+      for (int l = 0; l < p.L; ++l) {
+        const float *qp = p.qpart[l] + (long long)g * p.sQg[l] + i;
+        for (int k = 0; k < p.nparts[l]; ++k) q += qp[(long long)k * p.sQpart[l]];
+      }
+      if (p.q_out) p.q_out[o] = q;
+      s4 += (double)q;
+      s3 += (double)q * (double)q;
+    }
+  }
+  double *out = p.partials + ((long long)g * 5) * STATS_PBLK + blockIdx.x;
+  double r;
+  r = block_sum<4>(s1, red); if (threadIdx.x == 0) out[0 * STATS_PBLK] = r;
+  r = block_sum<4>(s3, red); if (threadIdx.x == 0) out[2 * STATS_PBLK] = r;
+  r = block_sum<4>(s4, red); if (threadIdx.x == 0) out[3 * STATS_PBLK] = r;
+  r = block_sum<4>(sl, red); if (threadIdx.x == 0) out[4 * STATS_PBLK] = r;
+}
+
+// Stage 1b (grid: PBLK x groups): ||gbar||^2 over the padded gradient vector.
+__global__ void __launch_bounds__(256) stats_gradsq_kernel(const float *__restrict__ grad, long long Ppad,
+                                                           double *__restrict__ partials) {
+  __shared__ double red[4];
+  const int g = blockIdx.y;
+  const float4 *p4 = reinterpret_cast<const float4 *>(grad + (long long)g * Ppad);
+  const long long n4 = Ppad / 4;
+  double s = 0.0;
+  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n4; i += 256LL * STATS_PBLK) {
+    const float4 v = p4[i];
+    const float t = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, v.w * v.w)));
+    s += (double)t;
+  }
+  const double r = block_sum<4>(s, red);
+  if (threadIdx.x == 0) partials[((long long)g * 5 + 1) * STATS_PBLK + blockIdx.x] = r;
+}
+
+// Stage 2 (grid: groups): add the PBLK partials of each of the five sums in index order.
+__global__ void __launch_bounds__(256) stats_final_kernel(const double *__restrict__ partials,
+                                                          double *__restrict__ stats) {
+  __shared__ double red[4];
+  const int g = blockIdx.x;
+  static_assert(STATS_PBLK == 256, "one partial per thread");
+  for (int k = 0; k < 5; ++k) {
+    const double v = partials[((long long)g * 5 + k) * STATS_PBLK + threadIdx.x];
+    const double r = block_sum<4>(v, red);
+    if (threadIdx.x == 0) stats[g * 8 + k] = r;
+  }
+}
+
+// ---- optimizer update ------------------------------------------------------------------------
+template <int OPT, bool SHADOW>
+__global__ void __launch_bounds__(256) update_kernel(const UpdateP p) {
+  const long long n4 = p.n / 4;
+  const long long stride = (long long)gridDim.x * 256;
+  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n4; i += stride) {
+    float4 x = reinterpret_cast<float4 *>(p.x)[i];
+    const float4 g = reinterpret_cast<const float4 *>(p.g)[i];
+    float xs[4] = {x.x, x.y, x.z, x.w};
+    const float gs[4] = {g.x, g.y, g.z, g.w};
+    if (OPT == OPT_SGD) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) xs[k] = fmaf(-p.lr, gs[k], xs[k]);
+    } else if (OPT == OPT_SHB) {
+      float4 v = reinterpret_cast<float4 *>(p.v)[i];
+      float vs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        vs[k] = fmaf(p.momentum, vs[k], gs[k]);
+        xs[k] = fmaf(-p.lr, vs[k], xs[k]);
+      }
+      reinterpret_cast<float4 *>(p.v)[i] = make_float4(vs[0], vs[1], vs[2], vs[3]);
+    } else {
+      float4 v = reinterpret_cast<float4 *>(p.v)[i];
+      float4 m = reinterpret_cast<float4 *>(p.m)[i];
+      float vs[4] = {v.x, v.y, v.z, v.w}, ms[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        ms[k] = fmaf(p.beta1, ms[k], (1.0f - p.beta1) * gs[k]);
+        vs[k] = fmaf(p.beta2, vs[k], (1.0f - p.beta2) * gs[k] * gs[k]);
+        const float mhat = ms[k] * p.c1, vhat = vs[k] * p.c2;
+        xs[k] = xs[k] * (1.0f - p.lr * p.wd) - p.lr * mhat / (sqrtf(vhat) + p.eps);
+      }
+      reinterpret_cast<float4 *>(p.v)[i] = make_float4(vs[0], vs[1], vs[2], vs[3]);
+      reinterpret_cast<float4 *>(p.m)[i] = make_float4(ms[0], ms[1], ms[2], ms[3]);
+    }
+    reinterpret_cast<float4 *>(p.x)[i] = make_float4(xs[0], xs[1], xs[2], xs[3]);
+    if (SHADOW) {
+      uint2 o;
+      o.x = pack2bf(xs[0], xs[1]);
+      o.y = pack2bf(xs[2], xs[3]);
+      reinterpret_cast<uint2 *>(p.shadow)[i] = o;
+    }
+  }
+}
+
+// ---- replica average ------------------------------------------------------------------------
+// Thread owns 4 consecutive parameters: reads them from all replicas (in replica order), divides
+// once, writes the mean back to every replica (and the bf16 shadow if there is one).
+template <bool SHADOW>
+__global__ void __launch_bounds__(256) average_f32_kernel(float *__restrict__ x, bf16_t *__restrict__ shadow,
+                                                          int groups, long long Ppad) {
+  const long long n4 = Ppad / 4;
+  const long long stride = (long long)gridDim.x * 256;
+  const float Mf = (float)groups;
+  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n4; i += stride) {
+    float4 s = reinterpret_cast<const float4 *>(x)[i];
+    for (int g = 1; g < groups; ++g) {
+      const float4 v = reinterpret_cast<const float4 *>(x + (long long)g * Ppad)[i];
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    s.x /= Mf; s.y /= Mf; s.z /= Mf; s.w /= Mf;
+    uint2 o;
+    if (SHADOW) { o.x = pack2bf(s.x, s.y); o.y = pack2bf(s.z, s.w); }
+    for (int g = 0; g < groups; ++g) {
+      reinterpret_cast<float4 *>(x + (long long)g * Ppad)[i] = s;
+      if (SHADOW) reinterpret_cast<uint2 *>(shadow + (long long)g * Ppad)[i] = o;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) average_bf16_kernel(bf16_t *__restrict__ x, int groups, long long n) {
+  const long long n8 = n / 8;
+  const long long stride = (long long)gridDim.x * 256;
+  const float Mf = (float)groups;
+  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n8; i += stride) {
+    float s[8];
+    Vec<bf16_t>::load(x + i * 8, s);
+    for (int g = 1; g < groups; ++g) {
+      float v[8];
+      Vec<bf16_t>::load(x + (long long)g * n + i * 8, v);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s[k] += v[k];
+    }
+    uint4 o;
+    o.x = pack2bf(s[0] / Mf, s[1] / Mf);
+    o.y = pack2bf(s[2] / Mf, s[3] / Mf);
+    o.z = pack2bf(s[4] / Mf, s[5] / Mf);
+    o.w = pack2bf(s[6] / Mf, s[7] / Mf);
+    for (int g = 0; g < groups; ++g) *reinterpret_cast<uint4 *>(x + (long long)g * n + i * 8) = o;
+  }
+}
+
+// sum_m ||g^m||^2 and ||mean_m g^m||^2 over the padded gradient block (Alg. 2 statistics)
+__global__ void __launch_bounds__(256) cross_worker_kernel(const float *__restrict__ grad, int groups,
+                                                           long long Ppad, double *__restrict__ partials) {
+  __shared__ double red[4];
+  double ss = 0.0, sm = 0.0;
+  const double invM = 1.0 / (double)groups;
+  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < Ppad; i += 256LL * STATS_PBLK) {
+    double s = 0.0;
+    for (int g = 0; g < groups; ++g) {
+      const double v = (double)grad[(long long)g * Ppad + i];
+      s += v;
+      ss += v * v;
+    }
+    s *= invM;
+    sm += s * s;
+  }
+  double r = block_sum<4>(ss, red);
+  if (threadIdx.x == 0) partials[blockIdx.x] = r;
+  r = block_sum<4>(sm, red);
+  if (threadIdx.x == 0) partials[STATS_PBLK + blockIdx.x] = r;
+}
+__global__ void __launch_bounds__(256) cross_worker_final_kernel(const double *__restrict__ partials,
+                                                                 double *__restrict__ out) {
+  __shared__ double red[4];
+  for (int k = 0; k < 2; ++k) {
+    const double r = block_sum<4>(partials[k * STATS_PBLK + threadIdx.x], red);
+    if (threadIdx.x == 0) out[k] = r;
+  }
+}
+
+__global__ void fill_zero_kernel(uint4 *p, long long n16) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n16; i += stride)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
+inline int grid_for(long long work_items, int per_block, int max_blocks) {
+  long long b = (work_items + per_block - 1) / per_block;
+  if (b < 1) b = 1;
+  if (b > max_blocks) b = max_blocks;
+  return (int)b;
+}
+
+}  // namespace
+
+hipError_t launch_convert_f32_to_bf16(const float *src, bf16_t *dst, long long n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(convert_kernel, dim3(grid_for(n / 4, 256, 8192)), dim3(256), 0, s, src, dst, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(int is_bf16, const void *X, int d, int N, const int32_t *idx, int groups, int b,
+                              void *A0, long long sA0g, int ldo, float *an0, long long sNg, hipStream_t s) {
+  const dim3 grid((b + 3) / 4, groups), blk(256);
+  if (is_bf16)
+    hipLaunchKernelGGL(gather_kernel<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), d, N, idx, b,
+                       static_cast<bf16_t *>(A0), sA0g, ldo, an0, sNg);
+  else
+    hipLaunchKernelGGL(gather_kernel<float>, grid, blk, 0, s, static_cast<const float *>(X), d, N, idx, b,
+                       static_cast<float *>(A0), sA0g, ldo, an0, sNg);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_ce(int is_bf16, const float *Z, long long sZg, int ldz, int K, const int32_t *y,
+                             int N, const int32_t *idx, int groups, int b, void *D, long long sDg, int ldd,
+                             float *dn, float *loss, long long sNg, hipStream_t s) {
+  const dim3 grid((b + 3) / 4, groups), blk(256);
+  if (is_bf16)
+    hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, b,
+                       static_cast<bf16_t *>(D), sDg, ldd, dn, loss, sNg);
+  else
+    hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, b,
+                       static_cast<float *>(D), sDg, ldd, dn, loss, sNg);
+  return hipGetLastError();
+}
+
+hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
+                             float *out, long long sOg, hipStream_t s) {
+  const dim3 grid((b + 3) / 4, groups), blk(256);
+  if (is_bf16)
+    hipLaunchKernelGGL(row_sqnorm_kernel<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld,
+                       cols, b, out, sOg);
+  else
+    hipLaunchKernelGGL(row_sqnorm_kernel<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld,
+                       cols, b, out, sOg);
+  return hipGetLastError();
+}
+
+hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
+                          float alpha, float *out, long long sOg, hipStream_t s) {
+  const dim3 grid((cols + 63) / 64, groups), blk(256);
+  if (is_bf16)
+    hipLaunchKernelGGL(col_sum_kernel<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols,
+                       b, alpha, out, sOg);
+  else
+    hipLaunchKernelGGL(col_sum_kernel<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols,
+                       b, alpha, out, sOg);
+  return hipGetLastError();
+}
+
+hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U, long long sUg, int ldu,
+                             int cols, int groups, int b, float *q, long long sQg, int accumulate,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(rowdot_f32_kernel, dim3((b + 3) / 4, groups), dim3(256), 0, s, D, sDg, ldd, U, sUg, ldu,
+                     cols, b, q, sQg, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_stats(const StatsP &p, hipStream_t s) {
+  hipLaunchKernelGGL(stats_samples_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p);
+  if (p.grad)
+    hipLaunchKernelGGL(stats_gradsq_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.grad, p.Ppad,
+                       p.partials);
+  hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_update(const UpdateP &p, hipStream_t s) {
+  const dim3 grid(grid_for(p.n / 4, 256 * 4, 1 << 20)), blk(256);
+  const bool sh = p.shadow != nullptr;
+#define ABS_UPD(O)                                                                  \
+  do {                                                                              \
+    if (sh) hipLaunchKernelGGL((update_kernel<O, true>), grid, blk, 0, s, p);       \
+    else hipLaunchKernelGGL((update_kernel<O, false>), grid, blk, 0, s, p);         \
+  } while (0)
+  if (p.opt == OPT_SGD) ABS_UPD(OPT_SGD);
+  else if (p.opt == OPT_SHB) ABS_UPD(OPT_SHB);
+  else ABS_UPD(OPT_ADAMW);
+#undef ABS_UPD
+  return hipGetLastError();
+}
+
+hipError_t launch_average_f32(float *x, bf16_t *shadow, int groups, long long Ppad, hipStream_t s) {
+  const dim3 grid(grid_for(Ppad / 4, 256, 1 << 20)), blk(256);
+  if (shadow) hipLaunchKernelGGL(average_f32_kernel<true>, grid, blk, 0, s, x, shadow, groups, Ppad);
+  else hipLaunchKernelGGL(average_f32_kernel<false>, grid, blk, 0, s, x, shadow, groups, Ppad);
+  return hipGetLastError();
+}
+
+hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s) {
+  hipLaunchKernelGGL(average_bf16_kernel, dim3(grid_for(n / 8, 256, 1 << 20)), dim3(256), 0, s, x, groups, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials, double *out,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(cross_worker_kernel, dim3(STATS_PBLK), dim3(256), 0, s, g, groups, Ppad, partials);
+  hipLaunchKernelGGL(cross_worker_final_kernel, dim3(1), dim3(256), 0, s, partials, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s) {
+  if (bytes <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(bytes / 16, 256, 4096)), dim3(256), 0, s,
+                     static_cast<uint4 *>(p), bytes / 16);
+  return hipGetLastError();
+}
+
+}  // namespace absk

@@ -1,0 +1,126 @@
+// Replica-batched fp32 GEMM (plain vector ALU, LDS-tiled) for the fp32 precision mode:
+//   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k]
+// with the same operand-layout flags and epilogues as the bf16 matrix-core family.  The fp32
+// mode serves small, latency-bound problems (logistic regression), so this kernel favours
+// generality (arbitrary strides and extents) over peak rate: 64x64 block tile, k-step 16,
+// 256 threads, 4x4 outputs per thread.
+#include "abs_internal.h"
+#include "device_utils.h"
+
+namespace absk {
+namespace {
+
+template <int EPI, int ACT>
+__global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP p) {
+  __shared__ float As[16][68];
+  __shared__ float Bs[16][68];
+  const int g = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const float *A = static_cast<const float *>(p.A) + (long long)g * p.sAg;
+  const float *B = static_cast<const float *>(p.B) + (long long)g * p.sBg;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
+
+  for (int k0 = 0; k0 < p.Kd; k0 += 16) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int id = tid + e * 256;
+      int kk, rr;
+      if (!p.a_trans) { kk = id & 15; rr = id >> 4; } else { rr = id & 63; kk = id >> 6; }
+      const int m = m0 + rr, k = k0 + kk;
+      float v = 0.0f;
+      if (m < p.Md && k < p.Kd) v = p.a_trans ? A[(long long)k * p.lda + m] : A[(long long)m * p.lda + k];
+      As[kk][rr] = v;
+      if (!p.b_trans) { kk = id & 15; rr = id >> 4; } else { rr = id & 63; kk = id >> 6; }
+      const int n = n0 + rr, kb = k0 + kk;
+      v = 0.0f;
+      if (n < p.Nd && kb < p.Kd) v = p.b_trans ? B[(long long)kb * p.ldb + n] : B[(long long)n * p.ldb + kb];
+      Bs[kk][rr] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+
+  const float *bias = p.bias ? p.bias + (long long)g * p.sBiasg : nullptr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= p.Md) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      const bool nin = n < p.Nd;
+      const float v = acc[i][j];
+      const float bv = (bias && nin) ? bias[n] : 0.0f;
+      if (EPI == EPI_FWD_ACT) {
+        if (n < p.ldc && (nin || p.pad_to_ld)) {
+          float a = 0.0f, d = 0.0f;
+          if (nin) act_fwd<ACT>(v + bv, a, d);
+          static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = a;
+          if (ACT == ACT_GELU && p.C2)
+            static_cast<float *>(p.C2)[(long long)g * p.sC2g + (long long)m * p.ldc2 + n] = d;
+        }
+      } else if (EPI == EPI_LOGITS) {
+        if (nin) static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = v + bv;
+      } else if (EPI == EPI_BWD) {
+        if (n < p.ldc && (nin || p.pad_to_ld)) {
+          float o = 0.0f;
+          if (nin) {
+            float e = 1.0f;
+            if (ACT != ACT_NONE) e = static_cast<const float *>(p.E)[(long long)g * p.sEg + (long long)m * p.lde + n];
+            o = (ACT == ACT_RELU) ? (e > 0.0f ? v : 0.0f) : (ACT == ACT_GELU ? v * e : v);
+          }
+          static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = o;
+        }
+      } else if (EPI == EPI_WGRAD) {
+        if (nin) static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = v * p.alpha;
+      }
+    }
+  }
+}
+
+template <int EPI, int ACT>
+hipError_t launch1(const GemmP &p, hipStream_t s) {
+  const dim3 grid((p.Nd + 63) / 64, (p.Md + 63) / 64, p.groups);
+  if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((gemm_f32_kernel<EPI, ACT>), grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+template <int EPI>
+hipError_t launch_act(const GemmP &p, hipStream_t s) {
+  if constexpr (EPI == EPI_FWD_ACT || EPI == EPI_BWD) {
+    if (p.act == ACT_RELU) return launch1<EPI, ACT_RELU>(p, s);
+    if (p.act == ACT_GELU) return launch1<EPI, ACT_GELU>(p, s);
+  }
+  return launch1<EPI, ACT_NONE>(p, s);
+}
+
+}  // namespace
+
+hipError_t launch_gemm_f32(const GemmP &p, int epi, hipStream_t s) {
+  if (p.Md <= 0 || p.Nd <= 0 || p.groups <= 0) return hipSuccess;
+  switch (epi) {
+    case EPI_FWD_ACT: return launch_act<EPI_FWD_ACT>(p, s);
+    case EPI_LOGITS: return launch_act<EPI_LOGITS>(p, s);
+    case EPI_BWD: return launch_act<EPI_BWD>(p, s);
+    case EPI_WGRAD: return launch_act<EPI_WGRAD>(p, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace absk
