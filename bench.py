@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input: the local
+step of all M replicas (gather, forward, backward, batch gradient, test statistics, optimizer
+update), the batch-size test and rule on the host, and, every H steps, the replica average.
+Inputs (dataset, parameters, index batches) are resident in HBM before the timed region.
+
+Default workload: the MLP 3072-2048-2048-2048-100 / GELU / heavy-ball / inner-product-test
+configuration with M=16 replicas, timed in steady state at the batch cap b=8192 (the shapes
+the matrix-core target is stated on).  `--workload` selects another configuration, `--adaptive`
+times the run from b0 with the batch size growing under the test.
+
+Prints ONE JSON line: throughput in samples/s (all replicas), the roofline record of the
+dominant kernel (per-launch HIP-event timing collected inside the timed region), and the CPU
+oracle's throughput on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4"])
+    ap.add_argument("--adaptive", action="store_true", help="start at b0 and let the test grow b")
+    ap.add_argument("--batch", type=int, default=0, help="fixed local batch size (default: the cap)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    return ap.parse_args()
+
+
+def cpu_baseline(w, X, y, x0, sample_b):
+    """The oracle as it stands, timed on this machine's host cores: one local step of all M
+    replicas (statistics and test included) at local batch size sample_b."""
+    import numpy as np
+    from oracle import abs_oracle as O
+    from paper_2406_13936_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    net = O.Net(w.dims, w.act, w.has_bias)
+    orc = O.Replicas(net, x0, X, y, w.M, opt=w.opt, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2,
+                     eps=w.eps, weight_decay=w.weight_decay, mixed=(w.prec == W.PREC_BF16),
+                     want_ip=(w.test != W.TEST_NORM))
+    idx = W.step_indices(w, 0, 0, sample_b)
+    t0 = time.perf_counter()
+    orc.local_step(idx, w.lr)
+    orc.test(w.test, eta=w.eta, theta=w.theta, nu=w.nu)
+    dt = time.perf_counter() - t0
+    return {"value": w.M * sample_b / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"one local step of all M={w.M} replicas at b={sample_b} incl. statistics and test "
+                      f"({dt:.1f} s, fp64 numpy, bf16 rounding points emulated)"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU; all M worker replicas are batched on it and the "
+              "replica average is an in-device mean (no collective). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2406_13936_amd as A
+    from paper_2406_13936_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(3)
+    w = getattr(W, a.workload)()
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    b_fixed = a.batch or w.b_cap
+
+    def test_and_rule(b):
+        if w.test == W.TEST_NORM:
+            res = rep.norm_test(w.eta)
+        else:
+            res = rep.inner_product_test(w.theta, w.nu if w.test == W.TEST_AUG_IP else 0.0)
+        return A.next_batch_size(res, [b] * w.M, w.b_cap, True)[0]
+
+    # pre-stage every index batch in HBM
+    total = a.warmup + a.steps
+    sizes, idx_dev = [], []
+    if not a.adaptive:
+        for s in range(total):
+            k, h = divmod(s, w.H)
+            t, b = rep.upload_indices(W.step_indices(w, k, h, b_fixed))
+            idx_dev.append(t)
+            sizes.append(b)
+    else:
+        # indices for the largest size; row m of step s uses its first b entries per replica
+        for s in range(total):
+            k, h = divmod(s, w.H)
+            idx_dev.append(W.step_indices(w, k, h, w.b_cap))
+    torch.cuda.synchronize()
+
+    def run(s, b):
+        if a.adaptive:
+            t, _ = rep.upload_indices(np.ascontiguousarray(idx_dev[s][:, :b]))
+        else:
+            t = idx_dev[s]
+        rep.local_step_dev(t, b, w.lr)
+        nb = test_and_rule(b)
+        if (s + 1) % w.H == 0:
+            rep.average_replicas()
+        return nb
+
+    b = w.b0 if a.adaptive else b_fixed
+    for s in range(a.warmup):
+        nb = run(s, b)
+        b = nb if a.adaptive else b
+    torch.cuda.synchronize()
+    rep.profile_enable(True)
+    samples = 0
+    sched = []
+    t0 = time.perf_counter()
+    for s in range(a.warmup, total):
+        samples += w.M * b
+        sched.append(b)
+        nb = run(s, b)
+        b = nb if a.adaptive else b
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = rep.profile_read()
+    rep.profile_enable(False)
+
+    # dominant kernel = the matrix-core GEMM class with the largest total time
+    gemms = {k: v for k, v in prof.items() if k.startswith("gemm_")}
+    kernels = {}
+    for k, v in prof.items():
+        e = {"calls": v["calls"], "avg_ms": v["total_ms"] / v["calls"],
+             "share": v["total_ms"] / (dt * 1e3)}
+        if v["flops"] > 0:
+            e["tflops"] = v["flops"] / (v["total_ms"] * 1e-3) / 1e12
+        if v["bytes"] > 0:
+            e["gbs"] = v["bytes"] / (v["total_ms"] * 1e-3) / 1e9
+        kernels[k] = e
+    roof = None
+    if gemms and w.prec == W.PREC_BF16:
+        name = max(gemms, key=lambda k: gemms[k]["total_ms"])
+        v = gemms[name]
+        ach = v["flops"] / (v["total_ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": name, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                "avg_launch_ms": v["total_ms"] / v["calls"], "launches": v["calls"],
+                "flops_per_launch": v["flops"] / v["calls"]}
+        allf = sum(v["flops"] for v in gemms.values())
+        allt = sum(v["total_ms"] for v in gemms.values())
+        roof["all_gemms_tflops"] = allf / (allt * 1e-3) / 1e12
+        roof["all_gemms_frac"] = roof["all_gemms_tflops"] / PEAK_BF16_TFLOPS
+    rep.close()
+
+    out = {
+        "metric": "local-step samples/sec (all replicas, incl. batch test)",
+        "value": samples / dt, "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt * 1e3 / a.steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if w.prec == W.PREC_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "dims": list(w.dims), "M": w.M, "H": w.H,
+                   "local_batch": "adaptive from b0=%d" % w.b0 if a.adaptive else b_fixed,
+                   "schedule": sched if a.adaptive else None,
+                   "optimizer": ["sgd", "shb", "adamw"][w.opt],
+                   "test": ["norm", "inner_product", "augmented_inner_product"][w.test]},
+        "roofline": roof, "kernels": kernels,
+    }
+    if not a.no_cpu_baseline:
+        sb = a.cpu_sample_batch or {"config1": 512, "config2": 512, "config3": 64, "config4": 32}[a.workload]
+        out["cpu_baseline"] = cpu_baseline(w, X, y, x0, min(sb, w.b_cap))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -188,6 +188,22 @@ abs_status abs_layer_stats_workspace_bytes(int L, const int *in_dims, const int 
  * replica order, one rounding):  params_dev : device, bf16 [M x n]; n multiple of 8. */
 abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *hip_stream);
 
+/*
+ * Per-kernel timing (measurement aid; not part of the method).  While enabled, every kernel
+ * launch of abs_local_step / abs_average_replicas is bracketed by two HIP events on the
+ * context's stream.  abs_profile_read synchronises, folds the elapsed times into per-kernel
+ * totals (accumulated since abs_profile_enable) and returns one entry per kernel class that ran:
+ * calls, total milliseconds, and the algorithmic work of those calls (flops for the matrix-core
+ * GEMMs: 2 m n k per replica; bytes for the bandwidth-bound kernels).   out : host.
+ */
+typedef struct {
+  char name[32];
+  long long calls;
+  double total_ms, flops, bytes;
+} abs_profile_entry;
+abs_status abs_profile_enable(abs_ctx *ctx, int on);
+abs_status abs_profile_read(abs_ctx *ctx, int max_entries, abs_profile_entry *out, int *n_entries);
+
 abs_status abs_destroy(abs_ctx *ctx);
 const char *abs_last_error(const abs_ctx *ctx);   /* ctx may be NULL: last error of this thread */
 

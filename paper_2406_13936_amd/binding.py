@@ -24,6 +24,7 @@ EXPORTS = [
     "abs_average_replicas", "abs_get_params", "abs_set_params", "abs_get_grad",
     "abs_get_per_sample", "abs_n_params", "abs_layer_stats",
     "abs_layer_stats_workspace_bytes", "abs_average_bf16", "abs_destroy", "abs_last_error",
+    "abs_profile_enable", "abs_profile_read",
 ]
 
 
@@ -47,6 +48,11 @@ class TestResult(C.Structure):
                 ("var", C.c_double), ("var_perp", C.c_double), ("lhs", C.c_double),
                 ("rhs", C.c_double), ("ratio", C.c_double), ("T", C.c_longlong),
                 ("pass_", C.c_int)]
+
+
+class ProfileEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("calls", C.c_longlong), ("total_ms", C.c_double),
+                ("flops", C.c_double), ("bytes", C.c_double)]
 
 
 def load_library(reload: bool = False):
@@ -87,6 +93,8 @@ def load_library(reload: bool = False):
                                                     C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     lib.abs_average_bf16.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
     lib.abs_destroy.argtypes = [C.c_void_p]
+    lib.abs_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.abs_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(ProfileEntry), C.POINTER(C.c_int)]
     _lib = lib
     return lib
 
@@ -212,6 +220,18 @@ class Replicas:
         _check(self._lib.abs_get_per_sample(self._ctx, int(m), n.ctypes.data,
                                             q.ctypes.data if want_q else None), self._ctx)
         return n, q
+
+    def profile_enable(self, on: bool = True):
+        _check(self._lib.abs_profile_enable(self._ctx, int(bool(on))), self._ctx)
+
+    def profile_read(self):
+        """{kernel class: dict(calls, total_ms, flops, bytes)} accumulated since profile_enable."""
+        buf = (ProfileEntry * 64)()
+        n = C.c_int(0)
+        _check(self._lib.abs_profile_read(self._ctx, 64, buf, C.byref(n)), self._ctx)
+        return {buf[i].name.decode(): dict(calls=buf[i].calls, total_ms=buf[i].total_ms,
+                                           flops=buf[i].flops, bytes=buf[i].bytes)
+                for i in range(n.value)}
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx.value:

@@ -127,7 +127,28 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
 
 }  // namespace
 
+// Event-timed launch classes (abs_profile_*): one entry per kernel symbol of interest.
+enum {
+  T_GATHER = 0, T_SOFTMAX, T_ROWNORM, T_COLSUM, T_STATS, T_UPDATE, T_AVERAGE, T_ROWDOT,
+  T_GEMM0,                       // + epi * 3 + tile shape (bf16) ; fp32 family uses shape 1
+  T_COUNT = T_GEMM0 + 5 * 3
+};
+static const char *const kTagNames[T_COUNT] = {
+  "gather_rows", "softmax_ce", "row_sqnorm", "col_sum", "stats", "update", "average", "rowdot",
+  "gemm_fwd_128x64", "gemm_fwd_128x128", "gemm_fwd_256x256",
+  "gemm_logits_128x64", "gemm_logits_128x128", "gemm_logits_256x256",
+  "gemm_bwd_128x64", "gemm_bwd_128x128", "gemm_bwd_256x256",
+  "gemm_wgrad_128x64", "gemm_wgrad_128x128", "gemm_wgrad_256x256",
+  "gemm_ipdot_128x64", "gemm_ipdot_128x128", "gemm_ipdot_256x256"};
+
+struct ProfRec { int tag; hipEvent_t e0, e1; double flops, bytes; };
+
 struct abs_ctx {
+  bool prof_on = false;
+  std::vector<ProfRec> prof_recs;      // event pool, reused
+  size_t prof_used = 0;
+  double prof_ms[T_COUNT] = {0}, prof_flops[T_COUNT] = {0}, prof_bytes[T_COUNT] = {0};
+  long long prof_calls[T_COUNT] = {0};
   Plan pl;
   abs_config cfg;
   hipStream_t stream = nullptr;
@@ -175,7 +196,26 @@ void to_external(const Plan &pl, bool has_bias, const float *in, float *ext) {
   }
 }
 
-hipError_t gemm(const abs_ctx *c, const GemmP &p, int epi) {
+// Optional event bracket around one launch (profiling on: two hipEventRecord calls).
+struct ProfScope {
+  abs_ctx *c; ProfRec *r = nullptr;
+  ProfScope(abs_ctx *ctx, int tag, double flops, double bytes) : c(ctx) {
+    if (!c->prof_on) return;
+    if (c->prof_used == c->prof_recs.size()) {
+      ProfRec n{};
+      if (hipEventCreate(&n.e0) != hipSuccess || hipEventCreate(&n.e1) != hipSuccess) return;
+      c->prof_recs.push_back(n);
+    }
+    r = &c->prof_recs[c->prof_used++];
+    r->tag = tag; r->flops = flops; r->bytes = bytes;
+    (void)hipEventRecord(r->e0, c->stream);
+  }
+  ~ProfScope() { if (r) (void)hipEventRecord(r->e1, c->stream); }
+};
+
+hipError_t gemm(abs_ctx *c, const GemmP &p, int epi) {
+  const int shape = c->pl.bf16 ? gemm_bf16_tile_shape(p.Md, p.Nd) : 1;
+  ProfScope ps(c, T_GEMM0 + epi * 3 + shape, 2.0 * p.Md * p.Nd * p.Kd * p.groups, 0.0);
   return c->pl.bf16 ? launch_gemm_bf16(p, epi, c->stream) : launch_gemm_f32(p, epi, c->stream);
 }
 
@@ -286,7 +326,41 @@ abs_status abs_destroy(abs_ctx *c) {
   if (!c) return ABS_OK;
   (void)hipStreamSynchronize(c->stream);
   if (c->host_stats) (void)hipHostFree(c->host_stats);
+  for (ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   delete c;
+  return ABS_OK;
+}
+
+abs_status abs_profile_enable(abs_ctx *c, int on) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->prof_on = on != 0;
+  c->prof_used = 0;
+  for (int t = 0; t < T_COUNT; ++t) { c->prof_ms[t] = c->prof_flops[t] = c->prof_bytes[t] = 0.0; c->prof_calls[t] = 0; }
+  return ABS_OK;
+}
+
+abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out, int *n_entries) {
+  if (!c || !out || !n_entries) return fail(ABS_EINVAL, "NULL argument");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (size_t i = 0; i < c->prof_used; ++i) {
+    ProfRec &r = c->prof_recs[i];
+    float ms = 0.0f;
+    HIPCHK(c, hipEventElapsedTime(&ms, r.e0, r.e1));
+    c->prof_ms[r.tag] += ms; c->prof_flops[r.tag] += r.flops; c->prof_bytes[r.tag] += r.bytes;
+    c->prof_calls[r.tag] += 1;
+  }
+  c->prof_used = 0;
+  int n = 0;
+  for (int t = 0; t < T_COUNT && n < max_entries; ++t) {
+    if (!c->prof_calls[t]) continue;
+    abs_profile_entry e;
+    std::memset(&e, 0, sizeof(e));
+    std::strncpy(e.name, kTagNames[t], sizeof(e.name) - 1);
+    e.calls = c->prof_calls[t]; e.total_ms = c->prof_ms[t]; e.flops = c->prof_flops[t]; e.bytes = c->prof_bytes[t];
+    out[n++] = e;
+  }
+  *n_entries = n;
   return ABS_OK;
 }
 
@@ -310,8 +384,9 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
 
   // batch gather (Alg. 1: "sample the local batch")
   const void *Xsrc = pl.bf16 ? static_cast<const void *>(c->at<bf16_t>(pl.o_Xbf)) : static_cast<const void *>(c->X);
+  { ProfScope ps_(c, T_GATHER, 0.0, 2.0 * M * b * pl.dims[0] * pl.esz);
   HIPCHK(c, launch_gather_rows(isb, Xsrc, pl.dims[0], (int)c->N, idx_dev, M, b, act_ptr(pl.o_A[0]), cap * pl.ld[0],
-                               pl.ld[0], c->at<float>(pl.o_an[0]), cap, s));
+                               pl.ld[0], c->at<float>(pl.o_an[0]), cap, s)); }
 
   // forward
   for (int l = 1; l <= L; ++l) {
@@ -326,16 +401,18 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
       p.C = act_ptr(pl.o_A[l]); p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l]; p.pad_to_ld = 1;
       if (pl.gelu) { p.C2 = act_ptr(pl.o_Dact[l]); p.sC2g = cap * pl.ld[l]; p.ldc2 = pl.ld[l]; }
       HIPCHK(c, gemm(c, p, EPI_FWD_ACT));
-      HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, s));
+      { ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
+  HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, s)); }
     } else {
       p.C = c->at<float>(pl.o_Z); p.sCg = cap * pl.ld[L]; p.ldc = pl.ld[L];
       HIPCHK(c, gemm(c, p, EPI_LOGITS));
     }
   }
   // loss head: per-sample backprop signal of the last layer
+  { ProfScope ps_(c, T_SOFTMAX, 0.0, 1.0 * M * b * pl.ld[L] * (4 + pl.esz));
   HIPCHK(c, launch_softmax_ce(isb, c->at<float>(pl.o_Z), cap * pl.ld[L], pl.ld[L], pl.dims[L], c->y, (int)c->N, idx_dev, M, b,
                               act_ptr(pl.o_Dl[L]), cap * pl.ld[L], pl.ld[L], c->at<float>(pl.o_dn[L]),
-                              c->at<float>(pl.o_loss), cap, s));
+                              c->at<float>(pl.o_loss), cap, s)); }
   // backward-data
   for (int l = L; l >= 2; --l) {
     GemmP p;
@@ -348,7 +425,8 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
     p.sEg = cap * pl.ld[l - 1]; p.lde = pl.ld[l - 1];
     HIPCHK(c, gemm(c, p, EPI_BWD));
-    HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, s));
+    { ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
+  HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, s)); }
   }
   // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
   const float inv_b = 1.0f / (float)b;
@@ -363,7 +441,8 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
     HIPCHK(c, gemm(c, p, EPI_WGRAD));
     if (hb)
-      HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad, s));
+      { ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
+  HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad, s)); }
   }
   // inner products <g_i, gbar>
   StatsP sp;
@@ -391,8 +470,9 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
         p.C = U; p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l];
         HIPCHK(c, gemm(c, p, EPI_LOGITS));
         float *q = c->at<float>(pl.o_qpart[0]);
-        HIPCHK(c, launch_rowdot_f32(static_cast<const float *>(act_ptr(pl.o_Dl[l])), cap * pl.ld[l], pl.ld[l], U,
-                                    cap * pl.ld[l], pl.ld[l], pl.dims[l], M, b, q, cap, l > 1, s));
+        { ProfScope ps_(c, T_ROWDOT, 0.0, 2.0 * M * b * pl.ld[l] * 4);
+  HIPCHK(c, launch_rowdot_f32(static_cast<const float *>(act_ptr(pl.o_Dl[l])), cap * pl.ld[l], pl.ld[l], U,
+                                    cap * pl.ld[l], pl.ld[l], pl.dims[l], M, b, q, cap, l > 1, s)); }
         sp.qpart[l - 1] = q; sp.nparts[l - 1] = (l == 1) ? 1 : 0; sp.sQg[l - 1] = cap; sp.sQpart[l - 1] = cap;
       }
     }
@@ -405,7 +485,8 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   sp.n_out = c->at<float>(pl.o_nout); sp.q_out = c->at<float>(pl.o_qout);
   sp.grad = grad; sp.Ppad = pl.Ppad;
   sp.partials = c->at<double>(pl.o_partials); sp.stats = c->at<double>(pl.o_stats);
-  HIPCHK(c, launch_stats(sp, s));
+  { ProfScope ps_(c, T_STATS, 0.0, 4.0 * M * pl.Ppad);
+  HIPCHK(c, launch_stats(sp, s)); }
   // optimizer update (Alg. 1: "local SGD step ... or other inner optimizers")
   c->t += 1;
   UpdateP up;
@@ -421,7 +502,8 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     up.c1 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta1, (double)c->t)));
     up.c2 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta2, (double)c->t)));
   }
-  HIPCHK(c, launch_update(up, s));
+  { ProfScope ps_(c, T_UPDATE, 0.0, 1.0 * M * pl.P * (c->cfg.opt == ABS_OPT_SGD ? 12 : c->cfg.opt == ABS_OPT_SHB ? 20 : 28) + (pl.bf16 ? 2.0 * M * pl.P : 0.0));
+  HIPCHK(c, launch_update(up, s)); }
   c->last_b = b;
   c->have_stats = true;
   return ABS_OK;
@@ -519,7 +601,10 @@ abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_c
 abs_status abs_average_replicas(abs_ctx *c) {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   const Plan &pl = c->pl;
-  HIPCHK(c, launch_average_f32(c->at<float>(pl.o_xm), pl.bf16 ? c->at<bf16_t>(pl.o_xs) : nullptr, pl.M, pl.Ppad, c->stream));
+  {
+    ProfScope ps_(c, T_AVERAGE, 0.0, (double)pl.M * pl.P * (pl.bf16 ? 10.0 : 8.0));
+    HIPCHK(c, launch_average_f32(c->at<float>(pl.o_xm), pl.bf16 ? c->at<bf16_t>(pl.o_xs) : nullptr, pl.M, pl.Ppad, c->stream));
+  }
   return ABS_OK;
 }
 

@@ -40,6 +40,8 @@ struct GemmP {
 // EPI_IPDOT writes per row (tiles along n) for the tile shape it picks.
 hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s);
 int gemm_bf16_ipdot_parts(int Nd);
+// Tile shape the bf16 family uses for an Md x Nd output: 0 = 128x64, 1 = 128x128, 2 = 256x256.
+int gemm_bf16_tile_shape(int Md, int Nd);
 // fp32 SIMT family (gemm_f32.hip); EPI_IPDOT is not offered (U is materialised instead).
 hipError_t launch_gemm_f32(const GemmP &p, int epi, hipStream_t s);
 

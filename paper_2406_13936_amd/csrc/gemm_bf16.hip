@@ -312,9 +312,11 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
 // otherwise a 128x128 (or 128x64 for narrow outputs) tile.
 template <bool AT, bool BT, int EPI, int ACT>
 hipError_t launch_shape(const GemmP &p, hipStream_t s) {
-  if (p.Nd <= 64) return launch_cfg<128, 64, 64, 4, 1, AT, BT, EPI, ACT>(p, s);
-  if (p.Md >= 1024 && p.Nd >= 1024) return launch_cfg<256, 256, 64, 2, 4, AT, BT, EPI, ACT>(p, s);
-  return launch_cfg<128, 128, 64, 2, 2, AT, BT, EPI, ACT>(p, s);
+  switch (gemm_bf16_tile_shape(p.Md, p.Nd)) {
+    case 0: return launch_cfg<128, 64, 64, 4, 1, AT, BT, EPI, ACT>(p, s);
+    case 2: return launch_cfg<256, 256, 64, 2, 4, AT, BT, EPI, ACT>(p, s);
+    default: return launch_cfg<128, 128, 64, 2, 2, AT, BT, EPI, ACT>(p, s);
+  }
 }
 
 template <bool AT, bool BT, int EPI>
@@ -330,6 +332,12 @@ hipError_t launch_act(const GemmP &p, hipStream_t s) {
 }
 
 }  // namespace
+
+int gemm_bf16_tile_shape(int Md, int Nd) {
+  if (Nd <= 64) return 0;
+  if (Md >= 1024 && Nd >= 1024) return 2;
+  return 1;
+}
 
 int gemm_bf16_ipdot_parts(int Nd) {
   if (Nd <= 64) return 1;
