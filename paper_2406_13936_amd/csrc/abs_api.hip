@@ -34,7 +34,7 @@ struct Plan {
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
   size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
-  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0;
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0;
   size_t total = 0;
 };
 
@@ -119,6 +119,11 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
       if (pl.qparts[l - 1]) pl.o_qpart[l - 1] = take(MB * 4 * pl.qparts[l - 1]);
     }
   }
+  if (c->has_bias) {
+    int mx = 0;
+    for (int l = 1; l <= pl.L; ++l) mx = pl.dims[l] > mx ? pl.dims[l] : mx;
+    pl.o_colpart = take((size_t)pl.M * ((pl.cap + COLSUM_ROWS - 1) / COLSUM_ROWS) * mx * 4);
+  }
   pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
   pl.o_stats = take((size_t)pl.M * 8 * 8);
   pl.o_cw = take((2 * STATS_PBLK + 8) * 8);
@@ -131,9 +136,10 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
 enum {
   T_GATHER = 0, T_SOFTMAX, T_ROWNORM, T_COLSUM, T_STATS, T_UPDATE, T_AVERAGE, T_ROWDOT,
   T_GEMM0,                       // + epi * 3 + tile shape (bf16) ; fp32 family uses shape 1
-  T_COUNT = T_GEMM0 + 5 * 3
+  T_GEMM_KINDS = 5 * 3, T_LAYERS = 17,   // GEMM classes are resolved per layer
+  T_COUNT = T_GEMM0 + T_GEMM_KINDS * T_LAYERS
 };
-static const char *const kTagNames[T_COUNT] = {
+static const char *const kTagNames[T_GEMM0 + T_GEMM_KINDS] = {
   "gather_rows", "softmax_ce", "row_sqnorm", "col_sum", "stats", "update", "average", "rowdot",
   "gemm_fwd_128x64", "gemm_fwd_128x128", "gemm_fwd_256x256",
   "gemm_logits_128x64", "gemm_logits_128x128", "gemm_logits_256x256",
@@ -213,9 +219,9 @@ struct ProfScope {
   ~ProfScope() { if (r) (void)hipEventRecord(r->e1, c->stream); }
 };
 
-hipError_t gemm(abs_ctx *c, const GemmP &p, int epi) {
+hipError_t gemm(abs_ctx *c, const GemmP &p, int epi, int layer) {
   const int shape = c->pl.bf16 ? gemm_bf16_tile_shape(p.Md, p.Nd) : 1;
-  ProfScope ps(c, T_GEMM0 + epi * 3 + shape, 2.0 * p.Md * p.Nd * p.Kd * p.groups, 0.0);
+  ProfScope ps(c, T_GEMM0 + (epi * 3 + shape) * T_LAYERS + layer, 2.0 * p.Md * p.Nd * p.Kd * p.groups, 0.0);
   return c->pl.bf16 ? launch_gemm_bf16(p, epi, c->stream) : launch_gemm_f32(p, epi, c->stream);
 }
 
@@ -356,7 +362,8 @@ abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out,
     if (!c->prof_calls[t]) continue;
     abs_profile_entry e;
     std::memset(&e, 0, sizeof(e));
-    std::strncpy(e.name, kTagNames[t], sizeof(e.name) - 1);
+    if (t < T_GEMM0) std::strncpy(e.name, kTagNames[t], sizeof(e.name) - 1);
+    else std::snprintf(e.name, sizeof(e.name), "%s_L%d", kTagNames[T_GEMM0 + (t - T_GEMM0) / T_LAYERS], (t - T_GEMM0) % T_LAYERS);
     e.calls = c->prof_calls[t]; e.total_ms = c->prof_ms[t]; e.flops = c->prof_flops[t]; e.bytes = c->prof_bytes[t];
     out[n++] = e;
   }
@@ -400,12 +407,12 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     if (l < L) {
       p.C = act_ptr(pl.o_A[l]); p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l]; p.pad_to_ld = 1;
       if (pl.gelu) { p.C2 = act_ptr(pl.o_Dact[l]); p.sC2g = cap * pl.ld[l]; p.ldc2 = pl.ld[l]; }
-      HIPCHK(c, gemm(c, p, EPI_FWD_ACT));
+      HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
       { ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
   HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, s)); }
     } else {
       p.C = c->at<float>(pl.o_Z); p.sCg = cap * pl.ld[L]; p.ldc = pl.ld[L];
-      HIPCHK(c, gemm(c, p, EPI_LOGITS));
+      HIPCHK(c, gemm(c, p, EPI_LOGITS, l));
     }
   }
   // loss head: per-sample backprop signal of the last layer
@@ -424,7 +431,7 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     p.act = c->cfg.act;
     p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
     p.sEg = cap * pl.ld[l - 1]; p.lde = pl.ld[l - 1];
-    HIPCHK(c, gemm(c, p, EPI_BWD));
+    HIPCHK(c, gemm(c, p, EPI_BWD, l));
     { ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
   HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, s)); }
   }
@@ -439,10 +446,10 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
     p.alpha = inv_b;
     if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
-    HIPCHK(c, gemm(c, p, EPI_WGRAD));
+    HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
     if (hb)
       { ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
-  HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad, s)); }
+  HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad, c->at<float>(pl.o_colpart), s)); }
   }
   // inner products <g_i, gbar>
   StatsP sp;
@@ -461,14 +468,14 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
         p.part = c->at<float>(pl.o_qpart[l - 1]);
         p.sPartg = cap * pl.qparts[l - 1]; p.sPartTile = cap;
         HIPCHK(c, launch_fill_zero(p.part, (long long)M * cap * pl.qparts[l - 1] * 4, s));
-        HIPCHK(c, gemm(c, p, EPI_IPDOT));
+        HIPCHK(c, gemm(c, p, EPI_IPDOT, l));
         sp.qpart[l - 1] = p.part; sp.nparts[l - 1] = pl.qparts[l - 1];
         sp.sQg[l - 1] = p.sPartg; sp.sQpart[l - 1] = cap;
       } else {
         p.B = grad + pl.offW[l];
         float *U = c->at<float>(pl.o_U);
         p.C = U; p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l];
-        HIPCHK(c, gemm(c, p, EPI_LOGITS));
+        HIPCHK(c, gemm(c, p, EPI_LOGITS, l));
         float *q = c->at<float>(pl.o_qpart[0]);
         { ProfScope ps_(c, T_ROWDOT, 0.0, 2.0 * M * b * pl.ld[l] * 4);
   HIPCHK(c, launch_rowdot_f32(static_cast<const float *>(act_ptr(pl.o_Dl[l])), cap * pl.ld[l], pl.ld[l], U,

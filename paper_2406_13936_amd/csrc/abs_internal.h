@@ -61,9 +61,11 @@ hipError_t launch_softmax_ce(int is_bf16, const float *Z, long long sZg, int ldz
 // out[g][i] = sum_j X[g][i][j]^2
 hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, int cols,
                              int groups, int b, float *out, long long sOg, hipStream_t s);
-// out[g][j] = alpha * sum_i X[g][i][j]   (bias gradients)
+// out[g][j] = alpha * sum_i X[g][i][j]   (bias gradients); scratch: groups * ceil(b / COLSUM_ROWS)
+// * cols floats of partial sums
+enum { COLSUM_ROWS = 128 };
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups,
-                          int b, float alpha, float *out, long long sOg, hipStream_t s);
+                          int b, float alpha, float *out, long long sOg, float *scratch, hipStream_t s);
 // q[g][i] += sum_j D[g][i][j] * U[g][i][j]  (fp32 path of the inner products)
 hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U,
                              long long sUg, int ldu, int cols, int groups, int b, float *q,

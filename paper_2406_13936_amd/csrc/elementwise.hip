@@ -142,24 +142,35 @@ __global__ void row_sqnorm_kernel(const T *__restrict__ X, long long sXg, int ld
   if (lane == 0) out[(long long)g * sOg + i] = s;
 }
 
-// 64 columns x 4 row-lanes per block; each row-lane strides over the rows, the four
-// partial sums are added in a fixed order.
+// Column sums in two fixed-order stages.  Stage 1: a block owns 64 columns x COLSUM_ROWS rows
+// (4 row-lanes striding over them, added in lane order) and writes one partial per column;
+// stage 2 adds the partials of all row-blocks in index order and scales.
 template <class T>
-__global__ void col_sum_kernel(const T *__restrict__ X, long long sXg, int ld, int cols, int b,
-                               float alpha, float *__restrict__ out, long long sOg) {
+__global__ void __launch_bounds__(256) col_sum_stage1(const T *__restrict__ X, long long sXg, int ld, int cols,
+                                                      int b, float *__restrict__ part, int nsplit) {
   __shared__ float red[4][64];
-  const int g = blockIdx.y;
+  const int g = blockIdx.z, rs = blockIdx.y;
   const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
+  const int r0 = rs * COLSUM_ROWS, r1 = min(b, r0 + COLSUM_ROWS);
   float s = 0.0f;
   if (c < cols) {
     const T *p = X + (long long)g * sXg + c;
-    for (int i = rl; i < b; i += 4) s += Elem<T>::ld(p + (long long)i * ld);
+    for (int i = r0 + rl; i < r1; i += 4) s += Elem<T>::ld(p + (long long)i * ld);
   }
   red[rl][cl] = s;
   __syncthreads();
   if (rl == 0 && c < cols)
-    out[(long long)g * sOg + c] = alpha * (((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
+    part[((long long)g * nsplit + rs) * cols + c] = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
+}
+__global__ void __launch_bounds__(256) col_sum_stage2(const float *__restrict__ part, int cols, int nsplit,
+                                                      float alpha, float *__restrict__ out, long long sOg) {
+  const int g = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= cols) return;
+  const float *p = part + (long long)g * nsplit * cols + c;
+  float s = 0.0f;
+  for (int r = 0; r < nsplit; ++r) s += p[(long long)r * cols];
+  out[(long long)g * sOg + c] = alpha * s;
 }
 
 __global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, int ldd,
@@ -427,14 +438,17 @@ hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, 
 }
 
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
-                          float alpha, float *out, long long sOg, hipStream_t s) {
-  const dim3 grid((cols + 63) / 64, groups), blk(256);
+                          float alpha, float *out, long long sOg, float *scratch, hipStream_t s) {
+  const int nsplit = (b + COLSUM_ROWS - 1) / COLSUM_ROWS;
+  const dim3 grid((cols + 63) / 64, nsplit, groups), blk(256);
   if (is_bf16)
-    hipLaunchKernelGGL(col_sum_kernel<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols,
-                       b, alpha, out, sOg);
+    hipLaunchKernelGGL(col_sum_stage1<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols, b,
+                       scratch, nsplit);
   else
-    hipLaunchKernelGGL(col_sum_kernel<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols,
-                       b, alpha, out, sOg);
+    hipLaunchKernelGGL(col_sum_stage1<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
+                       scratch, nsplit);
+  hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, scratch, cols, nsplit,
+                     alpha, out, sOg);
   return hipGetLastError();
 }
 

@@ -2,133 +2,143 @@
 //
 //   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k],   g = replica
 //
-// covers the three contractions of one local step (Alg. 1 of the paper, "compute the local
-// batch gradient"): forward  a W^T, backward-data  delta W, weight gradient  delta^T a, and
-// the extra contraction  a Gbar^T  of the inner-product statistics.  Either operand may be
-// stored k-contiguous ([row][k]) or row-contiguous ([k][row]); the latter is transposed in
-// registers (8x8 / 8x4 bf16 blocks, v_perm) on its way into LDS, so LDS always holds
-// k-contiguous tiles and every MFMA operand fragment is one 16-byte LDS read.
+// covers the contractions of one local step (Alg. 1 of the paper, "compute the local batch
+// gradient"): forward  a W^T, backward-data  delta W, weight gradient  delta^T a, and the extra
+// contraction  a Gbar^T  of the inner-product statistics.  Either operand may be stored
+// k-contiguous (memory [row][k]) or row-contiguous (memory [k][row]).
 //
-// Tiling: BM x BN x BK block tile, WM x WN wavefronts of 64 lanes, each computing a
-// (BM/WM) x (BN/WN) sub-tile as a grid of 32x32x16 bf16 MFMAs with fp32 accumulators.
-// Global -> registers -> LDS with two LDS buffers: the loads of tile k+1 are issued before
-// the MFMAs of tile k and written to the other buffer afterwards (one barrier per k-tile).
-// Work-group ids are remapped so that each XCD (ids are dealt round-robin to the 8 XCDs)
-// works on a contiguous range of tiles and its L2 sees a few row-blocks of A and one
-// replica's B at a time.
+// Data path (no operand ever passes through vector registers on its way to LDS):
+//   * global -> LDS with `buffer_load_dwordx4 ... lds` (16 bytes per lane, written by the
+//     memory pipeline at M0 + 16*lane), NS stage buffers in a ring; out-of-range chunks come
+//     back as zeros through the buffer descriptor's range check, so ragged m / n / k need no
+//     branches.  A stage's loads are spread over the MFMA groups of the previous stage so that
+//     a wavefront never sits in the memory-issue queue while the matrix pipe idles.
+//   * k-contiguous tiles are kept as [row][BK] with the 16-byte chunk index XOR-swizzled by the
+//     row (the permutation is applied on the global-address side, since the LDS side of a
+//     direct load is linear in the lane id); an MFMA fragment is one ds_read_b128.
+//   * row-contiguous tiles are kept as [k][rows] and read with ds_read_b64_tr_b16, the LDS
+//     transpose read: inside each group of 16 lanes, lane i receives element (i % 4) of the
+//     8-byte vectors addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12 -- i.e. four
+//     consecutive k for its own row when lane j addresses (k = j / 4, rows 4 (j % 4) ..+3).
+//   * one s_barrier per k-tile; s_waitcnt vmcnt(n) lets the younger stages stay in flight.
+//
+// Tiling: BM x BN x BK block tile, WM x WN wavefronts of 64 lanes, each a grid of 32x32x16
+// bf16 MFMAs with fp32 accumulators.  Work-group ids are remapped so that each XCD (ids are
+// dealt round-robin to the 8 XCDs) works on a contiguous range of tiles and its L2 sees one
+// replica's operands at a time.
 #include "abs_internal.h"
 #include "device_utils.h"
 
 namespace absk {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 namespace {
 
-constexpr int LPAD = 8;  // bf16 elements of padding per LDS row (16 bytes)
+constexpr uint32_t OOB = 0x80000000u;   // byte offset beyond any operand (operands are < 2 GiB)
 
-// ---- global -> register staging ---------------------------------------------------------
-// k-contiguous operand tile [ROWS x BK]: 16-byte chunks, thread t takes chunks t, t+NT, ...
-template <int ROWS, int BK, int NT>
-struct StageK {
-  static constexpr int CPR = BK / 8;                 // chunks per row
-  static constexpr int N = (ROWS * CPR) / NT;        // chunks per thread
-  static_assert((ROWS * CPR) % NT == 0, "tile/threads mismatch");
-  uint4 r[N];
-  __device__ __forceinline__ void load(const bf16_t *base, int ld, int row0, int rows, int k0,
-                                       int K, int tid) {
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int c = tid + i * NT;
-      const int row = row0 + c / CPR, k = k0 + (c % CPR) * 8;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (row < rows && k < K) v = *reinterpret_cast<const uint4 *>(base + (long long)row * ld + k);
-      r[i] = v;
-    }
-  }
-  __device__ __forceinline__ void store(bf16_t *lds, int tid) const {
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int c = tid + i * NT;
-      *reinterpret_cast<uint4 *>(lds + (c / CPR) * (BK + LPAD) + (c % CPR) * 8) = r[i];
-    }
-  }
-};
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  // s_waitcnt immediate on gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
 
-// row-contiguous operand (memory [k][row]): thread takes 8 k-rows x NV rows-of-the-tile,
-// transposes them in registers and writes NV 16-byte LDS chunks.
-template <int ROWS, int BK, int NT>
-struct StageT {
-  static constexpr int PER = (ROWS * BK) / (8 * NT);   // tile rows per thread (times 8 k)
-  static constexpr int NV = PER >= 8 ? 8 : PER;        // rows per block: 8 (16 B), 4 or 2
-  static constexpr int NB = PER / NV;                  // blocks per thread
-  static_assert(PER == 2 || PER == 4 || PER % 8 == 0, "unsupported tile/threads ratio");
-  static constexpr int KC = BK / 8;                    // k-chunks per tile
-  static constexpr int NW = NV / 2;                    // 32-bit words per loaded vector
-  uint32_t r[NB][8][NW];
-  __device__ __forceinline__ void load(const bf16_t *base, int ld, int row0, int rows, int k0,
-                                       int K, int tid) {
+// ---- one operand's stage: addressing of the direct loads and of the fragment reads ---------
+// ROWS = tile extent along m (or n); TRANS = memory is [k][row].
+template <int ROWS, int BK, bool TRANS, int NW>
+struct Operand {
+  static constexpr int ELEMS = ROWS * BK;                 // bf16 elements per stage
+  static constexpr int NI = ELEMS / 8 / 64 / NW;          // load instructions per wave per stage
+  static_assert(ELEMS % (8 * 64 * NW) == 0 && NI >= 1, "tile too small for the wave count");
+  static constexpr int CPR = BK / 8;                      // k-contiguous: chunks per row
+  static constexpr int SWS = CPR >= 8 ? 1 : 2;
+  static constexpr int CH = ROWS / 8;                     // row-contiguous: chunks per k-row
+  static_assert(!TRANS || CH >= 8, "transposed tiles need at least 64 rows");
+
+  uint32_t voff[NI];     // per-lane byte offset of its chunk at k0 = 0 (OOB if the row is outside)
+  int kofs[NI];          // k (relative to k0) of the chunk, for the ragged last k-tile
+
+  __device__ __forceinline__ void init(int wave, int lane, int row0, int rows, int ld) {
 #pragma unroll
-    for (int bi = 0; bi < NB; ++bi) {
-      const int blk = tid + bi * NT;
-      const int kc = blk % KC, nb = blk / KC;
-      const int row = row0 + nb * NV;                  // first tile row (memory column)
-      const bool rin = row < rows;                     // ld is a multiple of 8: whole vector in
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int k = k0 + kc * 8 + j;
-        const bf16_t *src = base + (long long)k * ld + row;
-        const bool in = rin && k < K;
-        if constexpr (NV == 8) {
-          uint4 v = make_uint4(0, 0, 0, 0);
-          if (in) v = *reinterpret_cast<const uint4 *>(src);
-          r[bi][j][0] = v.x; r[bi][j][1] = v.y; r[bi][j][2] = v.z; r[bi][j][3] = v.w;
-        } else if constexpr (NV == 4) {
-          uint2 v = make_uint2(0, 0);
-          if (in) v = *reinterpret_cast<const uint2 *>(src);
-          r[bi][j][0] = v.x; r[bi][j][1] = v.y;
-        } else {
-          uint32_t v = 0;
-          if (in) v = *reinterpret_cast<const uint32_t *>(src);
-          r[bi][j][0] = v;
-        }
+    for (int i = 0; i < NI; ++i) {
+      const int c = (wave * NI + i) * 64 + lane;          // linear 16-byte chunk index in the stage
+      if (!TRANS) {
+        const int row = c / CPR, kc = (c % CPR) ^ ((row >> SWS) & (CPR - 1));
+        kofs[i] = kc * 8;
+        voff[i] = (row0 + row < rows) ? (uint32_t)((row0 + row) * ld + kc * 8) * 2u : OOB;
+      } else {
+        const int kq = c / CH, ch = (c % CH) ^ (2 * (kq & 3));
+        kofs[i] = kq;
+        voff[i] = (row0 + ch * 8 < rows) ? (uint32_t)(kq * ld + row0 + ch * 8) * 2u : OOB;
       }
     }
   }
-  __device__ __forceinline__ void store(bf16_t *lds, int tid) const {
-#pragma unroll
-    for (int bi = 0; bi < NB; ++bi) {
-      const int blk = tid + bi * NT;
-      const int kc = blk % KC, nb = blk / KC;
-#pragma unroll
-      for (int n = 0; n < NV; ++n) {
-        // column n of the 8 x NV block: element k of it sits in half (n&1) of r[.][k][n/2]
-        const uint32_t sel = (n & 1) ? 0x07060302u : 0x05040100u;
-        uint4 o;
-        o.x = __builtin_amdgcn_perm(r[bi][1][n / 2], r[bi][0][n / 2], sel);
-        o.y = __builtin_amdgcn_perm(r[bi][3][n / 2], r[bi][2][n / 2], sel);
-        o.z = __builtin_amdgcn_perm(r[bi][5][n / 2], r[bi][4][n / 2], sel);
-        o.w = __builtin_amdgcn_perm(r[bi][7][n / 2], r[bi][6][n / 2], sel);
-        *reinterpret_cast<uint4 *>(lds + (nb * NV + n) * (BK + LPAD) + kc * 8) = o;
-      }
-    }
+  // byte offset added for k-tile kt (scalar)
+  static __device__ __forceinline__ uint32_t soff(int kt, int ld) {
+    return TRANS ? (uint32_t)kt * BK * ld * 2u : (uint32_t)kt * BK * 2u;
+  }
+  // i is a compile-time constant after unrolling (voff / kofs live in registers)
+  __device__ __forceinline__ void load(int i, __amdgpu_buffer_rsrc_t rsrc, bf16_t *stage, int wave, int kt,
+                                       int K, int ld, bool full) const {
+    uint32_t v = voff[i];
+    if (!full && kt * BK + kofs[i] >= K) v = OOB;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void *)(stage + (wave * NI + i) * 512), 16, v,
+                                             soff(kt, ld), 0, 0);
   }
 };
 
-template <bool TRANS, int ROWS, int BK, int NT> struct StageSel { typedef StageK<ROWS, BK, NT> type; };
-template <int ROWS, int BK, int NT> struct StageSel<true, ROWS, BK, NT> { typedef StageT<ROWS, BK, NT> type; };
+// fragment of rows [r0, r0+32) for k-step kk of a stage
+template <int ROWS, int BK, bool TRANS>
+struct Frag {
+  static constexpr int CPR = BK / 8, SWS = CPR >= 8 ? 1 : 2, CH = ROWS / 8;
+  int base, swz;         // !TRANS: element offset of the row, and its swizzle
+  int tbase[2];          // TRANS: element offsets for the two transpose reads at kk = 0
+  __device__ __forceinline__ void init(int r0, int lane) {
+    if (!TRANS) {
+      const int r = r0 + (lane & 31);
+      base = r * BK;
+      swz = (r >> SWS) & (CPR - 1);
+    } else {
+      const int i16 = lane & 15, g16 = lane >> 4;
+      const int rr = r0 + (g16 & 1) * 16 + 4 * (i16 & 3);     // first of this lane's 4 rows
+      const int kq = (g16 >> 1) * 8 + (i16 >> 2);             // k within the 16-wide step
+      // the chunk swizzle 2*(k&3) does not depend on kk (16 | step) nor on the +4 of the 2nd read
+      const int ch = (rr >> 3) ^ (2 * (kq & 3));
+      tbase[0] = kq * ROWS + ch * 8 + (rr & 7);
+      tbase[1] = tbase[0] + 4 * ROWS;
+    }
+  }
+  __device__ __forceinline__ bf16x8 read(const bf16_t *stage, int kk) const {
+    if (!TRANS) {
+      const int kc = kk * 2 + (threadIdx.x >> 5 & 1);
+      return *reinterpret_cast<const bf16x8 *>(stage + base + ((kc ^ swz) << 3));
+    } else {
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + tbase[0] + kk * 16 * ROWS));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + tbase[1] + kk * 16 * ROWS));
+      const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, v);
+    }
+  }
+};
 
 // ---- the kernel --------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WM, int WN, bool AT, bool BT, int EPI, int ACT>
+template <int BM, int BN, int BK, int WM, int WN, int NS, bool AT, bool BT, int EPI, int ACT>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nblk, const int chunk) {
-  constexpr int NT = WM * WN * 64;
+  constexpr int NW = WM * WN, NT = NW * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
-  constexpr int LS = BK + LPAD;
-  constexpr int TILE = (BM + BN) * LS;                  // bf16 elements per LDS buffer
-  static_assert(TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0, "tile shape");
+  constexpr int STAGE = (BM + BN) * BK;                 // bf16 elements per stage
+  constexpr int NPART = BK / 16;                        // MFMA groups per k-tile
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0 && NS >= 2, "tile shape");
+  typedef Operand<BM, BK, AT, NW> OpA;
+  typedef Operand<BN, BK, BT, NW> OpB;
+  constexpr int NL = OpA::NI + OpB::NI;                 // load instructions per wave per stage
+  static_assert((NS - 2) * NL <= 63, "vmcnt range");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t *smem = reinterpret_cast<bf16_t *>(smem_raw);
@@ -143,14 +153,34 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
   const int tm = t / tilesN, tn = t - tm * tilesN;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
   const bf16_t *A = static_cast<const bf16_t *>(p.A) + (long long)g * p.sAg;
   const bf16_t *B = static_cast<const bf16_t *>(p.B) + (long long)g * p.sBg;
+  // range = the operand's extent in memory: rows*ld (k-contiguous) or K*ld (row-contiguous)
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t *>(A), 0, (int)((long long)(AT ? p.Kd : p.Md) * p.lda * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t *>(B), 0, (int)((long long)(BT ? p.Kd : p.Nd) * p.ldb * 2), 0x00020000);
 
-  typename StageSel<AT, BM, BK, NT>::type sa;
-  typename StageSel<BT, BN, BK, NT>::type sb;
+  OpA oa;
+  OpB ob;
+  oa.init(wave, lane, m0, p.Md, p.lda);
+  ob.init(wave, lane, n0, p.Nd, p.ldb);
+
+  // issue the loads of stage-slot `buf` for k-tile kt whose index l satisfies l % NPART == part
+  auto issue = [&](int kt, int buf, int part) {
+    bf16_t *sa = smem + buf * STAGE, *sb = sa + BM * BK;
+    const bool full = (kt + 1) * BK <= p.Kd;
+#pragma unroll
+    for (int l = 0; l < NL; ++l) {
+      if (l % NPART != part) continue;
+      if (l < OpA::NI) oa.load(l, ra, sa, wave, kt, p.Kd, p.lda, full);
+      else ob.load(l - OpA::NI, rb, sb, wave, kt, p.Kd, p.ldb, full);
+    }
+  };
 
   f32x16 acc[MI][NI];
 #pragma unroll
@@ -160,76 +190,124 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  const int KT = (p.Kd + BK - 1) / BK;
-  sa.load(A, p.lda, m0, p.Md, 0, p.Kd, tid);
-  sb.load(B, p.ldb, n0, p.Nd, 0, p.Kd, tid);
-  sa.store(smem, tid);
-  sb.store(smem + BM * LS, tid);
-  __syncthreads();
+  Frag<BM, BK, AT> fa[MI];
+  Frag<BN, BK, BT> fb[NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) fa[i].init(wm * TM + i * 32, lane);
+#pragma unroll
+  for (int j = 0; j < NI; ++j) fb[j].init(wn * TN + j * 32, lane);
 
-  const int lrow = lane & 31, lk = (lane >> 5) * 8;
-  for (int kt = 0; kt < KT; ++kt) {
-    const bf16_t *As = smem + (kt & 1) * TILE;
-    const bf16_t *Bs = As + BM * LS;
-    if (kt + 1 < KT) {
-      sa.load(A, p.lda, m0, p.Md, (kt + 1) * BK, p.Kd, tid);
-      sb.load(B, p.ldb, n0, p.Nd, (kt + 1) * BK, p.Kd, tid);
+  const int KT = (p.Kd + BK - 1) / BK;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) {
+    if (s < KT) {
+#pragma unroll
+      for (int q = 0; q < NPART; ++q) issue(s, s, q);
     }
+  }
+
+  for (int kt = 0; kt < KT; ++kt) {
+    // k-tile kt has landed once only the loads of the younger in-flight stages are outstanding
+    if (kt + NS - 1 <= KT) wait_vmcnt<(NS - 2) * NL>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();      // all waves' loads of kt visible; everyone is done with kt-1
+    const bool more = kt + NS - 1 < KT;
+    const bf16_t *S = smem + (kt % NS) * STAGE;
+    // fragments are double-buffered in registers: the LDS reads of MFMA group kk+1 and this
+    // group's share of the next stage's global loads are issued before the MFMAs of group kk,
+    // which then run as one raised-priority cluster
+    bf16x8 af[2][MI], bfr[2][NI];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 af[MI], bfr[NI];
+    for (int i = 0; i < MI; ++i) af[0][i] = fa[i].read(S, 0);
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        af[i] = *reinterpret_cast<const bf16x8 *>(As + (wm * TM + i * 32 + lrow) * LS + kk * 16 + lk);
+    for (int j = 0; j < NI; ++j) bfr[0][j] = fb[j].read(S + BM * BK, 0);
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8 *>(Bs + (wn * TN + j * 32 + lrow) * LS + kk * 16 + lk);
+    for (int kk = 0; kk < NPART; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
+      if (kk + 1 < NPART) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[nxt][i] = fa[i].read(S, kk + 1);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bfr[nxt][j] = fb[j].read(S + BM * BK, kk + 1);
+      }
+      if (more) issue(kt + NS - 1, (kt + NS - 1) % NS, kk);
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          // operands swapped: the accumulator tile is C^T, so a lane owns one row m of C and
+          // groups of four consecutive columns n (see the epilogue)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (kt + 1 < KT) {
-      bf16_t *nx = smem + ((kt + 1) & 1) * TILE;
-      sa.store(nx, tid);
-      sb.store(nx + BM * LS, tid);
-    }
-    __syncthreads();
   }
 
-  // ---- epilogue.  Accumulator element r of a 32x32 tile: column = lane % 32,
-  //      row = 8 * (r / 4) + 4 * (lane / 32) + r % 4.
+  // ---- epilogue.  With the operands swapped in the MFMA, accumulator element r = 4q + e of tile
+  // (i, j) belongs to   row  m = wm*TM + 32 i + lane % 32,
+  //                     col  n = wn*TN + 32 j + 8 q + 4 (lane / 32) + e      (tile-relative),
+  // i.e. a lane holds four consecutive columns per q.  bf16 outputs and the elementwise operand E
+  // go through a per-wave LDS staging slice of 32 rows x TN columns, so that every global access
+  // of the epilogue is a 16-byte vector, 8 lanes to a 128-byte row segment.
   const int lcol = lane & 31, lhalf = lane >> 5;
   const float *bias = p.bias ? p.bias + (long long)g * p.sBiasg : nullptr;
+  constexpr int SLD = TN + 8;                               // staging row stride (elements)
+  bf16_t *stg = smem + wave * (32 * SLD);
+  constexpr int CPRW = TN / 8;                              // 16-byte chunks per staged row
+  constexpr int SIT = 32 * CPRW / 64;                       // chunks per lane per slice
+  static_assert(32 * CPRW % 64 == 0, "staging slice");
+  const int nw0 = n0 + wn * TN;                             // first column of this wave
+
+  // global -> staging of rows [mrow0, mrow0+32) x this wave's TN columns of a bf16 matrix
+  auto stage_in = [&](const bf16_t *src, int ld, int mrow0, int ncols) {
+#pragma unroll
+    for (int it = 0; it < SIT; ++it) {
+      const int c = it * 64 + lane, row = c / CPRW, cc = c % CPRW;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (mrow0 + row < p.Md && nw0 + cc * 8 < ncols)
+        v = *reinterpret_cast<const uint4 *>(src + (long long)(mrow0 + row) * ld + nw0 + cc * 8);
+      *reinterpret_cast<uint4 *>(stg + row * SLD + cc * 8) = v;
+    }
+  };
+  // staging -> global
+  auto stage_out = [&](bf16_t *dst, int ld, int mrow0, int ncols) {
+#pragma unroll
+    for (int it = 0; it < SIT; ++it) {
+      const int c = it * 64 + lane, row = c / CPRW, cc = c % CPRW;
+      const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * SLD + cc * 8);
+      if (mrow0 + row < p.Md && nw0 + cc * 8 < ncols)
+        *reinterpret_cast<uint4 *>(dst + (long long)(mrow0 + row) * ld + nw0 + cc * 8) = v;
+    }
+  };
+  auto piece = [&](int j, int q) -> bf16_t * { return stg + lcol * SLD + j * 32 + q * 8 + lhalf * 4; };
+
+  if (EPI == EPI_FWD_ACT || EPI == EPI_BWD || EPI == EPI_IPDOT) __syncthreads();   // stages are dead
 
   if (EPI == EPI_IPDOT) {
     const bf16_t *E = static_cast<const bf16_t *>(p.E) + (long long)g * p.sEg;
-    float *red = reinterpret_cast<float *>(smem_raw);     // [WN][BM] row partials (tiles are dead)
+    float *red = reinterpret_cast<float *>(smem + NW * 32 * SLD);   // [WN][BM] row partials
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-      float rs[16];
+      const int mrow0 = m0 + wm * TM + i * 32;
+      stage_in(E, p.lde, mrow0, p.Nd);
+      float rs = 0.0f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) rs[r] = 0.0f;
+      for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int j = 0; j < NI; ++j) {
-        const int n = n0 + wn * TN + j * 32 + lcol;
-        const float bv = (bias && n < p.Nd) ? bias[n] : 0.0f;
+        for (int q = 0; q < 4; ++q) {
+          const uint2 ev = *reinterpret_cast<const uint2 *>(piece(j, q));
+          const float e4[4] = {__uint_as_float(ev.x << 16), __uint_as_float(ev.x & 0xffff0000u),
+                               __uint_as_float(ev.y << 16), __uint_as_float(ev.y & 0xffff0000u)};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-          float e = 0.0f;
-          if (m < p.Md && n < p.Nd) e = bf2f(E[(long long)m * p.lde + n]);
-          rs[r] = fmaf(e, acc[i][j][r] + bv, rs[r]);
+          for (int e = 0; e < 4; ++e) {
+            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
+            const float bv = (bias && n < p.Nd) ? bias[n] : 0.0f;
+            rs = fmaf(e4[e], acc[i][j][4 * q + e] + bv, rs);      // E is zero outside the matrix
+          }
         }
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = rs[r];
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);   // over the 32 columns
-        if (lcol == 0) red[wn * BM + wm * TM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3)] = v;
-      }
+      rs += __shfl_xor(rs, 32, 64);                               // the two column halves of the row
+      if (lhalf == 0) red[wn * BM + wm * TM + i * 32 + lcol] = rs;
     }
     __syncthreads();
     float *part = p.part + (long long)g * p.sPartg + (long long)tn * p.sPartTile;
@@ -242,56 +320,124 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
     return;
   }
 
+  if (EPI == EPI_FWD_ACT) {
+    bf16_t *C = static_cast<bf16_t *>(p.C) + (long long)g * p.sCg;
+    bf16_t *C2 = p.C2 ? static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g : nullptr;
+    const int ncols = p.pad_to_ld ? p.ldc : p.Nd;           // pad columns are written as zeros
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int mrow0 = m0 + wm * TM + i * 32;
+      uint2 dpk[NI][4];
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float a4[4], d4[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
+            a4[e] = 0.0f; d4[e] = 0.0f;
+            if (n < p.Nd) act_fwd<ACT>(acc[i][j][4 * q + e] + (bias ? bias[n] : 0.0f), a4[e], d4[e]);
+          }
+          uint2 apk;
+          apk.x = pack2bf(a4[0], a4[1]); apk.y = pack2bf(a4[2], a4[3]);
+          dpk[j][q].x = pack2bf(d4[0], d4[1]); dpk[j][q].y = pack2bf(d4[2], d4[3]);
+          *reinterpret_cast<uint2 *>(piece(j, q)) = apk;
+        }
+      stage_out(C, p.ldc, mrow0, ncols);
+      if (ACT == ACT_GELU && C2) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) *reinterpret_cast<uint2 *>(piece(j, q)) = dpk[j][q];
+        stage_out(C2, p.ldc2, mrow0, ncols);
+      }
+    }
+    return;
+  }
+
+  if (EPI == EPI_BWD) {
+    bf16_t *C = static_cast<bf16_t *>(p.C) + (long long)g * p.sCg;
+    const bf16_t *E = static_cast<const bf16_t *>(p.E) + (long long)g * p.sEg;
+    const int ncols = p.pad_to_ld ? p.ldc : p.Nd;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int mrow0 = m0 + wm * TM + i * 32;
+      if (ACT != ACT_NONE) stage_in(E, p.lde, mrow0, p.Nd);
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float e4[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+          if (ACT != ACT_NONE) {
+            const uint2 ev = *reinterpret_cast<const uint2 *>(piece(j, q));
+            e4[0] = __uint_as_float(ev.x << 16); e4[1] = __uint_as_float(ev.x & 0xffff0000u);
+            e4[2] = __uint_as_float(ev.y << 16); e4[3] = __uint_as_float(ev.y & 0xffff0000u);
+          }
+          float o4[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
+            const float v = acc[i][j][4 * q + e];
+            o4[e] = (ACT == ACT_RELU) ? (e4[e] > 0.0f ? v : 0.0f) : (ACT == ACT_GELU ? v * e4[e] : v);
+            if (n >= p.Nd) o4[e] = 0.0f;
+          }
+          uint2 opk;
+          opk.x = pack2bf(o4[0], o4[1]); opk.y = pack2bf(o4[2], o4[3]);
+          *reinterpret_cast<uint2 *>(piece(j, q)) = opk;      // each lane overwrites the piece it read
+        }
+      stage_out(C, p.ldc, mrow0, ncols);
+    }
+    return;
+  }
+
+  // fp32 outputs (weight gradient, logits): direct stores, four consecutive columns per lane
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
+    const int m = m0 + wm * TM + i * 32 + lcol;
+    if (m >= p.Md) continue;
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int n = n0 + wn * TN + j * 32 + lcol;
-      const bool nin = n < p.Nd;
-      const float bv = (bias && nin) ? bias[n] : 0.0f;
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * TM + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-        if (m >= p.Md) continue;
-        const float v = acc[i][j][r];
-        if (EPI == EPI_FWD_ACT) {
-          if (n < p.ldc && (nin || p.pad_to_ld)) {
-            float a = 0.0f, d = 0.0f;
-            if (nin) act_fwd<ACT>(v + bv, a, d);
-            static_cast<bf16_t *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = f2bf(a);
-            if (ACT == ACT_GELU && p.C2)
-              static_cast<bf16_t *>(p.C2)[(long long)g * p.sC2g + (long long)m * p.ldc2 + n] = f2bf(d);
-          }
-        } else if (EPI == EPI_LOGITS) {
-          if (nin) static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = v + bv;
-        } else if (EPI == EPI_BWD) {
-          if (n < p.ldc && (nin || p.pad_to_ld)) {
-            float o = 0.0f;
-            if (nin) {
-              const float e = bf2f(static_cast<const bf16_t *>(p.E)[(long long)g * p.sEg + (long long)m * p.lde + n]);
-              o = (ACT == ACT_RELU) ? (e > 0.0f ? v : 0.0f) : (ACT == ACT_GELU ? v * e : v);
-            }
-            static_cast<bf16_t *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = f2bf(o);
-          }
-        } else if (EPI == EPI_WGRAD) {
-          if (nin) {
-            const float o = v * p.alpha;
-            static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = o;
-            if (p.C2) static_cast<bf16_t *>(p.C2)[(long long)g * p.sC2g + (long long)m * p.ldc2 + n] = f2bf(o);
+      for (int q = 0; q < 4; ++q) {
+        const int n = nw0 + j * 32 + q * 8 + lhalf * 4;
+        if (n >= p.Nd) continue;
+        float o4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float v = acc[i][j][4 * q + e];
+          o4[e] = (EPI == EPI_WGRAD) ? v * p.alpha : v + ((bias && n + e < p.Nd) ? bias[n + e] : 0.0f);
+        }
+        float *crow = static_cast<float *>(p.C) + (long long)g * p.sCg + (long long)m * p.ldc + n;
+        if (n + 4 <= p.Nd && (p.ldc & 3) == 0) {
+          *reinterpret_cast<float4 *>(crow) = make_float4(o4[0], o4[1], o4[2], o4[3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) if (n + e < p.Nd) crow[e] = o4[e];
+        }
+        if (EPI == EPI_WGRAD && p.C2) {
+          bf16_t *c2 = static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g + (long long)m * p.ldc2 + n;
+          if (n + 4 <= p.Nd && (p.ldc2 & 3) == 0) {
+            uint2 o;
+            o.x = pack2bf(o4[0], o4[1]); o.y = pack2bf(o4[2], o4[3]);
+            *reinterpret_cast<uint2 *>(c2) = o;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (n + e < p.Nd) c2[e] = f2bf(o4[e]);
           }
         }
       }
-    }
   }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool AT, bool BT, int EPI, int ACT>
+template <int BM, int BN, int BK, int WM, int WN, int NS, bool AT, bool BT, int EPI, int ACT>
 hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
   constexpr int NT = WM * WN * 64;
-  constexpr size_t tile_bytes = 2ull * (BM + BN) * (BK + LPAD) * sizeof(bf16_t);
-  constexpr size_t red_bytes = (size_t)WN * BM * sizeof(float);
-  constexpr size_t lds = tile_bytes > red_bytes ? tile_bytes : red_bytes;
-  auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, AT, BT, EPI, ACT>;
+  constexpr size_t tile_bytes = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
+  constexpr size_t epi_bytes = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(bf16_t) + (size_t)WN * BM * sizeof(float);
+  constexpr size_t lds = tile_bytes > epi_bytes ? tile_bytes : epi_bytes;
+  static_assert(lds <= 160 * 1024, "LDS budget");
+  auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, NS, AT, BT, EPI, ACT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -313,9 +459,9 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
 template <bool AT, bool BT, int EPI, int ACT>
 hipError_t launch_shape(const GemmP &p, hipStream_t s) {
   switch (gemm_bf16_tile_shape(p.Md, p.Nd)) {
-    case 0: return launch_cfg<128, 64, 64, 4, 1, AT, BT, EPI, ACT>(p, s);
-    case 2: return launch_cfg<256, 256, 64, 2, 4, AT, BT, EPI, ACT>(p, s);
-    default: return launch_cfg<128, 128, 64, 2, 2, AT, BT, EPI, ACT>(p, s);
+    case 0: return launch_cfg<128, 64, 64, 4, 1, 3, AT, BT, EPI, ACT>(p, s);
+    case 2: return launch_cfg<256, 256, 64, 2, 4, 2, AT, BT, EPI, ACT>(p, s);
+    default: return launch_cfg<128, 128, 64, 2, 2, 3, AT, BT, EPI, ACT>(p, s);
   }
 }
 
@@ -346,7 +492,7 @@ int gemm_bf16_ipdot_parts(int Nd) {
 }
 
 hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s) {
-  // operand checks the kernels rely on: 16-byte aligned rows
+  // operand checks the kernels rely on: 16-byte aligned rows, operands below 2 GiB per replica
   if ((p.lda & 7) || (p.ldb & 7)) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(p.A) & 15) || (reinterpret_cast<uintptr_t>(p.B) & 15)) return hipErrorInvalidValue;
   if ((p.sAg & 7) || (p.sBg & 7)) return hipErrorInvalidValue;
@@ -354,6 +500,9 @@ hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s) {
   if (!p.b_trans && (p.Kd > p.ldb)) return hipErrorInvalidValue;
   if (p.a_trans && (p.Md > p.lda)) return hipErrorInvalidValue;
   if (p.b_trans && (p.Nd > p.ldb)) return hipErrorInvalidValue;
+  const long long abytes = (long long)(p.a_trans ? p.Kd : p.Md) * p.lda * 2;
+  const long long bbytes = (long long)(p.b_trans ? p.Kd : p.Nd) * p.ldb * 2;
+  if (abytes >= (1LL << 31) || bbytes >= (1LL << 31)) return hipErrorInvalidValue;
   if (!p.a_trans && !p.b_trans) {
     if (epi == EPI_FWD_ACT) return launch_act<false, false, EPI_FWD_ACT>(p, s);
     if (epi == EPI_LOGITS) return launch_act<false, false, EPI_LOGITS>(p, s);

@@ -221,6 +221,41 @@ def test_bf16_step_matches_mixed_and_exact_oracle(dims, act, b, M, opt):
         rep.close()
 
 
+def test_config3_real_widths_large_tiles_ragged_batch():
+    """The real config-3 widths at a batch that is no tile multiple (1100 = 4 x 256 + 76):
+    every contraction runs in the 256x256 tile shape the benchmark times."""
+    A = _A()
+    base = W.config3()
+    import dataclasses
+    w = dataclasses.replace(base, name="cfg3_real_widths", N=4096, M=2, b0=1100, b_cap=1100, rounds=1)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    orc = _oracle_for(w, X, y, x0, mixed=True)
+    try:
+        idx = W.step_indices(w, 0, 0, 1100)
+        rep.local_step(idx, w.lr)
+        g = rep.inner_product_test(w.theta)
+        orc.local_step(idx, w.lr)
+        o = orc.test(W.TEST_IP, theta=w.theta)
+        for m in range(w.M):
+            s = orc.stats[m]
+            grad = rep.get_grad(m).astype(np.float64)
+            assert np.abs(grad - orc.grads[m]).max() <= 2e-3 * np.abs(orc.grads[m]).max()
+            n, q = rep.get_per_sample(m, 1100, want_q=True)
+            np.testing.assert_allclose(n, s["n"], rtol=5e-3)
+            np.testing.assert_allclose(q, s["q"], rtol=2e-2, atol=2e-3 * np.abs(s["q"]).max())
+            for name, got, want in (("S1", g[m].sum_sq, s["S1"]), ("S2", g[m].gbar_sq, s["S2"]),
+                                    ("S3", g[m].sum_q2, s["S3"]), ("S4", g[m].sum_q, s["S4"]),
+                                    ("loss", g[m].loss_sum, s["loss_sum"])):
+                assert _rel(got, want) <= 2e-3, (m, name, got, want)
+            assert _rel(g[m].ratio, o[m]["ratio"]) <= 5e-3
+            p = rep.get_params(m).astype(np.float64)
+            assert np.abs(p - orc.x[m]).max() <= 1e-3 * np.abs(orc.x[m]).max()
+    finally:
+        rep.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # trajectories
 # ---------------------------------------------------------------------------------------------
