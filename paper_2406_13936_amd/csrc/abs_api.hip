@@ -1,5 +1,6 @@
 // C ABI of the library (declared in include/abs.h): context, workspace plan, the call
 // sequence of one local step, host-side tests and the batch-size rule.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -30,6 +31,7 @@ struct Plan {
   long long P = 0, Ppad = 0;
   int M = 0, cap = 0;
   int qparts[MAXL] = {0};
+  int rparts[MAXL + 1] = {0};          // partial vectors kept for the row norms of width dims[l]
   // byte offsets into the workspace
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
@@ -108,8 +110,10 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
     for (int l = 1; l <= pl.L; ++l) mx = pl.ld[l] > mx ? pl.ld[l] : mx;
     pl.o_U = take(MB * mx * 4);
   }
-  for (int l = 0; l < pl.L; ++l) pl.o_an[l] = take(MB * 4);
-  for (int l = 1; l <= pl.L; ++l) pl.o_dn[l] = take(MB * 4);
+  for (int l = 0; l <= pl.L; ++l)
+    pl.rparts[l] = (pl.bf16 && l >= 1 && l < pl.L) ? gemm_bf16_ipdot_parts(pl.dims[l]) : 1;
+  for (int l = 0; l < pl.L; ++l) pl.o_an[l] = take(MB * 4 * pl.rparts[l]);
+  for (int l = 1; l <= pl.L; ++l) pl.o_dn[l] = take(MB * 4 * pl.rparts[l]);
   pl.o_loss = take(MB * 4);
   pl.o_nout = take(MB * 4);
   pl.o_qout = take(MB * 4);
@@ -122,7 +126,13 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   if (c->has_bias) {
     int mx = 0;
     for (int l = 1; l <= pl.L; ++l) mx = pl.dims[l] > mx ? pl.dims[l] : mx;
-    pl.o_colpart = take((size_t)pl.M * ((pl.cap + COLSUM_ROWS - 1) / COLSUM_ROWS) * mx * 4);
+    size_t per = (size_t)((pl.cap + COLSUM_ROWS - 1) / COLSUM_ROWS) * mx;      // standalone column sums
+    for (int l = 1; l < pl.L; ++l) {                                           // backward-epilogue partials
+      const size_t rows = pl.dims[l] > 64 ? (size_t)std::max((pl.cap + 255) / 256 * 2, 16)
+                                          : (size_t)((pl.cap + 127) / 128 * 4);
+      per = std::max(per, rows * pl.dims[l]);
+    }
+    pl.o_colpart = take((size_t)pl.M * per * 4);
   }
   pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
   pl.o_stats = take((size_t)pl.M * 8 * 8);
@@ -378,6 +388,9 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   if (b < 2 || b > pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
   const int L = pl.L, M = pl.M, isb = pl.bf16 ? 1 : 0;
+  int an_parts[MAXL + 1], dn_parts[MAXL + 2];
+  for (int l = 0; l <= MAXL; ++l) an_parts[l] = dn_parts[l] = 1;
+  dn_parts[MAXL + 1] = 1;
   const long long cap = pl.cap;
   hipStream_t s = c->stream;
   const bool hb = c->cfg.has_bias != 0;
@@ -407,9 +420,16 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     if (l < L) {
       p.C = act_ptr(pl.o_A[l]); p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l]; p.pad_to_ld = 1;
       if (pl.gelu) { p.C2 = act_ptr(pl.o_Dact[l]); p.sC2g = cap * pl.ld[l]; p.ldc2 = pl.ld[l]; }
-      HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
-      { ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
-  HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, s)); }
+      if (pl.bf16) {
+        // ||a_i^l||^2 as per-tile partials out of the GEMM epilogue (summed by the statistics kernel)
+        an_parts[l] = gemm_bf16_row_parts(b, pl.dims[l]);
+        p.part = c->at<float>(pl.o_an[l]); p.sPartg = cap * pl.rparts[l]; p.sPartTile = cap;
+        HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
+      } else {
+        HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
+        ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
+        HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, s));
+      }
     } else {
       p.C = c->at<float>(pl.o_Z); p.sCg = cap * pl.ld[L]; p.ldc = pl.ld[L];
       HIPCHK(c, gemm(c, p, EPI_LOGITS, l));
@@ -431,9 +451,25 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     p.act = c->cfg.act;
     p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
     p.sEg = cap * pl.ld[l - 1]; p.lde = pl.ld[l - 1];
-    HIPCHK(c, gemm(c, p, EPI_BWD, l));
-    { ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
-  HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, s)); }
+    if (pl.bf16) {
+      // ||delta_i^{l-1}||^2 and (with biases) the column sums of delta^{l-1} as epilogue partials
+      dn_parts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l - 1]);
+      p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap;
+      if (hb) {
+        p.cpart = c->at<float>(pl.o_colpart);
+        p.sCpartg = (long long)gemm_bf16_col_parts(b, pl.dims[l - 1]) * pl.dims[l - 1];
+      }
+      HIPCHK(c, gemm(c, p, EPI_BWD, l));
+      if (hb) {
+        ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1]) * pl.dims[l - 1]);
+        HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1]), M,
+                                        1.0f / (float)b, grad + pl.offB[l - 1], pl.Ppad, s));
+      }
+    } else {
+      HIPCHK(c, gemm(c, p, EPI_BWD, l));
+      ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
+      HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, s));
+    }
   }
   // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
   const float inv_b = 1.0f / (float)b;
@@ -447,9 +483,11 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     p.alpha = inv_b;
     if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
     HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
-    if (hb)
-      { ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
-  HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad, c->at<float>(pl.o_colpart), s)); }
+    if (hb && (!pl.bf16 || l == L)) {   // bf16 mode: layers below L got theirs from the backward epilogue
+      ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
+      HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad,
+                               c->at<float>(pl.o_colpart), s));
+    }
   }
   // inner products <g_i, gbar>
   StatsP sp;
@@ -467,9 +505,8 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
         p.E = act_ptr(pl.o_Dl[l]); p.sEg = cap * pl.ld[l]; p.lde = pl.ld[l];
         p.part = c->at<float>(pl.o_qpart[l - 1]);
         p.sPartg = cap * pl.qparts[l - 1]; p.sPartTile = cap;
-        HIPCHK(c, launch_fill_zero(p.part, (long long)M * cap * pl.qparts[l - 1] * 4, s));
         HIPCHK(c, gemm(c, p, EPI_IPDOT, l));
-        sp.qpart[l - 1] = p.part; sp.nparts[l - 1] = pl.qparts[l - 1];
+        sp.qpart[l - 1] = p.part; sp.nparts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l]);
         sp.sQg[l - 1] = p.sPartg; sp.sQpart[l - 1] = cap;
       } else {
         p.B = grad + pl.offW[l];
@@ -486,7 +523,11 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   }
   // statistics
   sp.L = L; sp.has_bias = hb ? 1 : 0; sp.groups = M; sp.b = b; sp.want_ip = pl.want_ip ? 1 : 0;
-  for (int l = 0; l < L; ++l) { sp.an[l] = c->at<float>(pl.o_an[l]); sp.dn[l] = c->at<float>(pl.o_dn[l + 1]); }
+  for (int l = 0; l < L; ++l) {
+    sp.an[l] = c->at<float>(pl.o_an[l]); sp.dn[l] = c->at<float>(pl.o_dn[l + 1]);
+    sp.an_parts[l] = an_parts[l]; sp.an_sg[l] = cap * pl.rparts[l];
+    sp.dn_parts[l] = dn_parts[l + 1]; sp.dn_sg[l] = cap * pl.rparts[l + 1];
+  }
   sp.sNg = cap;
   sp.loss = c->at<float>(pl.o_loss);
   sp.n_out = c->at<float>(pl.o_nout); sp.q_out = c->at<float>(pl.o_qout);
@@ -754,10 +795,10 @@ abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M
     p.Md = b; p.Nd = out_dims[l]; p.Kd = in_dims[l]; p.groups = M;
     p.E = delta_dev[l]; p.sEg = sd; p.lde = out_dims[l];
     p.part = reinterpret_cast<float *>(ws + off[9 + l]); p.sPartg = (long long)b * np; p.sPartTile = b;
-    HIPCHK(nc, launch_fill_zero(p.part, (long long)M * b * np * 4, s));
     HIPCHK(nc, launch_gemm_bf16(p, EPI_IPDOT, s));
-    sp.qpart[l] = p.part; sp.nparts[l] = np; sp.sQg[l] = p.sPartg; sp.sQpart[l] = b;
+    sp.qpart[l] = p.part; sp.nparts[l] = gemm_bf16_row_parts(b, out_dims[l]); sp.sQg[l] = p.sPartg; sp.sQpart[l] = b;
     sp.an[l] = an + (size_t)l * M * b; sp.dn[l] = dn + (size_t)l * M * b;
+    sp.an_parts[l] = sp.dn_parts[l] = 1; sp.an_sg[l] = sp.dn_sg[l] = b;
   }
   sp.L = L; sp.has_bias = 0; sp.groups = M; sp.b = b; sp.want_ip = 1; sp.sNg = b;
   sp.loss = loss;

@@ -31,6 +31,10 @@ struct GemmP {
   const float *bias; long long sBiasg;   // per-column vector (may be null)
   const void *E; long long sEg; int lde; // elementwise operand of the epilogue
   float *part; long long sPartg; long long sPartTile; // row partials: part[g][tile_n][m]
+                               //   EPI_IPDOT: the row dots; EPI_FWD_ACT / EPI_BWD (bf16 family, optional):
+                               //   sum over the tile's columns of the squared stored outputs
+  float *cpart; long long sCpartg;   // EPI_BWD (bf16 family, optional): column partials
+                               //   cpart[g][tile_m * WM + wave_m][n] = sum over the wave's rows of the stored outputs
   float alpha;
   int act;
   int pad_to_ld;               // also write zeros to columns [Nd, ldc) of C (and C2)
@@ -40,6 +44,10 @@ struct GemmP {
 // EPI_IPDOT writes per row (tiles along n) for the tile shape it picks.
 hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s);
 int gemm_bf16_ipdot_parts(int Nd);
+// Exact number of row partials (tiles along n) and of column-partial rows (tiles along m times
+// wave rows) that the bf16 family writes for an Md x Nd output.
+int gemm_bf16_row_parts(int Md, int Nd);
+int gemm_bf16_col_parts(int Md, int Nd);
 // Tile shape the bf16 family uses for an Md x Nd output: 0 = 128x64, 1 = 128x128, 2 = 256x256.
 int gemm_bf16_tile_shape(int Md, int Nd);
 // fp32 SIMT family (gemm_f32.hip); EPI_IPDOT is not offered (U is materialised instead).
@@ -66,6 +74,9 @@ hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, 
 enum { COLSUM_ROWS = 128 };
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups,
                           int b, float alpha, float *out, long long sOg, float *scratch, hipStream_t s);
+// second stage alone: out[g][j] = alpha * sum_r part[g][r][j], r < nsplit (partials from a GEMM epilogue)
+hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha,
+                                 float *out, long long sOg, hipStream_t s);
 // q[g][i] += sum_j D[g][i][j] * U[g][i][j]  (fp32 path of the inner products)
 hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U,
                              long long sUg, int ldu, int cols, int groups, int b, float *q,
@@ -73,8 +84,10 @@ hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float
 
 struct StatsP {
   int L, has_bias, groups, b, want_ip;
-  const float *an[16];      // [g][i] layer-input squared norms, stride sNg
-  const float *dn[16];      // [g][i] backprop-signal squared norms
+  const float *an[16];      // layer-input squared norms as an_parts[l] partial vectors:
+  const float *dn[16];      //   an[l][g * an_sg[l] + part * sNg + i]; likewise the backprop-signal norms
+  int an_parts[16], dn_parts[16];
+  long long an_sg[16], dn_sg[16];
   long long sNg;
   const float *qpart[16];   // per layer: [g][part][i]
   int nparts[16];

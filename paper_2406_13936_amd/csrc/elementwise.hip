@@ -203,7 +203,12 @@ __global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p) {
   for (int i = blockIdx.x * 256 + threadIdx.x; i < p.b; i += 256 * STATS_PBLK) {
     const long long o = (long long)g * p.sNg + i;
     float n = 0.0f;
-    for (int l = 0; l < p.L; ++l) n = fmaf(p.dn[l][o], p.an[l][o] + hb, n);
+    for (int l = 0; l < p.L; ++l) {
+      float a = 0.0f, d = 0.0f;
+      for (int k = 0; k < p.an_parts[l]; ++k) a += p.an[l][(long long)g * p.an_sg[l] + (long long)k * p.sNg + i];
+      for (int k = 0; k < p.dn_parts[l]; ++k) d += p.dn[l][(long long)g * p.dn_sg[l] + (long long)k * p.sNg + i];
+      n = fmaf(d, a + hb, n);
+    }
     if (p.n_out) p.n_out[o] = n;
     s1 += (double)n;
     sl += (double)p.loss[o];
@@ -448,6 +453,13 @@ hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int
     hipLaunchKernelGGL(col_sum_stage1<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
                        scratch, nsplit);
   hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, scratch, cols, nsplit,
+                     alpha, out, sOg);
+  return hipGetLastError();
+}
+
+hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha, float *out,
+                                 long long sOg, hipStream_t s) {
+  hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, part, cols, nsplit,
                      alpha, out, sOg);
   return hipGetLastError();
 }

@@ -284,9 +284,27 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
 
   if (EPI == EPI_FWD_ACT || EPI == EPI_BWD || EPI == EPI_IPDOT) __syncthreads();   // stages are dead
 
+  float *red = reinterpret_cast<float *>(smem + NW * 32 * SLD);   // [WN][BM] row partials of the waves
+  // add the WN waves' row partials in wave order and write part[g][tn][m]
+  auto finish_rows = [&]() {
+    __syncthreads();
+    float *part = p.part + (long long)g * p.sPartg + (long long)tn * p.sPartTile;
+    for (int r = tid; r < BM; r += NT) {
+      float v = 0.0f;
+#pragma unroll
+      for (int w = 0; w < WN; ++w) v += red[w * BM + r];
+      if (m0 + r < p.Md) part[m0 + r] = v;
+    }
+  };
+  // squares of the four bf16 values packed in pk
+  auto sq4 = [](uint2 pk) -> float {
+    const float a = __uint_as_float(pk.x << 16), b = __uint_as_float(pk.x & 0xffff0000u);
+    const float c = __uint_as_float(pk.y << 16), d = __uint_as_float(pk.y & 0xffff0000u);
+    return fmaf(a, a, fmaf(b, b, fmaf(c, c, d * d)));
+  };
+
   if (EPI == EPI_IPDOT) {
     const bf16_t *E = static_cast<const bf16_t *>(p.E) + (long long)g * p.sEg;
-    float *red = reinterpret_cast<float *>(smem + NW * 32 * SLD);   // [WN][BM] row partials
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int mrow0 = m0 + wm * TM + i * 32;
@@ -309,14 +327,7 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
       rs += __shfl_xor(rs, 32, 64);                               // the two column halves of the row
       if (lhalf == 0) red[wn * BM + wm * TM + i * 32 + lcol] = rs;
     }
-    __syncthreads();
-    float *part = p.part + (long long)g * p.sPartg + (long long)tn * p.sPartTile;
-    for (int r = tid; r < BM; r += NT) {
-      float v = 0.0f;
-#pragma unroll
-      for (int w = 0; w < WN; ++w) v += red[w * BM + r];
-      if (m0 + r < p.Md) part[m0 + r] = v;
-    }
+    finish_rows();
     return;
   }
 
@@ -328,6 +339,7 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
     for (int i = 0; i < MI; ++i) {
       const int mrow0 = m0 + wm * TM + i * 32;
       uint2 dpk[NI][4];
+      float rs = 0.0f;
 #pragma unroll
       for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -343,7 +355,12 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
           apk.x = pack2bf(a4[0], a4[1]); apk.y = pack2bf(a4[2], a4[3]);
           dpk[j][q].x = pack2bf(d4[0], d4[1]); dpk[j][q].y = pack2bf(d4[2], d4[3]);
           *reinterpret_cast<uint2 *>(piece(j, q)) = apk;
+          rs += sq4(apk);
         }
+      if (p.part) {
+        rs += __shfl_xor(rs, 32, 64);
+        if (lhalf == 0) red[wn * BM + wm * TM + i * 32 + lcol] = rs;
+      }
       stage_out(C, p.ldc, mrow0, ncols);
       if (ACT == ACT_GELU && C2) {
 #pragma unroll
@@ -353,6 +370,7 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
         stage_out(C2, p.ldc2, mrow0, ncols);
       }
     }
+    if (p.part) finish_rows();
     return;
   }
 
@@ -360,10 +378,19 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
     bf16_t *C = static_cast<bf16_t *>(p.C) + (long long)g * p.sCg;
     const bf16_t *E = static_cast<const bf16_t *>(p.E) + (long long)g * p.sEg;
     const int ncols = p.pad_to_ld ? p.ldc : p.Nd;
+    float cs[NI][4][4];                                  // column sums over this wave's rows
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[j][q][e] = 0.0f;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int mrow0 = m0 + wm * TM + i * 32;
+      const bool row_in = mrow0 + lcol < p.Md;
       if (ACT != ACT_NONE) stage_in(E, p.lde, mrow0, p.Nd);
+      float rs = 0.0f;
 #pragma unroll
       for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -385,9 +412,35 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
           uint2 opk;
           opk.x = pack2bf(o4[0], o4[1]); opk.y = pack2bf(o4[2], o4[3]);
           *reinterpret_cast<uint2 *>(piece(j, q)) = opk;      // each lane overwrites the piece it read
+          rs += sq4(opk);
+          if (p.cpart && row_in) {                            // rows beyond the batch hold no signal
+            cs[j][q][0] += __uint_as_float(opk.x << 16); cs[j][q][1] += __uint_as_float(opk.x & 0xffff0000u);
+            cs[j][q][2] += __uint_as_float(opk.y << 16); cs[j][q][3] += __uint_as_float(opk.y & 0xffff0000u);
+          }
         }
+      if (p.part) {
+        rs += __shfl_xor(rs, 32, 64);
+        if (lhalf == 0) red[wn * BM + wm * TM + i * 32 + lcol] = rs;
+      }
       stage_out(C, p.ldc, mrow0, ncols);
     }
+    if (p.cpart) {
+      // add over the 32 lanes that share a column group (fixed order: xor butterfly)
+      float *cp = p.cpart + (long long)g * p.sCpartg + (long long)(tm * WM + wm) * p.Nd;
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float v = cs[j][q][e];
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
+            if (lcol == 0 && n < p.Nd) cp[n] = v;
+          }
+    }
+    if (p.part) finish_rows();
     return;
   }
 
@@ -483,6 +536,17 @@ int gemm_bf16_tile_shape(int Md, int Nd) {
   if (Nd <= 64) return 0;
   if (Md >= 1024 && Nd >= 1024) return 2;
   return 1;
+}
+
+int gemm_bf16_row_parts(int Md, int Nd) {
+  const int bn[3] = {64, 128, 256};
+  return (Nd + bn[gemm_bf16_tile_shape(Md, Nd)] - 1) / bn[gemm_bf16_tile_shape(Md, Nd)];
+}
+
+int gemm_bf16_col_parts(int Md, int Nd) {
+  const int bm[3] = {128, 128, 256}, wm[3] = {4, 2, 2};
+  const int sh = gemm_bf16_tile_shape(Md, Nd);
+  return (Md + bm[sh] - 1) / bm[sh] * wm[sh];
 }
 
 int gemm_bf16_ipdot_parts(int Nd) {
