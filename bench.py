@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--adaptive", action="store_true", help="start at b0 and let the test grow b")
     ap.add_argument("--batch", type=int, default=0, help="fixed local batch size (default: the cap)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="also run the library's plain copy kernel once on 2 x 1 GiB (the known-traffic "
+                         "reference for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     return ap.parse_args()
 
@@ -123,6 +126,14 @@ def main():
             rep.average_replicas()
         return nb
 
+    if a.pmc_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        src.zero_()
+        A.copy_probe(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     b = w.b0 if a.adaptive else b_fixed
     for s in range(a.warmup):
         nb = run(s, b)
@@ -162,6 +173,17 @@ def main():
                 "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
                 "avg_launch_ms": v["total_ms"] / v["calls"], "launches": v["calls"],
                 "flops_per_launch": v["flops"] / v["calls"]}
+        # HBM bytes per launch from the committed rocprofv3 --pmc summary of this same command
+        # (FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel); null when no summary covers it
+        tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.json" % a.workload)
+        if os.path.exists(tpath) and not a.adaptive and not a.batch:
+            try:
+                tj = json.load(open(tpath))
+                if name in tj.get("kernels", {}):
+                    roof["traffic"] = tj["kernels"][name]["hbm_bytes_per_launch"]
+                    roof["traffic_source"] = "profiles/" + os.path.basename(tpath)
+            except Exception:
+                pass
         allf = sum(v["flops"] for v in gemms.values())
         allt = sum(v["total_ms"] for v in gemms.values())
         roof["all_gemms_tflops"] = allf / (allt * 1e-3) / 1e12

@@ -204,6 +204,11 @@ typedef struct {
 abs_status abs_profile_enable(abs_ctx *ctx, int on);
 abs_status abs_profile_read(abs_ctx *ctx, int max_entries, abs_profile_entry *out, int *n_entries);
 
+/* Plain device-to-device copy kernel (one 16-byte vector per thread), bytes a multiple of 16,
+ * both pointers 16-byte aligned.  It moves a known number of bytes, so its hardware-counter
+ * readings are the reference that the counters of the other kernels are scaled by. */
+abs_status abs_copy_probe(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream);
+
 abs_status abs_destroy(abs_ctx *ctx);
 const char *abs_last_error(const abs_ctx *ctx);   /* ctx may be NULL: last error of this thread */
 

@@ -826,6 +826,15 @@ abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M
   return ABS_OK;
 }
 
+abs_status abs_copy_probe(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream) {
+  if (!src_dev || !dst_dev) return fail(ABS_EINVAL, "NULL argument");
+  if (bytes < 16 || (bytes % 16) || ((reinterpret_cast<uintptr_t>(src_dev) | reinterpret_cast<uintptr_t>(dst_dev)) & 15))
+    return fail(ABS_EINVAL, "bytes must be a positive multiple of 16 and the pointers 16-byte aligned");
+  abs_ctx *nc = nullptr;
+  HIPCHK(nc, launch_copy_probe(src_dev, dst_dev, bytes, static_cast<hipStream_t>(hip_stream)));
+  return ABS_OK;
+}
+
 abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *hip_stream) {
   if (!params_dev) return fail(ABS_EINVAL, "params_dev is NULL");
   if (M < 1 || n < 8 || (n % 8)) return fail(ABS_EINVAL, "M < 1 or n not a positive multiple of 8");

@@ -114,5 +114,6 @@ hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s
 hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials,
                                double *out, hipStream_t s);
 hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);
+hipError_t launch_copy_probe(const void *src, void *dst, long long bytes, hipStream_t s);
 
 }  // namespace absk

@@ -384,6 +384,14 @@ __global__ void __launch_bounds__(256) cross_worker_final_kernel(const double *_
   }
 }
 
+// Plain copy of n16 16-byte vectors, one per thread: the known-traffic reference that hardware
+// counters are scaled by.
+__global__ void __launch_bounds__(256) copy_probe_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                         long long n16) {
+  const long long i = blockIdx.x * 256LL + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
 __global__ void fill_zero_kernel(uint4 *p, long long n16) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n16; i += stride)
@@ -513,6 +521,14 @@ hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, doubl
                                hipStream_t s) {
   hipLaunchKernelGGL(cross_worker_kernel, dim3(STATS_PBLK), dim3(256), 0, s, g, groups, Ppad, partials);
   hipLaunchKernelGGL(cross_worker_final_kernel, dim3(1), dim3(256), 0, s, partials, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_probe(const void *src, void *dst, long long bytes, hipStream_t s) {
+  const long long n16 = bytes / 16;
+  if (n16 <= 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
+                     static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
   return hipGetLastError();
 }
 
