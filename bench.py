@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=16)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4"])
+    ap.add_argument("--workload", default="config3", choices=["config1", "config2", "config3", "config4", "config5"])
     ap.add_argument("--adaptive", action="store_true", help="start at b0 and let the test grow b")
     ap.add_argument("--batch", type=int, default=0, help="fixed local batch size (default: the cap)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -72,6 +72,61 @@ def cpu_baseline(w, X, y, x0, sample_b):
                       f"({dt:.1f} s, fp64 numpy, bf16 rounding points emulated)"}
 
 
+def stats_stress(a, np, torch, A, W):
+    """Statistics and averaging alone (no model run): M = 32 replicas of 4 stacked 4096x4096
+    layers in bf16 at b = 8192; per-sample squared gradient norms, ||gbar||^2, <g_i, gbar> for every
+    replica, then the 32-way average of the bf16 parameters (4.3 GB)."""
+    from concurrent.futures import ThreadPoolExecutor
+    M, L, b, d = 32, 4, a.batch or 8192, 4096
+    dev = torch.device("cuda")
+    a_list = [torch.empty((M, b, d), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    d_list = [torch.empty((M, b, d), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+
+    def gen(ml):
+        m, l = ml
+        return ml, W.stats_stress_layer(0, m, l, b, d, d)
+
+    with ThreadPoolExecutor(16) as ex:
+        for (m, l), (av, dv) in ex.map(gen, [(m, l) for m in range(M) for l in range(L)]):
+            a_list[l][m].copy_(torch.from_numpy(av).to(dev))
+            d_list[l][m].copy_(torch.from_numpy(dv).to(dev))
+    params = torch.empty((M, L * d * d), dtype=torch.bfloat16, device=dev)
+    rng = np.random.default_rng(5)
+    for m in range(M):
+        params[m].copy_(torch.from_numpy(rng.standard_normal(L * d * d, dtype=np.float32) / 64).to(dev))
+    torch.cuda.synchronize()
+    for _ in range(max(1, a.warmup)):
+        A.layer_stats(a_list, d_list)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        res, _, _, _ = A.layer_stats(a_list, d_list)
+    torch.cuda.synchronize()
+    dt_stats = (time.perf_counter() - t0) / a.steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    A.average_bf16(params)
+    e0.record()
+    for _ in range(a.steps):
+        A.average_bf16(params)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_avg = e0.elapsed_time(e1) / a.steps
+    avg_bytes = 2.0 * M * L * d * d * 2
+    flops = 2.0 * 2 * M * L * b * d * d                 # weight-gradient + inner-product contractions
+    return {
+        "metric": "statistics-only samples/sec (all replicas) + replica-average GB/s",
+        "value": M * b / dt_stats, "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt_stats * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg5_stats_stress", "M": M, "layers": L, "width": d, "local_batch": b},
+        "roofline": {"bound": "hbm", "kernel": "average_bf16_kernel", "achieved": avg_bytes / (ms_avg * 1e-3) / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": avg_bytes / (ms_avg * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": None, "avg_launch_ms": ms_avg},
+        "stats_gemm_tflops": flops / dt_stats / 1e12,
+        "check": {"S1_replica0": res[0].sum_sq, "S2_replica0": res[0].gbar_sq},
+    }
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -86,6 +141,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(3)
+    if a.workload == "config5":
+        print(json.dumps(stats_stress(a, np, torch, A, W)))
+        return
     w = getattr(W, a.workload)()
     X, y = W.make_dataset(w)
     x0 = W.make_x0(w)

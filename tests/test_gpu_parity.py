@@ -401,3 +401,43 @@ def test_statistics_alone_on_stacked_layers_and_bf16_average():
         bad = got[m] != want
         # fp32 summation may differ from fp64 in the last bf16 digit only on exact ties
         assert bad.mean() < 1e-3 and np.abs(got[m] - want).max() <= 2 ** -7 * np.abs(want).max()
+
+
+def test_statistics_alone_on_wide_layers_large_tiles():
+    """Two replicas of two 2048-wide stacked layers at b = 1100: the weight-gradient and the
+    inner-product contractions run in the 256x256 tile shape of the statistics stress workload."""
+    import torch
+    A = _A()
+    M, b, din, dout = 2, 1100, (2048, 1024), (1024, 2048)
+    a_list, d_list = [], []
+    for l in range(2):
+        a = np.stack([W.stats_stress_layer(1, m, l, b, din[l], dout[l])[0] for m in range(M)])
+        d = np.stack([W.stats_stress_layer(1, m, l, b, din[l], dout[l])[1] for m in range(M)])
+        a_list.append(torch.from_numpy(a).cuda().to(torch.bfloat16).contiguous())
+        d_list.append(torch.from_numpy(d).cuda().to(torch.bfloat16).contiguous())
+    res, n, q, gbar = A.layer_stats(a_list, d_list, want_per_sample=True, want_gbar=True)
+    n, q, gbar = n.cpu().numpy(), q.cpu().numpy(), gbar.cpu().numpy()
+    for m in range(M):
+        av = [a_list[l][m].float().cpu().numpy().astype(np.float64) for l in range(2)]
+        dv = [d_list[l][m].float().cpu().numpy().astype(np.float64) for l in range(2)]
+        G = [dv[l].T @ av[l] / b for l in range(2)]
+        n_o = sum((dv[l] ** 2).sum(1) * (av[l] ** 2).sum(1) for l in range(2))
+        q_o = sum((dv[l] * (av[l] @ O.bf16_round(G[l]).T)).sum(1) for l in range(2))
+        S2 = sum((G[l] ** 2).sum() for l in range(2))
+        np.testing.assert_allclose(n[m], n_o, rtol=1e-4)
+        np.testing.assert_allclose(q[m], q_o, rtol=2e-3, atol=2e-4 * np.abs(q_o).max())
+        gflat = np.concatenate([g.ravel() for g in G])
+        assert np.abs(gbar[m] - gflat).max() <= 1e-4 * np.abs(gflat).max()
+        assert _rel(res[m].sum_sq, n_o.sum()) <= 1e-4
+        assert _rel(res[m].gbar_sq, S2) <= 1e-4
+        assert _rel(res[m].sum_q, q_o.sum()) <= 1e-3
+        assert _rel(res[m].sum_q2, (q_o ** 2).sum()) <= 1e-3
+    # 32-way bf16 average of a larger block
+    rng = np.random.default_rng(2)
+    p = torch.from_numpy(rng.normal(size=(32, 1 << 16)).astype(np.float32)).cuda().to(torch.bfloat16).contiguous()
+    ref = p.float().cpu().numpy().astype(np.float64)
+    A.average_bf16(p)
+    want = O.bf16_round(ref.sum(axis=0) / 32)
+    got = p.float().cpu().numpy()
+    for m in (0, 17, 31):
+        assert (got[m] != want).mean() < 2e-3 and np.abs(got[m] - want).max() <= 2 ** -7 * np.abs(want).max()
