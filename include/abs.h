@@ -50,7 +50,8 @@ typedef enum {
 } abs_status;
 
 enum { ABS_ACT_NONE = 0, ABS_ACT_RELU = 1, ABS_ACT_GELU = 2 };   /* GELU: exact erf form */
-enum { ABS_OPT_SGD = 0, ABS_OPT_SHB = 1, ABS_OPT_ADAMW = 2 };
+enum { ABS_OPT_SGD = 0, ABS_OPT_SHB = 1, ABS_OPT_ADAMW = 2,   /* Adam = AdamW with weight_decay 0 */
+       ABS_OPT_ADAGRAD = 3 };                                   /* v <- v + g^2 ; x <- x - lr g / (sqrt v + eps) */
 enum { ABS_PREC_F32 = 0,    /* fp32 operands and accumulation */
        ABS_PREC_BF16 = 1 }; /* bf16 operands, fp32 accumulation, fp32 master weights */
 enum { ABS_STATS_NORM = 1,  /* sum_i ||g_i||^2 and ||gbar||^2 (norm test) */
@@ -163,6 +164,12 @@ abs_status abs_get_grad(abs_ctx *ctx, int m, float *out_host);    /* last local 
 /* Per-sample ||g_i||^2 (and <g_i,gbar> if gathered; else q_host may be NULL) of worker m
  * for the most recent step: host, b floats each. */
 abs_status abs_get_per_sample(abs_ctx *ctx, int m, float *n_host, float *q_host);
+
+/* Learning-rate schedule of the paper's experiments (Sec. 6.1): linear warm-up to `peak` over the
+ * first warmup_steps local steps (lr = peak (step+1)/warmup_steps), then cosine decay to `floor`,
+ * reached at total_steps.  Pure host function; abs_local_step takes the rate per call. */
+abs_status abs_lr_schedule(long long step, long long total_steps, long long warmup_steps, double peak,
+                           double floor, double *lr /*host*/);
 
 /* Number of parameters of cfg's network (host only, no GPU call). */
 abs_status abs_n_params(const abs_config *cfg, int64_t *n /*host*/);

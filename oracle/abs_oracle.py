@@ -15,6 +15,8 @@ for Distributed Local Gradient Methods"):
 * batch-size rule, ceiling of the ratio     -- eqs. (norm_test), (test_stat)
 * common size = max over workers            -- unnumbered display after (test_stat)
 * the loop itself                           -- Appendix "Main Algorithm", Alg. 1
+* inner optimizers beyond SGD (momentum SGD, AdaGrad, Adam, AdamW are named, not written out)
+                                            -- Sec. 4.2, last paragraph; warm-up + cosine schedule: Sec. 6.1
 * cross-worker estimator / once-per-round   -- Sec. 4.3 and Alg. 2
 
 The (augmented) inner-product test is only *named* by the paper (end of
@@ -50,7 +52,7 @@ import numpy as np
 from scipy.special import erf
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
-OPT_SGD, OPT_SHB, OPT_ADAMW = 0, 1, 2
+OPT_SGD, OPT_SHB, OPT_ADAMW, OPT_ADAGRAD = 0, 1, 2, 3
 TEST_NORM, TEST_IP, TEST_AUG_IP = 0, 1, 2
 
 
@@ -349,7 +351,22 @@ def opt_step(x, g, st: OptState, opt: int, lr: float, momentum=0.0, beta1=0.9,
         mhat = st.m / (1.0 - beta1 ** st.t)
         vhat = st.v / (1.0 - beta2 ** st.t)
         return x * (1.0 - lr * weight_decay) - lr * mhat / (np.sqrt(vhat) + eps)
+    if opt == OPT_ADAGRAD:                   # v <- v + g^2 ; x <- x - lr g / (sqrt(v) + eps)
+        st.v = st.v + g * g
+        den = np.sqrt(st.v) + eps            # zero only where no gradient has ever arrived: no move
+        return x - lr * np.divide(g, den, out=np.zeros_like(x), where=den > 0)
     raise ValueError(opt)
+
+
+def lr_schedule(step: int, total_steps: int, warmup_steps: int, peak: float, floor: float) -> float:
+    """Linear warm-up to `peak` over the first warmup_steps steps, then cosine decay to `floor`
+    at total_steps (the schedule of the paper's experiments, Sec. 6.1 / hyper-parameter tables)."""
+    if step < warmup_steps:
+        return peak * (step + 1) / warmup_steps
+    if step >= total_steps:
+        return floor
+    t = (step - warmup_steps) / max(1, total_steps - warmup_steps)
+    return floor + 0.5 * (peak - floor) * (1.0 + math.cos(math.pi * t))
 
 
 def average(xs: np.ndarray) -> np.ndarray:

@@ -24,7 +24,7 @@ EXPORTS = [
     "abs_average_replicas", "abs_get_params", "abs_set_params", "abs_get_grad",
     "abs_get_per_sample", "abs_n_params", "abs_layer_stats",
     "abs_layer_stats_workspace_bytes", "abs_average_bf16", "abs_destroy", "abs_last_error",
-    "abs_profile_enable", "abs_profile_read", "abs_copy_probe",
+    "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
 ]
 
 
@@ -93,6 +93,8 @@ def load_library(reload: bool = False):
                                                     C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     lib.abs_average_bf16.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
     lib.abs_destroy.argtypes = [C.c_void_p]
+    lib.abs_lr_schedule.argtypes = [C.c_longlong, C.c_longlong, C.c_longlong, C.c_double, C.c_double,
+                                    C.POINTER(C.c_double)]
     lib.abs_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.abs_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.abs_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(ProfileEntry), C.POINTER(C.c_int)]
@@ -272,6 +274,14 @@ def layer_stats(a_list, delta_list, want_per_sample: bool = False, want_gbar: bo
                                q_out.data_ptr() if want_per_sample else None,
                                gbar.data_ptr() if want_gbar else None))
     return list(out), n_out, q_out, gbar
+
+
+def lr_schedule(step: int, total_steps: int, warmup_steps: int, peak: float, floor: float) -> float:
+    lib = load_library()
+    out = C.c_double(0.0)
+    _check(lib.abs_lr_schedule(int(step), int(total_steps), int(warmup_steps), float(peak), float(floor),
+                               C.byref(out)))
+    return out.value
 
 
 def copy_probe(src, dst):

@@ -54,7 +54,7 @@ abs_status check_cfg(const abs_config *c) {
   if (c->M < 1) return fail(ABS_EINVAL, "M < 1");
   if (c->b_cap < 2) return fail(ABS_EINVAL, "b_cap < 2");
   if (c->act < ABS_ACT_NONE || c->act > ABS_ACT_GELU) return fail(ABS_EINVAL, "unknown activation");
-  if (c->opt < ABS_OPT_SGD || c->opt > ABS_OPT_ADAMW) return fail(ABS_EINVAL, "unknown optimizer");
+  if (c->opt < ABS_OPT_SGD || c->opt > ABS_OPT_ADAGRAD) return fail(ABS_EINVAL, "unknown optimizer");
   if (c->prec != ABS_PREC_F32 && c->prec != ABS_PREC_BF16) return fail(ABS_EINVAL, "unknown precision");
   if (!(c->stats_mask & ABS_STATS_NORM)) return fail(ABS_EINVAL, "stats_mask needs ABS_STATS_NORM");
   if (c->prec == ABS_PREC_BF16)
@@ -266,6 +266,21 @@ abs_status read_stats(abs_ctx *c) {
 extern "C" {
 
 const char *abs_last_error(const abs_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+abs_status abs_lr_schedule(long long step, long long total_steps, long long warmup_steps, double peak, double floor,
+                           double *lr) {
+  if (!lr) return fail(ABS_EINVAL, "lr is NULL");
+  if (step < 0 || total_steps < 1 || warmup_steps < 0 || warmup_steps > total_steps)
+    return fail(ABS_EINVAL, "need 0 <= step, 0 <= warmup_steps <= total_steps, total_steps >= 1");
+  const double kPi = 3.14159265358979323846;
+  if (step < warmup_steps) *lr = peak * (double)(step + 1) / (double)warmup_steps;
+  else if (step >= total_steps) *lr = floor;
+  else {
+    const long long span = total_steps - warmup_steps > 1 ? total_steps - warmup_steps : 1;
+    *lr = floor + 0.5 * (peak - floor) * (1.0 + std::cos(kPi * (double)(step - warmup_steps) / (double)span));
+  }
+  return ABS_OK;
+}
 
 abs_status abs_n_params(const abs_config *cfg, int64_t *n) {
   if (!n) return fail(ABS_EINVAL, "n is NULL");
@@ -550,7 +565,7 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     up.c1 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta1, (double)c->t)));
     up.c2 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta2, (double)c->t)));
   }
-  { ProfScope ps_(c, T_UPDATE, 0.0, 1.0 * M * pl.P * (c->cfg.opt == ABS_OPT_SGD ? 12 : c->cfg.opt == ABS_OPT_SHB ? 20 : 28) + (pl.bf16 ? 2.0 * M * pl.P : 0.0));
+  { ProfScope ps_(c, T_UPDATE, 0.0, 1.0 * M * pl.P * (c->cfg.opt == ABS_OPT_SGD ? 12 : c->cfg.opt == ABS_OPT_ADAMW ? 28 : 20) + (pl.bf16 ? 2.0 * M * pl.P : 0.0));
   HIPCHK(c, launch_update(up, s)); }
   c->last_b = b;
   c->have_stats = true;

@@ -9,7 +9,7 @@ namespace absk {
 typedef uint16_t bf16_t;   // raw bfloat16 bits in memory
 
 enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
-enum { OPT_SGD = 0, OPT_SHB = 1, OPT_ADAMW = 2 };
+enum { OPT_SGD = 0, OPT_SHB = 1, OPT_ADAMW = 2, OPT_ADAGRAD = 3 };
 
 // Epilogues of the grouped GEMM  C[g][m][n] = sum_k A[g][m][k] * B[g][n][k].
 enum {

@@ -283,6 +283,16 @@ __global__ void __launch_bounds__(256) update_kernel(const UpdateP p) {
         xs[k] = fmaf(-p.lr, vs[k], xs[k]);
       }
       reinterpret_cast<float4 *>(p.v)[i] = make_float4(vs[0], vs[1], vs[2], vs[3]);
+    } else if (OPT == OPT_ADAGRAD) {
+      float4 v = reinterpret_cast<float4 *>(p.v)[i];
+      float vs[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        vs[k] = fmaf(gs[k], gs[k], vs[k]);
+        const float den = sqrtf(vs[k]) + p.eps;          // den == 0 only where no gradient has ever arrived
+        if (den > 0.f) xs[k] = xs[k] - p.lr * gs[k] / den;
+      }
+      reinterpret_cast<float4 *>(p.v)[i] = make_float4(vs[0], vs[1], vs[2], vs[3]);
     } else {
       float4 v = reinterpret_cast<float4 *>(p.v)[i];
       float4 m = reinterpret_cast<float4 *>(p.m)[i];
@@ -500,6 +510,7 @@ hipError_t launch_update(const UpdateP &p, hipStream_t s) {
   } while (0)
   if (p.opt == OPT_SGD) ABS_UPD(OPT_SGD);
   else if (p.opt == OPT_SHB) ABS_UPD(OPT_SHB);
+  else if (p.opt == OPT_ADAGRAD) ABS_UPD(OPT_ADAGRAD);
   else ABS_UPD(OPT_ADAMW);
 #undef ABS_UPD
   return hipGetLastError();

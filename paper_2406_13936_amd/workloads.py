@@ -18,7 +18,7 @@ from typing import Optional, Tuple
 import numpy as np
 
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
-OPT_SGD, OPT_SHB, OPT_ADAMW = 0, 1, 2
+OPT_SGD, OPT_SHB, OPT_ADAMW, OPT_ADAGRAD = 0, 1, 2, 3
 TEST_NORM, TEST_IP, TEST_AUG_IP = 0, 1, 2
 PREC_F32, PREC_BF16 = 0, 1
 

@@ -67,3 +67,13 @@ def test_config_validation_without_a_gpu():
     assert p.value == 20 * 16 + 16 + 16 * 4 + 4
     cfg.b_cap = 1
     assert lib.abs_workspace_bytes(C.byref(cfg), 100, C.byref(n)) == 1      # ABS_EINVAL
+
+
+def test_lr_schedule_matches_oracle_on_the_host():
+    from paper_2406_13936_amd import binding as B
+    from oracle import abs_oracle as O
+    for s in (0, 1, 49, 50, 51, 300, 999, 1000, 1200):
+        assert B.lr_schedule(s, 1000, 50, 0.05, 0.005) == pytest.approx(O.lr_schedule(s, 1000, 50, 0.05, 0.005),
+                                                                         rel=1e-14)
+    with pytest.raises(B.AbsError):
+        B.lr_schedule(3, 10, 20, 0.1, 0.01)

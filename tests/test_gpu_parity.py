@@ -284,9 +284,9 @@ def test_scaled_twin_lockstep(cfg):
 
 
 def test_fp32_free_running_twin_with_heavy_ball_and_adamw():
-    for opt in (W.OPT_SHB, W.OPT_ADAMW):
+    for opt in (W.OPT_SHB, W.OPT_ADAMW, W.OPT_ADAGRAD):
         w = W.Workload("free", (64, 48, 10), W.ACT_GELU, True, W.PREC_F32, N=2048, M=3, H=3, rounds=4,
-                       b0=8, b_cap=128, opt=opt, lr=0.05 if opt == W.OPT_SHB else 2e-3, momentum=0.9,
+                       b0=8, b_cap=128, opt=opt, lr={W.OPT_SHB: 0.05, W.OPT_ADAMW: 2e-3, W.OPT_ADAGRAD: 0.02}[opt], momentum=0.9,
                        weight_decay=0.05, test=W.TEST_NORM, eta=0.6, data="teacher_mlp", seed=5)
         _lockstep(w, w.rounds, stat_tol=2e-4, band=2e-4, resync_params=False, param_tol=1e-3)
 

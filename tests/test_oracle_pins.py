@@ -305,3 +305,28 @@ def test_mixed_mode_stays_close_to_exact():
     mx = O.stats_factored(net, O.backprop(net, x, Xb, yb, mixed=True), True, mixed=True)
     for key in ("S1", "S2", "S3", "S4"):
         assert mx[key] == pytest.approx(ex[key], rel=2e-2), key
+
+
+def test_adagrad_closed_forms():
+    # first step: x - lr g / (|g| + eps); two steps by hand on a scalar
+    rng = np.random.default_rng(18)
+    x, g = rng.normal(size=12), rng.normal(size=12)
+    x1 = O.opt_step(x, g, O.OptState(12), O.OPT_ADAGRAD, 0.1, eps=1e-8)
+    np.testing.assert_allclose(x1, x - 0.1 * g / (np.abs(g) + 1e-8), rtol=1e-13)
+    st, y = O.OptState(1), np.array([1.0])
+    y = O.opt_step(y, np.array([3.0]), st, O.OPT_ADAGRAD, 0.5, eps=0.0)      # v = 9  -> 1 - 0.5*3/3 = 0.5
+    assert y[0] == pytest.approx(0.5)
+    y = O.opt_step(y, np.array([4.0]), st, O.OPT_ADAGRAD, 0.5, eps=0.0)      # v = 25 -> 0.5 - 0.5*4/5 = 0.1
+    assert y[0] == pytest.approx(0.1)
+
+
+def test_lr_schedule_endpoints_and_shape():
+    peak, floor, total, warm = 0.05, 0.005, 1000, 100
+    f = lambda s: O.lr_schedule(s, total, warm, peak, floor)
+    assert f(0) == pytest.approx(peak / warm) and f(warm - 1) == pytest.approx(peak)
+    assert f(warm) == pytest.approx(peak) and f(total) == floor and f(total + 5) == floor
+    assert f(warm + (total - warm) // 2) == pytest.approx(0.5 * (peak + floor))   # cosine midpoint
+    vals = [f(s) for s in range(total + 1)]
+    assert all(a <= b + 1e-15 for a, b in zip(vals[:warm], vals[1:warm]))          # warm-up rises
+    assert all(a >= b - 1e-15 for a, b in zip(vals[warm:], vals[warm + 1:]))       # then decays
+    assert min(vals[warm:]) >= floor - 1e-15
