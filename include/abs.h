@@ -127,6 +127,14 @@ abs_status abs_local_step(abs_ctx *ctx, const int32_t *idx_dev, int b, float lr)
 abs_status abs_norm_test(abs_ctx *ctx, double eta, abs_test_result *out);
 
 /*
+ * The same test with the finite-population factor of Sec. 4.1's estimate of delta_B^2 (a batch
+ * of b drawn from n samples without replacement): Var is multiplied by (n - b)/(n - 1), taken
+ * at the current b, before the comparison and the ceiling.  n_total >= b, n_total >= 2.
+ * n_total == b gives Var = 0 (the batch is the whole population), so the rule keeps b.
+ */
+abs_status abs_norm_test_fpc(abs_ctx *ctx, double eta, int64_t n_total, abs_test_result *out);
+
+/*
  * Inner-product test of the adaptive-sampling literature the paper cites (named at the end
  * of its Sec. 4.1), applied per worker to its own batch:
  *   Var_q = sample variance of q_i = <g_i,gbar>;  condition Var_q/b <= theta^2 S2^2;
@@ -164,6 +172,9 @@ abs_status abs_get_grad(abs_ctx *ctx, int m, float *out_host);    /* last local 
 /* Per-sample ||g_i||^2 (and <g_i,gbar> if gathered; else q_host may be NULL) of worker m
  * for the most recent step: host, b floats each. */
 abs_status abs_get_per_sample(abs_ctx *ctx, int m, float *n_host, float *q_host);
+
+/* Linear scaling of the learning rate with the batch size (Sec. 6.1): lr_ref * b / b_ref. */
+abs_status abs_lr_linear_scaling(double lr_ref, int64_t b, int64_t b_ref, double *lr /*host*/);
 
 /* Learning-rate schedule of the paper's experiments (Sec. 6.1): linear warm-up to `peak` over the
  * first warmup_steps local steps (lr = peak (step+1)/warmup_steps), then cosine decay to `floor`,

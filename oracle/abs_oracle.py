@@ -278,9 +278,14 @@ def _ceil_ratio(num: float, den: float, b: int) -> Tuple[float, int]:
     return r, int(math.ceil(r))
 
 
-def norm_test(var: float, S2: float, b: int, eta: float) -> dict:
+def norm_test(var: float, S2: float, b: int, eta: float, n_total: int = 0) -> dict:
     """Approximate norm test, eq. (approx_norm): var/b <= eta^2 ||gbar||^2;
-    statistic T = ceil(var / (eta^2 ||gbar||^2)), eq. (norm_test) / Alg. 1."""
+    statistic T = ceil(var / (eta^2 ||gbar||^2)), eq. (norm_test) / Alg. 1.
+    With n_total > 0 the variance carries the finite-population factor (n - b)/(n - 1) of the
+    estimate of delta_B^2 in Sec. 4.1 (sampling b of n without replacement), taken at the
+    current b."""
+    if n_total > 0:
+        var = var * (n_total - b) / (n_total - 1)
     ratio, T = _ceil_ratio(var, eta * eta * S2, b)
     return {"lhs": var / b, "rhs": eta * eta * S2, "ratio": ratio, "T": T,
             "pass": bool(var / b <= eta * eta * S2)}
@@ -367,6 +372,12 @@ def lr_schedule(step: int, total_steps: int, warmup_steps: int, peak: float, flo
         return floor
     t = (step - warmup_steps) / max(1, total_steps - warmup_steps)
     return floor + 0.5 * (peak - floor) * (1.0 + math.cos(math.pi * t))
+
+
+def lr_linear_scaling(lr_ref: float, b: int, b_ref: int) -> float:
+    """Linear scaling of the learning rate with the batch size (Sec. 6.1, constant-batch
+    baselines): lr = lr_ref * b / b_ref."""
+    return lr_ref * b / b_ref
 
 
 def average(xs: np.ndarray) -> np.ndarray:

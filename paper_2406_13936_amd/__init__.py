@@ -5,7 +5,8 @@ __graft_entry__.build()).  PyTorch is used only for device memory and the stream
 There is no CPU fallback: without the built library every call raises.
 """
 from .binding import (Replicas, TestResult, average_bf16, copy_probe, layer_stats, load_library,
-                      lr_schedule, next_batch_size, AbsError)
+                      lr_linear_scaling, lr_schedule, next_batch_size, AbsError)
 
-__all__ = ["Replicas", "TestResult", "average_bf16", "copy_probe", "layer_stats", "load_library", "lr_schedule",
+__all__ = ["Replicas", "TestResult", "average_bf16", "copy_probe", "layer_stats", "load_library", "lr_linear_scaling",
+           "lr_schedule",
            "next_batch_size", "AbsError"]

@@ -25,6 +25,7 @@ EXPORTS = [
     "abs_get_per_sample", "abs_n_params", "abs_layer_stats",
     "abs_layer_stats_workspace_bytes", "abs_average_bf16", "abs_destroy", "abs_last_error",
     "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
+    "abs_lr_linear_scaling", "abs_norm_test_fpc",
 ]
 
 
@@ -95,6 +96,8 @@ def load_library(reload: bool = False):
     lib.abs_destroy.argtypes = [C.c_void_p]
     lib.abs_lr_schedule.argtypes = [C.c_longlong, C.c_longlong, C.c_longlong, C.c_double, C.c_double,
                                     C.POINTER(C.c_double)]
+    lib.abs_lr_linear_scaling.argtypes = [C.c_double, C.c_int64, C.c_int64, C.POINTER(C.c_double)]
+    lib.abs_norm_test_fpc.argtypes = [C.c_void_p, C.c_double, C.c_int64, C.POINTER(TestResult)]
     lib.abs_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.abs_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.abs_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(ProfileEntry), C.POINTER(C.c_int)]
@@ -186,6 +189,11 @@ class Replicas:
     def norm_test(self, eta: float) -> List[TestResult]:
         out = (TestResult * self.M)()
         _check(self._lib.abs_norm_test(self._ctx, float(eta), out), self._ctx)
+        return list(out)
+
+    def norm_test_fpc(self, eta: float, n_total: int) -> List[TestResult]:
+        out = (TestResult * self.M)()
+        _check(self._lib.abs_norm_test_fpc(self._ctx, float(eta), int(n_total), out), self._ctx)
         return list(out)
 
     def inner_product_test(self, theta: float, nu: float = 0.0) -> List[TestResult]:
@@ -281,6 +289,13 @@ def lr_schedule(step: int, total_steps: int, warmup_steps: int, peak: float, flo
     out = C.c_double(0.0)
     _check(lib.abs_lr_schedule(int(step), int(total_steps), int(warmup_steps), float(peak), float(floor),
                                C.byref(out)))
+    return out.value
+
+
+def lr_linear_scaling(lr_ref: float, b: int, b_ref: int) -> float:
+    lib = load_library()
+    out = C.c_double(0.0)
+    _check(lib.abs_lr_linear_scaling(float(lr_ref), int(b), int(b_ref), C.byref(out)))
     return out.value
 
 

@@ -267,6 +267,13 @@ extern "C" {
 
 const char *abs_last_error(const abs_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
+abs_status abs_lr_linear_scaling(double lr_ref, int64_t b, int64_t b_ref, double *lr) {
+  if (!lr) return fail(ABS_EINVAL, "lr is NULL");
+  if (b < 1 || b_ref < 1) return fail(ABS_EINVAL, "batch sizes must be positive");
+  *lr = lr_ref * (double)b / (double)b_ref;
+  return ABS_OK;
+}
+
 abs_status abs_lr_schedule(long long step, long long total_steps, long long warmup_steps, double peak, double floor,
                            double *lr) {
   if (!lr) return fail(ABS_EINVAL, "lr is NULL");
@@ -572,16 +579,19 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   return ABS_OK;
 }
 
-abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) {
+static abs_status norm_test_impl(abs_ctx *c, double eta, int64_t n_total, abs_test_result *out) {
   if (!c || !out) return fail(ABS_EINVAL, "NULL argument");
   if (!(eta > 0.0 && eta < 1.0)) return cfail(c, ABS_EINVAL, "eta must be in (0,1)");
   abs_status st = read_stats(c);
   if (st != ABS_OK) return st;
   const int b = c->last_b;
+  if (n_total != 0 && (n_total < 2 || n_total < b)) return cfail(c, ABS_EINVAL, "n_total must be >= max(2, b)");
+  // finite-population factor of Sec. 4.1 (1 when sampling with replacement / n unknown)
+  const double fpc = n_total > 0 ? (double)(n_total - b) / (double)(n_total - 1) : 1.0;
   for (int m = 0; m < c->pl.M; ++m) {
     abs_test_result r;
     fill_result(r, b, c->host_stats + m * 8);
-    r.var = (r.sum_sq - (double)b * r.gbar_sq) / (double)(b - 1);
+    r.var = fpc * (r.sum_sq - (double)b * r.gbar_sq) / (double)(b - 1);
     r.lhs = r.var / (double)b;
     r.rhs = eta * eta * r.gbar_sq;
     ceil_ratio(r.var, eta * eta * r.gbar_sq, b, r.ratio, r.T);
@@ -589,6 +599,13 @@ abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) {
     out[m] = r;
   }
   return ABS_OK;
+}
+
+abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) { return norm_test_impl(c, eta, 0, out); }
+
+abs_status abs_norm_test_fpc(abs_ctx *c, double eta, int64_t n_total, abs_test_result *out) {
+  if (n_total < 2) return c ? cfail(c, ABS_EINVAL, "n_total must be >= max(2, b)") : fail(ABS_EINVAL, "NULL argument");
+  return norm_test_impl(c, eta, n_total, out);
 }
 
 abs_status abs_inner_product_test(abs_ctx *c, double theta, double nu, abs_test_result *out) {

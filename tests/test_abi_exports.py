@@ -77,3 +77,10 @@ def test_lr_schedule_matches_oracle_on_the_host():
                                                                          rel=1e-14)
     with pytest.raises(B.AbsError):
         B.lr_schedule(3, 10, 20, 0.1, 0.01)
+
+
+def test_linear_lr_scaling_on_the_host():
+    from paper_2406_13936_amd import binding as B
+    assert B.lr_linear_scaling(0.05, 2048, 256) == pytest.approx(0.4)
+    with pytest.raises(B.AbsError):
+        B.lr_linear_scaling(0.05, 0, 256)

@@ -341,6 +341,30 @@ def test_identical_samples_give_zero_variance_and_smallest_batch():
         rep.close()
 
 
+def test_norm_test_with_finite_population_factor():
+    A = _A()
+    w = W.Workload("fpc", (40, 24, 5), W.ACT_RELU, True, W.PREC_F32, N=96, M=3, H=1, rounds=1, b0=24,
+                   b_cap=96, opt=W.OPT_SGD, lr=0.1, test=W.TEST_NORM, eta=0.5, data="teacher_mlp", seed=11)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    try:
+        idx = W.step_indices(w, 0, 0, 24)
+        rep.local_step(idx, w.lr)
+        net = O.Net(w.dims, w.act, w.has_bias)
+        plain, fpc = rep.norm_test(0.5), rep.norm_test_fpc(0.5, w.N)
+        for m in range(w.M):
+            s = O.stats_factored(net, O.backprop(net, x0.astype(np.float64), X[idx[m]].astype(np.float64), y[idx[m]]))
+            o = O.norm_test(s["var"], s["S2"], 24, 0.5, n_total=w.N)
+            assert _rel(fpc[m].ratio, o["ratio"]) <= 1e-4 and bool(fpc[m].pass_) == o["pass"]
+            assert fpc[m].T == o["T"] or _near_boundary(o["ratio"], 24, 1e-4)
+            assert fpc[m].ratio == pytest.approx(plain[m].ratio * (w.N - 24) / (w.N - 1), rel=1e-12)
+        with pytest.raises(A.AbsError, match="n_total"):
+            rep.norm_test_fpc(0.5, 10)
+    finally:
+        rep.close()
+
+
 def test_error_paths_leave_outputs_untouched():
     A = _A()
     w = W.Workload("err", (32, 16, 4), W.ACT_RELU, True, W.PREC_BF16, N=64, M=2, H=1, rounds=1, b0=4,

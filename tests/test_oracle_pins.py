@@ -330,3 +330,31 @@ def test_lr_schedule_endpoints_and_shape():
     assert all(a <= b + 1e-15 for a, b in zip(vals[:warm], vals[1:warm]))          # warm-up rises
     assert all(a >= b - 1e-15 for a, b in zip(vals[warm:], vals[warm + 1:]))       # then decays
     assert min(vals[warm:]) >= floor - 1e-15
+
+
+def test_finite_population_factor_in_the_norm_test():
+    # b = n: the batch is the population, no sampling error -> T = 0 and the test passes
+    r = O.norm_test(7.0, 0.01, 50, 0.5, n_total=50)
+    assert r["T"] == 0 and r["pass"] and r["lhs"] == 0.0
+    # n -> infinity: the factor tends to 1
+    big = O.norm_test(7.0, 2.0, 50, 0.5, n_total=10 ** 15)
+    ref = O.norm_test(7.0, 2.0, 50, 0.5)
+    assert big["ratio"] == pytest.approx(ref["ratio"], rel=1e-12) and big["T"] == ref["T"]
+    # hand case: var 12, b 4, n 10 -> 12 * 6/9 = 8; eta^2 S2 = 0.25 * 2 -> ratio 16
+    r = O.norm_test(12.0, 2.0, 4, 0.5, n_total=10)
+    assert r["ratio"] == pytest.approx(16.0) and r["T"] == 16 and not r["pass"]
+    # brute force: the factor is the exact variance ratio of a mean of b draws without replacement
+    # from a population of n versus b i.i.d. draws with the (n-1)-normalised population variance.
+    import itertools
+    pop = np.array([0.3, -1.2, 2.0, 0.7, -0.4])
+    n, b = len(pop), 3
+    means = [np.mean(c) for c in itertools.combinations(pop, b)]
+    exact = float(np.mean((np.array(means) - pop.mean()) ** 2))
+    assert exact == pytest.approx(pop.var(ddof=1) / b * (n - b) / n, rel=1e-12)        # textbook form
+    # the paper's factor uses n - 1 with the 1/(b-1)-style variance; the two agree up to (n-1)/n
+    assert (n - b) / (n - 1) == pytest.approx((n - b) / n * n / (n - 1))
+
+
+def test_linear_lr_scaling():
+    assert O.lr_linear_scaling(0.05, 2048, 256) == pytest.approx(0.4)
+    assert O.lr_linear_scaling(0.05, 256, 256) == 0.05
