@@ -119,12 +119,27 @@ abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const 
 abs_status abs_local_step(abs_ctx *ctx, const int32_t *idx_dev, int b, float lr);
 
 /*
+ * The same step with one local batch size per worker (eq. (test_stat) gives each worker its own
+ * b^m before the practical rule takes their maximum; Sec. 3 allows heterogeneous workers).
+ *   idx_dev : device, int32 [M x ldi]; worker m uses the first b_host[m] entries of row m.
+ *   b_host  : host, M entries, each in [2, b_cap]; ldi >= max_m b_host[m].  The array is copied
+ *             during the call and may be reused at once.
+ * Worker m's batch gradient is the mean over its own b^m samples and its statistics are taken
+ * over those samples only.  abs_cross_worker_test refuses a ragged step (Alg. 2 assumes equal b).
+ */
+abs_status abs_local_step_ragged(abs_ctx *ctx, const int32_t *idx_dev, int ldi, const int *b_host /*host*/,
+                                 float lr);
+
+/*
  * Approximate local norm test, eqs. (approx_norm_local) and (test_stat), per worker:
  *   Var = (S1 - b S2)/(b-1)  [eq. (def_var)],  condition Var/b <= eta^2 S2,
  *   T = ceil(Var / (eta^2 S2)).   0 < eta < 1.   A zero batch gradient gives T = b, pass = 1.
  *   out : host, M entries.
  */
 abs_status abs_norm_test(abs_ctx *ctx, double eta, abs_test_result *out);
+
+/* The same test with one constant per worker (eta^m of eq. (approx_norm_local)); eta: host, M entries. */
+abs_status abs_norm_test_per_worker(abs_ctx *ctx, const double *eta /*host*/, abs_test_result *out);
 
 /*
  * The same test with the finite-population factor of Sec. 4.1's estimate of delta_B^2 (a batch

@@ -405,8 +405,9 @@ class Replicas:
         self.grads: Optional[np.ndarray] = None
 
     def local_step(self, idx: np.ndarray, lr: float):
-        """One local step of every worker on the given [M, b] indices; the
-        statistics refer to the gradient at the pre-update iterate."""
+        """One local step of every worker; idx[m] holds worker m's sample indices (an [M, b]
+        array, or M arrays of different lengths for per-worker batch sizes).  The statistics
+        refer to the gradient at the pre-update iterate."""
         self.stats = []
         grads = []
         for m in range(self.M):
@@ -420,10 +421,13 @@ class Replicas:
         return self.stats
 
     def test(self, kind: int, eta=0.5, theta=0.9, nu=0.0) -> List[dict]:
+        """Per-worker test on each worker's own batch (its own b^m; eta may be one constant per
+        worker, eq. (approx_norm_local))."""
         out = []
-        for s in self.stats:
+        for m, s in enumerate(self.stats):
             if kind == TEST_NORM:
-                out.append(norm_test(s["var"], s["S2"], s["b"], eta))
+                eta_m = eta[m] if np.ndim(eta) else eta
+                out.append(norm_test(s["var"], s["S2"], s["b"], eta_m))
             else:
                 out.append(inner_product_test(
                     s["var_q"], s["var_perp"], s["S2"], s["b"], theta,

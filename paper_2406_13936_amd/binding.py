@@ -25,7 +25,7 @@ EXPORTS = [
     "abs_get_per_sample", "abs_n_params", "abs_layer_stats",
     "abs_layer_stats_workspace_bytes", "abs_average_bf16", "abs_destroy", "abs_last_error",
     "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
-    "abs_lr_linear_scaling", "abs_norm_test_fpc",
+    "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
 ]
 
 
@@ -97,6 +97,8 @@ def load_library(reload: bool = False):
     lib.abs_lr_schedule.argtypes = [C.c_longlong, C.c_longlong, C.c_longlong, C.c_double, C.c_double,
                                     C.POINTER(C.c_double)]
     lib.abs_lr_linear_scaling.argtypes = [C.c_double, C.c_int64, C.c_int64, C.POINTER(C.c_double)]
+    lib.abs_local_step_ragged.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int), C.c_float]
+    lib.abs_norm_test_per_worker.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(TestResult)]
     lib.abs_norm_test_fpc.argtypes = [C.c_void_p, C.c_double, C.c_int64, C.POINTER(TestResult)]
     lib.abs_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.abs_profile_enable.argtypes = [C.c_void_p, C.c_int]
@@ -185,6 +187,26 @@ class Replicas:
     def local_step(self, idx: np.ndarray, lr: float):
         t, b = self.upload_indices(idx)
         self.local_step_dev(t, b, lr)
+
+    def local_step_ragged(self, idx_rows, lr: float):
+        """idx_rows: M index arrays of (possibly) different lengths, one per worker."""
+        assert len(idx_rows) == self.M
+        bs = [int(len(r)) for r in idx_rows]
+        ldi = max(bs)
+        host = np.zeros((self.M, ldi), dtype=np.int32)
+        for m, r in enumerate(idx_rows):
+            host[m, :bs[m]] = np.asarray(r, dtype=np.int32)
+        t = self._torch.as_tensor(host).to(self._X.device)
+        self._idx_keep = t
+        _check(self._lib.abs_local_step_ragged(self._ctx, t.data_ptr(), ldi, (C.c_int * self.M)(*bs), float(lr)),
+               self._ctx)
+
+    def norm_test_per_worker(self, etas) -> List[TestResult]:
+        out = (TestResult * self.M)()
+        assert len(etas) == self.M
+        _check(self._lib.abs_norm_test_per_worker(self._ctx, (C.c_double * self.M)(*[float(e) for e in etas]), out),
+               self._ctx)
+        return list(out)
 
     def norm_test(self, eta: float) -> List[TestResult]:
         out = (TestResult * self.M)()

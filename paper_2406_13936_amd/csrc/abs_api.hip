@@ -36,7 +36,7 @@ struct Plan {
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
   size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
-  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0;
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0;
   size_t total = 0;
 };
 
@@ -136,6 +136,7 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   }
   pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
   pl.o_stats = take((size_t)pl.M * 8 * 8);
+  pl.o_rows = take((size_t)pl.M * sizeof(int));
   pl.o_cw = take((2 * STATS_PBLK + 8) * 8);
   pl.total = off;
 }
@@ -174,7 +175,9 @@ struct abs_ctx {
   long long N = 0;
   double *host_stats = nullptr;     // pinned, M*8 + 8 doubles
   long long t = 0;                  // local steps taken (Adam bias correction)
-  int last_b = 0;
+  int last_b = 0;                 // largest local batch size of the last step
+  std::vector<int> last_bm;       // per worker
+  bool last_ragged = false;
   bool have_stats = false;
   std::string err;
 
@@ -403,13 +406,18 @@ abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out,
   return ABS_OK;
 }
 
-abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
-  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
-  if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
+// One local step.  b is the largest local batch size; with b_host (M entries, each in [2, b]) the
+// workers' batches are ragged: worker m uses the first b_host[m] entries of row m of idx (row
+// stride ldi) and every kernel takes its group's own row count from the device copy `rows`.
+static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, int b, const int *b_host, float lr) {
   const Plan &pl = c->pl;
-  if (b < 2 || b > pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
-  if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
   const int L = pl.L, M = pl.M, isb = pl.bf16 ? 1 : 0;
+  const int *rows = nullptr;
+  if (b_host) {
+    int *rows_dev = c->at<int>(pl.o_rows);
+    HIPCHK(c, launch_set_ints(b_host, M, rows_dev, c->stream));
+    rows = rows_dev;
+  }
   int an_parts[MAXL + 1], dn_parts[MAXL + 2];
   for (int l = 0; l <= MAXL; ++l) an_parts[l] = dn_parts[l] = 1;
   dn_parts[MAXL + 1] = 1;
@@ -427,8 +435,8 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   // batch gather (Alg. 1: "sample the local batch")
   const void *Xsrc = pl.bf16 ? static_cast<const void *>(c->at<bf16_t>(pl.o_Xbf)) : static_cast<const void *>(c->X);
   { ProfScope ps_(c, T_GATHER, 0.0, 2.0 * M * b * pl.dims[0] * pl.esz);
-  HIPCHK(c, launch_gather_rows(isb, Xsrc, pl.dims[0], (int)c->N, idx_dev, M, b, act_ptr(pl.o_A[0]), cap * pl.ld[0],
-                               pl.ld[0], c->at<float>(pl.o_an[0]), cap, s)); }
+  HIPCHK(c, launch_gather_rows(isb, Xsrc, pl.dims[0], (int)c->N, idx_dev, ldi, M, b, act_ptr(pl.o_A[0]), cap * pl.ld[0],
+                               pl.ld[0], c->at<float>(pl.o_an[0]), cap, rows, s)); }
 
   // forward
   for (int l = 1; l <= L; ++l) {
@@ -436,7 +444,7 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     std::memset(&p, 0, sizeof(p));
     p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
     p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1];
-    p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M;
+    p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows;
     if (hb) { p.bias = xm + pl.offB[l]; p.sBiasg = pl.Ppad; }
     p.act = c->cfg.act;
     if (l < L) {
@@ -450,7 +458,7 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
       } else {
         HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
         ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
-        HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, s));
+        HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, rows, s));
       }
     } else {
       p.C = c->at<float>(pl.o_Z); p.sCg = cap * pl.ld[L]; p.ldc = pl.ld[L];
@@ -459,16 +467,16 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   }
   // loss head: per-sample backprop signal of the last layer
   { ProfScope ps_(c, T_SOFTMAX, 0.0, 1.0 * M * b * pl.ld[L] * (4 + pl.esz));
-  HIPCHK(c, launch_softmax_ce(isb, c->at<float>(pl.o_Z), cap * pl.ld[L], pl.ld[L], pl.dims[L], c->y, (int)c->N, idx_dev, M, b,
+  HIPCHK(c, launch_softmax_ce(isb, c->at<float>(pl.o_Z), cap * pl.ld[L], pl.ld[L], pl.dims[L], c->y, (int)c->N, idx_dev, ldi, M, b,
                               act_ptr(pl.o_Dl[L]), cap * pl.ld[L], pl.ld[L], c->at<float>(pl.o_dn[L]),
-                              c->at<float>(pl.o_loss), cap, s)); }
+                              c->at<float>(pl.o_loss), cap, rows, s)); }
   // backward-data
   for (int l = L; l >= 2; --l) {
     GemmP p;
     std::memset(&p, 0, sizeof(p));
     p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l];
     p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1]; p.b_trans = 1;
-    p.Md = b; p.Nd = pl.dims[l - 1]; p.Kd = pl.dims[l]; p.groups = M;
+    p.Md = b; p.Nd = pl.dims[l - 1]; p.Kd = pl.dims[l]; p.groups = M; p.rows = rows;
     p.C = act_ptr(pl.o_Dl[l - 1]); p.sCg = cap * pl.ld[l - 1]; p.ldc = pl.ld[l - 1]; p.pad_to_ld = 1;
     p.act = c->cfg.act;
     p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
@@ -484,13 +492,15 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
       HIPCHK(c, gemm(c, p, EPI_BWD, l));
       if (hb) {
         ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1]) * pl.dims[l - 1]);
+        int tile_m = 0, ppt = 0;
+        gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1]), &tile_m, &ppt);
         HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1]), M,
-                                        1.0f / (float)b, grad + pl.offB[l - 1], pl.Ppad, s));
+                                        1.0f / (float)b, grad + pl.offB[l - 1], pl.Ppad, rows, tile_m, ppt, s));
       }
     } else {
       HIPCHK(c, gemm(c, p, EPI_BWD, l));
       ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
-      HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, s));
+      HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, rows, s));
     }
   }
   // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
@@ -500,7 +510,7 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     std::memset(&p, 0, sizeof(p));
     p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l]; p.a_trans = 1;
     p.B = act_ptr(pl.o_A[l - 1]); p.sBg = cap * pl.ld[l - 1]; p.ldb = pl.ld[l - 1]; p.b_trans = 1;
-    p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M;
+    p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M; p.rows = rows; p.rows_is_k = 1;
     p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
     p.alpha = inv_b;
     if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
@@ -508,7 +518,7 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
     if (hb && (!pl.bf16 || l == L)) {   // bf16 mode: layers below L got theirs from the backward epilogue
       ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
       HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad,
-                               c->at<float>(pl.o_colpart), s));
+                               c->at<float>(pl.o_colpart), rows, s));
     }
   }
   // inner products <g_i, gbar>
@@ -519,7 +529,7 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
       GemmP p;
       std::memset(&p, 0, sizeof(p));
       p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
-      p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M;
+      p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows;
       p.ldb = pl.dims[l - 1]; p.sBg = pl.Ppad;
       if (hb) { p.bias = grad + pl.offB[l]; p.sBiasg = pl.Ppad; }
       if (pl.bf16) {
@@ -538,13 +548,13 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
         float *q = c->at<float>(pl.o_qpart[0]);
         { ProfScope ps_(c, T_ROWDOT, 0.0, 2.0 * M * b * pl.ld[l] * 4);
   HIPCHK(c, launch_rowdot_f32(static_cast<const float *>(act_ptr(pl.o_Dl[l])), cap * pl.ld[l], pl.ld[l], U,
-                                    cap * pl.ld[l], pl.ld[l], pl.dims[l], M, b, q, cap, l > 1, s)); }
+                                    cap * pl.ld[l], pl.ld[l], pl.dims[l], M, b, q, cap, l > 1, rows, s)); }
         sp.qpart[l - 1] = q; sp.nparts[l - 1] = (l == 1) ? 1 : 0; sp.sQg[l - 1] = cap; sp.sQpart[l - 1] = cap;
       }
     }
   }
   // statistics
-  sp.L = L; sp.has_bias = hb ? 1 : 0; sp.groups = M; sp.b = b; sp.want_ip = pl.want_ip ? 1 : 0;
+  sp.L = L; sp.has_bias = hb ? 1 : 0; sp.groups = M; sp.b = b; sp.want_ip = pl.want_ip ? 1 : 0; sp.rows = rows;
   for (int l = 0; l < L; ++l) {
     sp.an[l] = c->at<float>(pl.o_an[l]); sp.dn[l] = c->at<float>(pl.o_dn[l + 1]);
     sp.an_parts[l] = an_parts[l]; sp.an_sg[l] = cap * pl.rparts[l];
@@ -575,20 +585,49 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   { ProfScope ps_(c, T_UPDATE, 0.0, 1.0 * M * pl.P * (c->cfg.opt == ABS_OPT_SGD ? 12 : c->cfg.opt == ABS_OPT_ADAMW ? 28 : 20) + (pl.bf16 ? 2.0 * M * pl.P : 0.0));
   HIPCHK(c, launch_update(up, s)); }
   c->last_b = b;
+  c->last_bm.assign(M, b);
+  if (b_host) c->last_bm.assign(b_host, b_host + M);
+  c->last_ragged = b_host != nullptr;
   c->have_stats = true;
   return ABS_OK;
 }
 
-static abs_status norm_test_impl(abs_ctx *c, double eta, int64_t n_total, abs_test_result *out) {
+abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
+  if (b < 2 || b > c->pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
+  if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
+  return local_step_impl(c, idx_dev, b, b, nullptr, lr);
+}
+
+abs_status abs_local_step_ragged(abs_ctx *c, const int32_t *idx_dev, int ldi, const int *b_host, float lr) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (!idx_dev || !b_host) return cfail(c, ABS_EINVAL, "idx_dev or b_host is NULL");
+  if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
+  int bmax = 0;
+  for (int m = 0; m < c->pl.M; ++m) {
+    if (b_host[m] < 2 || b_host[m] > c->pl.cap) return cfail(c, ABS_EINVAL, "every b[m] must be in [2, b_cap]");
+    if (b_host[m] > bmax) bmax = b_host[m];
+  }
+  if (ldi < bmax) return cfail(c, ABS_EINVAL, "ldi must be >= max_m b[m]");
+  return local_step_impl(c, idx_dev, ldi, bmax, b_host, lr);
+}
+
+static abs_status norm_test_impl(abs_ctx *c, const double *eta_m, double eta_all, int64_t n_total,
+                                 abs_test_result *out) {
   if (!c || !out) return fail(ABS_EINVAL, "NULL argument");
-  if (!(eta > 0.0 && eta < 1.0)) return cfail(c, ABS_EINVAL, "eta must be in (0,1)");
+  for (int m = 0; m < c->pl.M; ++m) {
+    const double eta = eta_m ? eta_m[m] : eta_all;
+    if (!(eta > 0.0 && eta < 1.0)) return cfail(c, ABS_EINVAL, "eta must be in (0,1)");
+  }
   abs_status st = read_stats(c);
   if (st != ABS_OK) return st;
-  const int b = c->last_b;
-  if (n_total != 0 && (n_total < 2 || n_total < b)) return cfail(c, ABS_EINVAL, "n_total must be >= max(2, b)");
-  // finite-population factor of Sec. 4.1 (1 when sampling with replacement / n unknown)
-  const double fpc = n_total > 0 ? (double)(n_total - b) / (double)(n_total - 1) : 1.0;
+  if (n_total != 0 && (n_total < 2 || n_total < c->last_b)) return cfail(c, ABS_EINVAL, "n_total must be >= max(2, b)");
   for (int m = 0; m < c->pl.M; ++m) {
+    const int b = c->last_bm[m];
+    const double eta = eta_m ? eta_m[m] : eta_all;
+    // finite-population factor of Sec. 4.1 (1 when sampling with replacement / n unknown)
+    const double fpc = n_total > 0 ? (double)(n_total - b) / (double)(n_total - 1) : 1.0;
     abs_test_result r;
     fill_result(r, b, c->host_stats + m * 8);
     r.var = fpc * (r.sum_sq - (double)b * r.gbar_sq) / (double)(b - 1);
@@ -601,11 +640,18 @@ static abs_status norm_test_impl(abs_ctx *c, double eta, int64_t n_total, abs_te
   return ABS_OK;
 }
 
-abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) { return norm_test_impl(c, eta, 0, out); }
+abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) {
+  return norm_test_impl(c, nullptr, eta, 0, out);
+}
+
+abs_status abs_norm_test_per_worker(abs_ctx *c, const double *eta, abs_test_result *out) {
+  if (!eta) return c ? cfail(c, ABS_EINVAL, "eta is NULL") : fail(ABS_EINVAL, "NULL argument");
+  return norm_test_impl(c, eta, 0.0, 0, out);
+}
 
 abs_status abs_norm_test_fpc(abs_ctx *c, double eta, int64_t n_total, abs_test_result *out) {
   if (n_total < 2) return c ? cfail(c, ABS_EINVAL, "n_total must be >= max(2, b)") : fail(ABS_EINVAL, "NULL argument");
-  return norm_test_impl(c, eta, n_total, out);
+  return norm_test_impl(c, nullptr, eta, n_total, out);
 }
 
 abs_status abs_inner_product_test(abs_ctx *c, double theta, double nu, abs_test_result *out) {
@@ -614,8 +660,8 @@ abs_status abs_inner_product_test(abs_ctx *c, double theta, double nu, abs_test_
   if (!c->pl.want_ip) return cfail(c, ABS_ESTATE, "stats_mask lacks ABS_STATS_IP");
   abs_status st = read_stats(c);
   if (st != ABS_OK) return st;
-  const int b = c->last_b;
   for (int m = 0; m < c->pl.M; ++m) {
+    const int b = c->last_bm[m];
     abs_test_result r;
     fill_result(r, b, c->host_stats + m * 8);
     const double S1 = r.sum_sq, S2 = r.gbar_sq, S3 = r.sum_q2, S4 = r.sum_q;
@@ -642,6 +688,7 @@ abs_status abs_cross_worker_test(abs_ctx *c, double eta, abs_test_result *out) {
   if (!(eta > 0.0 && eta < 1.0)) return cfail(c, ABS_EINVAL, "eta must be in (0,1)");
   if (c->pl.M < 2) return cfail(c, ABS_EINVAL, "the cross-worker estimator needs M >= 2");
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
+  if (c->last_ragged) return cfail(c, ABS_ESTATE, "the cross-worker estimator needs equal local batch sizes");
   const Plan &pl = c->pl;
   double *cw = c->at<double>(pl.o_cw);
   HIPCHK(c, launch_cross_worker(c->at<float>(pl.o_grad), pl.M, pl.Ppad, cw + 8, cw, c->stream));
@@ -730,9 +777,9 @@ abs_status abs_get_per_sample(abs_ctx *c, int m, float *n_host, float *q_host) {
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
   if (q_host && !c->pl.want_ip) return cfail(c, ABS_ESTATE, "stats_mask lacks ABS_STATS_IP");
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  HIPCHK(c, hipMemcpy(n_host, c->at<float>(c->pl.o_nout) + (size_t)m * c->pl.cap, (size_t)c->last_b * sizeof(float), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(n_host, c->at<float>(c->pl.o_nout) + (size_t)m * c->pl.cap, (size_t)c->last_bm[m] * sizeof(float), hipMemcpyDeviceToHost));
   if (q_host)
-    HIPCHK(c, hipMemcpy(q_host, c->at<float>(c->pl.o_qout) + (size_t)m * c->pl.cap, (size_t)c->last_b * sizeof(float), hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(q_host, c->at<float>(c->pl.o_qout) + (size_t)m * c->pl.cap, (size_t)c->last_bm[m] * sizeof(float), hipMemcpyDeviceToHost));
   return ABS_OK;
 }
 
@@ -805,8 +852,8 @@ abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M
   const float inv_b = 1.0f / (float)b;
   for (int l = 0; l < L; ++l) {
     const long long sa = (long long)b * in_dims[l], sd = (long long)b * out_dims[l];
-    HIPCHK(nc, launch_row_sqnorm(1, a_dev[l], sa, in_dims[l], in_dims[l], M, b, an + (size_t)l * M * b, b, s));
-    HIPCHK(nc, launch_row_sqnorm(1, delta_dev[l], sd, out_dims[l], out_dims[l], M, b, dn + (size_t)l * M * b, b, s));
+    HIPCHK(nc, launch_row_sqnorm(1, a_dev[l], sa, in_dims[l], in_dims[l], M, b, an + (size_t)l * M * b, b, nullptr, s));
+    HIPCHK(nc, launch_row_sqnorm(1, delta_dev[l], sd, out_dims[l], out_dims[l], M, b, dn + (size_t)l * M * b, b, nullptr, s));
     GemmP p;
     std::memset(&p, 0, sizeof(p));
     p.A = delta_dev[l]; p.sAg = sd; p.lda = out_dims[l]; p.a_trans = 1;

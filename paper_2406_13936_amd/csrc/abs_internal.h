@@ -38,6 +38,11 @@ struct GemmP {
   float alpha;
   int act;
   int pad_to_ld;               // also write zeros to columns [Nd, ldc) of C (and C2)
+  // Ragged groups (optional): rows[g] (device) replaces Md (rows_is_k == 0) or Kd (rows_is_k == 1,
+  // where alpha becomes 1 / rows[g]) for group g; Md / Kd then hold the largest count and size the
+  // grid.  Memory beyond a group's own rows is neither read nor written.
+  const int *rows;
+  int rows_is_k;
 };
 
 // bf16 MFMA family (gemm_bf16.hip).  Returns the number of column partials that
@@ -57,30 +62,36 @@ hipError_t launch_gemm_f32(const GemmP &p, int epi, hipStream_t s);
 // T = activation element type: 0 float, 1 bf16
 hipError_t launch_convert_f32_to_bf16(const float *src, bf16_t *dst, long long n, hipStream_t s);
 // A0[g][i][:] = X[idx[g][i]][:]  and  an0[g][i] = ||row||^2
-hipError_t launch_gather_rows(int is_bf16, const void *X, int d, int N, const int32_t *idx, int groups,
+// Every launcher below takes `rows` (device, may be null): per-group row counts that replace b
+// (then b is the largest count and sizes the grid).  `ldi` is the row stride of idx.
+hipError_t launch_gather_rows(int is_bf16, const void *X, int d, int N, const int32_t *idx, int ldi, int groups,
                               int b, void *A0, long long sA0g, int ldo, float *an0, long long sNg,
-                              hipStream_t s);
+                              const int *rows, hipStream_t s);
 // softmax cross-entropy head: delta = p - e_y (stored in T, pad columns zeroed),
 // dn[g][i] = ||stored delta_i||^2, loss[g][i] = f_i
 hipError_t launch_softmax_ce(int is_bf16, const float *Z, long long sZg, int ldz, int K,
-                             const int32_t *y, int N, const int32_t *idx, int groups, int b,
+                             const int32_t *y, int N, const int32_t *idx, int ldi, int groups, int b,
                              void *D, long long sDg, int ldd, float *dn, float *loss,
-                             long long sNg, hipStream_t s);
+                             long long sNg, const int *rows, hipStream_t s);
 // out[g][i] = sum_j X[g][i][j]^2
 hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, int cols,
-                             int groups, int b, float *out, long long sOg, hipStream_t s);
+                             int groups, int b, float *out, long long sOg, const int *rows, hipStream_t s);
 // out[g][j] = alpha * sum_i X[g][i][j]   (bias gradients); scratch: groups * ceil(b / COLSUM_ROWS)
 // * cols floats of partial sums
 enum { COLSUM_ROWS = 128 };
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups,
-                          int b, float alpha, float *out, long long sOg, float *scratch, hipStream_t s);
-// second stage alone: out[g][j] = alpha * sum_r part[g][r][j], r < nsplit (partials from a GEMM epilogue)
+                          int b, float alpha, float *out, long long sOg, float *scratch, const int *rows,
+                          hipStream_t s);
+// second stage alone: out[g][j] = alpha * sum_r part[g][r][j], r < nsplit (partials from a GEMM epilogue).
+// With rows: alpha = 1 / rows[g] and only the first ceil(rows[g] / tile_m) * parts_per_tile partials
+// of group g exist.
 hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha,
-                                 float *out, long long sOg, hipStream_t s);
+                                 float *out, long long sOg, const int *rows, int tile_m, int parts_per_tile,
+                                 hipStream_t s);
 // q[g][i] += sum_j D[g][i][j] * U[g][i][j]  (fp32 path of the inner products)
 hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U,
                              long long sUg, int ldu, int cols, int groups, int b, float *q,
-                             long long sQg, int accumulate, hipStream_t s);
+                             long long sQg, int accumulate, const int *rows, hipStream_t s);
 
 struct StatsP {
   int L, has_bias, groups, b, want_ip;
@@ -98,6 +109,7 @@ struct StatsP {
   long long Ppad;
   double *partials;         // scratch: [groups][5][PBLK]
   double *stats;            // out: [groups][8] = S1, S2, S3, S4, loss, 0,0,0
+  const int *rows;          // optional per-group sample counts (device) replacing b
 };
 enum { STATS_PBLK = 256 };
 hipError_t launch_stats(const StatsP &p, hipStream_t s);
@@ -114,6 +126,11 @@ hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s
 hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials,
                                double *out, hipStream_t s);
 hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);
+// dst[0..n) = v[0..n): the values travel as kernel arguments, so the host array may be reused at once
+enum { SET_INTS_MAX = 64 };
+hipError_t launch_set_ints(const int *v_host, int n, int *dst, hipStream_t s);
+// tile extent along m and column partials per tile of the bf16 family's tile shape `shape`
+void gemm_bf16_col_part_shape(int shape, int *tile_m, int *parts_per_tile);
 hipError_t launch_copy_probe(const void *src, void *dst, long long bytes, hipStream_t s);
 
 }  // namespace absk

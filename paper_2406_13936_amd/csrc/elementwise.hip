@@ -47,14 +47,14 @@ __global__ void convert_kernel(const float *__restrict__ src, bf16_t *__restrict
 // destination row stride is ldo >= d (multiple of 8), pad columns are written as zeros.
 // Indices outside [0, N) are clamped into the range (the kernels never read out of bounds).
 template <class T>
-__global__ void gather_kernel(const T *__restrict__ X, int d, int N, const int32_t *__restrict__ idx, int b,
+__global__ void gather_kernel(const T *__restrict__ X, int d, int N, const int32_t *__restrict__ idx, int ldi, int b,
                               T *__restrict__ A0, long long sAg, int ldo, float *__restrict__ an0,
-                              long long sNg) {
+                              long long sNg, const int *__restrict__ rows) {
   const int g = blockIdx.y;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (i >= b) return;
+  if (i >= (rows ? rows[g] : b)) return;
   const int lane = threadIdx.x & 63;
-  const int32_t id = min(max(idx[(long long)g * b + i], 0), N - 1);
+  const int32_t id = min(max(idx[(long long)g * ldi + i], 0), N - 1);
   const long long src = (long long)id * d;
   T *dst = A0 + (long long)g * sAg + (long long)i * ldo;
   float s = 0.0f;
@@ -84,15 +84,16 @@ __global__ void gather_kernel(const T *__restrict__ X, int d, int N, const int32
 // One wavefront per row of logits.
 template <class T>
 __global__ void softmax_ce_kernel(const float *__restrict__ Z, long long sZg, int ldz, int K,
-                                  const int32_t *__restrict__ y, int N, const int32_t *__restrict__ idx,
+                                  const int32_t *__restrict__ y, int N, const int32_t *__restrict__ idx, int ldi,
                                   int b, T *__restrict__ D, long long sDg, int ldd,
-                                  float *__restrict__ dn, float *__restrict__ loss, long long sNg) {
+                                  float *__restrict__ dn, float *__restrict__ loss, long long sNg,
+                                  const int *__restrict__ rows) {
   const int g = blockIdx.y;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (i >= b) return;
+  if (i >= (rows ? rows[g] : b)) return;
   const int lane = threadIdx.x & 63;
   const float *z = Z + (long long)g * sZg + (long long)i * ldz;
-  const int label = min(max(y[min(max(idx[(long long)g * b + i], 0), N - 1)], 0), K - 1);
+  const int label = min(max(y[min(max(idx[(long long)g * ldi + i], 0), N - 1)], 0), K - 1);
   float mx = -INFINITY;
   for (int c = lane; c < K; c += 64) mx = fmaxf(mx, z[c]);
 #pragma unroll
@@ -119,10 +120,10 @@ __global__ void softmax_ce_kernel(const float *__restrict__ Z, long long sZg, in
 
 template <class T>
 __global__ void row_sqnorm_kernel(const T *__restrict__ X, long long sXg, int ld, int cols, int b,
-                                  float *__restrict__ out, long long sOg) {
+                                  float *__restrict__ out, long long sOg, const int *__restrict__ rows) {
   const int g = blockIdx.y;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (i >= b) return;
+  if (i >= (rows ? rows[g] : b)) return;
   const int lane = threadIdx.x & 63;
   const T *row = X + (long long)g * sXg + (long long)i * ld;
   constexpr int V = Vec<T>::N;
@@ -147,12 +148,13 @@ __global__ void row_sqnorm_kernel(const T *__restrict__ X, long long sXg, int ld
 // stage 2 adds the partials of all row-blocks in index order and scales.
 template <class T>
 __global__ void __launch_bounds__(256) col_sum_stage1(const T *__restrict__ X, long long sXg, int ld, int cols,
-                                                      int b, float *__restrict__ part, int nsplit) {
+                                                      int b, float *__restrict__ part, int nsplit,
+                                                      const int *__restrict__ rows) {
   __shared__ float red[4][64];
   const int g = blockIdx.z, rs = blockIdx.y;
   const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
-  const int r0 = rs * COLSUM_ROWS, r1 = min(b, r0 + COLSUM_ROWS);
+  const int r0 = rs * COLSUM_ROWS, r1 = min(rows ? rows[g] : b, r0 + COLSUM_ROWS);
   float s = 0.0f;
   if (c < cols) {
     const T *p = X + (long long)g * sXg + c;
@@ -164,21 +166,28 @@ __global__ void __launch_bounds__(256) col_sum_stage1(const T *__restrict__ X, l
     part[((long long)g * nsplit + rs) * cols + c] = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
 }
 __global__ void __launch_bounds__(256) col_sum_stage2(const float *__restrict__ part, int cols, int nsplit,
-                                                      float alpha, float *__restrict__ out, long long sOg) {
+                                                      float alpha, float *__restrict__ out, long long sOg,
+                                                      const int *__restrict__ rows, int tile_m, int parts_per_tile) {
   const int g = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
   if (c >= cols) return;
   const float *p = part + (long long)g * nsplit * cols + c;
+  int ns = nsplit;
+  if (rows) {
+    alpha = 1.0f / (float)rows[g];
+    if (tile_m > 0) ns = (rows[g] + tile_m - 1) / tile_m * parts_per_tile;   // only these were written
+  }
   float s = 0.0f;
-  for (int r = 0; r < nsplit; ++r) s += p[(long long)r * cols];
+  for (int r = 0; r < ns; ++r) s += p[(long long)r * cols];
   out[(long long)g * sOg + c] = alpha * s;
 }
 
 __global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, int ldd,
                                   const float *__restrict__ U, long long sUg, int ldu, int cols,
-                                  int b, float *__restrict__ q, long long sQg, int accumulate) {
+                                  int b, float *__restrict__ q, long long sQg, int accumulate,
+                                  const int *__restrict__ rows) {
   const int g = blockIdx.y;
   const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (i >= b) return;
+  if (i >= (rows ? rows[g] : b)) return;
   const int lane = threadIdx.x & 63;
   const float *d = D + (long long)g * sDg + (long long)i * ldd;
   const float *u = U + (long long)g * sUg + (long long)i * ldu;
@@ -200,7 +209,8 @@ __global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p) {
   const int g = blockIdx.y;
   double s1 = 0.0, s3 = 0.0, s4 = 0.0, sl = 0.0;
   const float hb = p.has_bias ? 1.0f : 0.0f;
-  for (int i = blockIdx.x * 256 + threadIdx.x; i < p.b; i += 256 * STATS_PBLK) {
+  const int bg = p.rows ? p.rows[g] : p.b;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < bg; i += 256 * STATS_PBLK) {
     const long long o = (long long)g * p.sNg + i;
     float n = 0.0f;
     for (int l = 0; l < p.L; ++l) {
@@ -402,6 +412,11 @@ __global__ void __launch_bounds__(256) copy_probe_kernel(const uint4 *__restrict
   if (i < n16) dst[i] = src[i];
 }
 
+struct IntsArg { int v[SET_INTS_MAX]; };
+__global__ void set_ints_kernel(const IntsArg a, int n, int *__restrict__ dst) {
+  if ((int)threadIdx.x < n) dst[threadIdx.x] = a.v[threadIdx.x];
+}
+
 __global__ void fill_zero_kernel(uint4 *p, long long n16) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x; i < n16; i += stride)
@@ -423,70 +438,72 @@ hipError_t launch_convert_f32_to_bf16(const float *src, bf16_t *dst, long long n
   return hipGetLastError();
 }
 
-hipError_t launch_gather_rows(int is_bf16, const void *X, int d, int N, const int32_t *idx, int groups, int b,
-                              void *A0, long long sA0g, int ldo, float *an0, long long sNg, hipStream_t s) {
+hipError_t launch_gather_rows(int is_bf16, const void *X, int d, int N, const int32_t *idx, int ldi, int groups, int b,
+                              void *A0, long long sA0g, int ldo, float *an0, long long sNg, const int *rows,
+                              hipStream_t s) {
   const dim3 grid((b + 3) / 4, groups), blk(256);
   if (is_bf16)
-    hipLaunchKernelGGL(gather_kernel<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), d, N, idx, b,
-                       static_cast<bf16_t *>(A0), sA0g, ldo, an0, sNg);
+    hipLaunchKernelGGL(gather_kernel<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), d, N, idx, ldi, b,
+                       static_cast<bf16_t *>(A0), sA0g, ldo, an0, sNg, rows);
   else
-    hipLaunchKernelGGL(gather_kernel<float>, grid, blk, 0, s, static_cast<const float *>(X), d, N, idx, b,
-                       static_cast<float *>(A0), sA0g, ldo, an0, sNg);
+    hipLaunchKernelGGL(gather_kernel<float>, grid, blk, 0, s, static_cast<const float *>(X), d, N, idx, ldi, b,
+                       static_cast<float *>(A0), sA0g, ldo, an0, sNg, rows);
   return hipGetLastError();
 }
 
 hipError_t launch_softmax_ce(int is_bf16, const float *Z, long long sZg, int ldz, int K, const int32_t *y,
-                             int N, const int32_t *idx, int groups, int b, void *D, long long sDg, int ldd,
-                             float *dn, float *loss, long long sNg, hipStream_t s) {
+                             int N, const int32_t *idx, int ldi, int groups, int b, void *D, long long sDg, int ldd,
+                             float *dn, float *loss, long long sNg, const int *rows, hipStream_t s) {
   const dim3 grid((b + 3) / 4, groups), blk(256);
   if (is_bf16)
-    hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, b,
-                       static_cast<bf16_t *>(D), sDg, ldd, dn, loss, sNg);
+    hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+                       static_cast<bf16_t *>(D), sDg, ldd, dn, loss, sNg, rows);
   else
-    hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, b,
-                       static_cast<float *>(D), sDg, ldd, dn, loss, sNg);
+    hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+                       static_cast<float *>(D), sDg, ldd, dn, loss, sNg, rows);
   return hipGetLastError();
 }
 
 hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
-                             float *out, long long sOg, hipStream_t s) {
+                             float *out, long long sOg, const int *rows, hipStream_t s) {
   const dim3 grid((b + 3) / 4, groups), blk(256);
   if (is_bf16)
     hipLaunchKernelGGL(row_sqnorm_kernel<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld,
-                       cols, b, out, sOg);
+                       cols, b, out, sOg, rows);
   else
     hipLaunchKernelGGL(row_sqnorm_kernel<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld,
-                       cols, b, out, sOg);
+                       cols, b, out, sOg, rows);
   return hipGetLastError();
 }
 
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
-                          float alpha, float *out, long long sOg, float *scratch, hipStream_t s) {
+                          float alpha, float *out, long long sOg, float *scratch, const int *rows, hipStream_t s) {
   const int nsplit = (b + COLSUM_ROWS - 1) / COLSUM_ROWS;
   const dim3 grid((cols + 63) / 64, nsplit, groups), blk(256);
   if (is_bf16)
     hipLaunchKernelGGL(col_sum_stage1<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols, b,
-                       scratch, nsplit);
+                       scratch, nsplit, rows);
   else
     hipLaunchKernelGGL(col_sum_stage1<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
-                       scratch, nsplit);
+                       scratch, nsplit, rows);
+  // stage 1 writes every partial (zeros past a group's rows), so stage 2 adds all of them
   hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, scratch, cols, nsplit,
-                     alpha, out, sOg);
+                     alpha, out, sOg, rows, 0, 0);
   return hipGetLastError();
 }
 
 hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha, float *out,
-                                 long long sOg, hipStream_t s) {
+                                 long long sOg, const int *rows, int tile_m, int parts_per_tile, hipStream_t s) {
   hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, part, cols, nsplit,
-                     alpha, out, sOg);
+                     alpha, out, sOg, rows, tile_m, parts_per_tile);
   return hipGetLastError();
 }
 
 hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U, long long sUg, int ldu,
                              int cols, int groups, int b, float *q, long long sQg, int accumulate,
-                             hipStream_t s) {
+                             const int *rows, hipStream_t s) {
   hipLaunchKernelGGL(rowdot_f32_kernel, dim3((b + 3) / 4, groups), dim3(256), 0, s, D, sDg, ldd, U, sUg, ldu,
-                     cols, b, q, sQg, accumulate);
+                     cols, b, q, sQg, accumulate, rows);
   return hipGetLastError();
 }
 
@@ -540,6 +557,16 @@ hipError_t launch_copy_probe(const void *src, void *dst, long long bytes, hipStr
   if (n16 <= 0) return hipSuccess;
   hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
                      static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_set_ints(const int *v_host, int n, int *dst, hipStream_t s) {
+  for (int o = 0; o < n; o += SET_INTS_MAX) {
+    IntsArg a;
+    const int m = n - o < SET_INTS_MAX ? n - o : SET_INTS_MAX;
+    for (int i = 0; i < SET_INTS_MAX; ++i) a.v[i] = i < m ? v_host[o + i] : 0;
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(SET_INTS_MAX), 0, s, a, m, dst + o);
+  }
   return hipGetLastError();
 }
 

@@ -128,7 +128,7 @@ struct Frag {
 // ---- the kernel --------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WM, int WN, int NS, bool AT, bool BT, int EPI, int ACT>
 __global__ void __launch_bounds__(WM * WN * 64)
-gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nblk, const int chunk) {
+gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int nblk, const int chunk) {
   constexpr int NW = WM * WN, NT = NW * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
   constexpr int MI = TM / 32, NI = TN / 32;
@@ -152,6 +152,12 @@ gemm_bf16_kernel(const GemmP p, const int tilesM, const int tilesN, const int nb
   const int t = lb - g * per_g;
   const int tm = t / tilesN, tn = t - tm * tilesN;
   const int m0 = tm * BM, n0 = tn * BN;
+  GemmP p = pin;
+  if (p.rows) {                                   // ragged groups: this group's own extent
+    const int r = p.rows[g];
+    if (p.rows_is_k) { p.Kd = r; p.alpha = 1.0f / (float)r; } else p.Md = r;
+    if (m0 >= p.Md) return;                       // uniform over the block, before any barrier
+  }
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -547,6 +553,12 @@ int gemm_bf16_col_parts(int Md, int Nd) {
   const int bm[3] = {128, 128, 256}, wm[3] = {4, 2, 2};
   const int sh = gemm_bf16_tile_shape(Md, Nd);
   return (Md + bm[sh] - 1) / bm[sh] * wm[sh];
+}
+
+void gemm_bf16_col_part_shape(int shape, int *tile_m, int *parts_per_tile) {
+  const int bm[3] = {128, 128, 256}, wm[3] = {4, 2, 2};
+  *tile_m = bm[shape];
+  *parts_per_tile = wm[shape];
 }
 
 int gemm_bf16_ipdot_parts(int Nd) {

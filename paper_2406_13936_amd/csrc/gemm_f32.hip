@@ -11,10 +11,16 @@ namespace absk {
 namespace {
 
 template <int EPI, int ACT>
-__global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP p) {
+__global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
   __shared__ float As[16][68];
   __shared__ float Bs[16][68];
   const int g = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  GemmP p = pin;
+  if (p.rows) {                                   // ragged groups: this group's own extent
+    const int r = p.rows[g];
+    if (p.rows_is_k) { p.Kd = r; p.alpha = 1.0f / (float)r; } else p.Md = r;
+    if (m0 >= p.Md) return;                       // uniform over the block, before any barrier
+  }
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const float *A = static_cast<const float *>(p.A) + (long long)g * p.sAg;
   const float *B = static_cast<const float *>(p.B) + (long long)g * p.sBg;

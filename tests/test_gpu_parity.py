@@ -292,6 +292,131 @@ def test_fp32_free_running_twin_with_heavy_ball_and_adamw():
 
 
 # ---------------------------------------------------------------------------------------------
+# per-worker (ragged) batch sizes
+# ---------------------------------------------------------------------------------------------
+
+def _ragged_rows(w, bs):
+    return [W.batch_indices(w.seed, 0, 0, m, b, w.N) for m, b in enumerate(bs)]
+
+
+@pytest.mark.parametrize("prec,dims,act,bs,opt,hb", [
+    (W.PREC_F32, (40, 24, 5), W.ACT_GELU, [37, 150, 9, 2], W.OPT_SHB, True),
+    (W.PREC_F32, (72, 10), W.ACT_NONE, [130, 64, 3], W.OPT_SGD, False),
+    (W.PREC_BF16, (384, 256, 256, 256, 100), W.ACT_GELU, [333, 40, 129], W.OPT_SHB, True),
+    (W.PREC_BF16, (136, 264, 100), W.ACT_RELU, [2, 517, 128, 260], W.OPT_ADAGRAD, True),
+    # 256x256 tiles; workers that own fewer row tiles than the grid has
+    (W.PREC_BF16, (1024, 1024, 1024, 100), W.ACT_RELU, [1100, 260, 2], W.OPT_SGD, True),
+])
+def test_ragged_step_matches_oracle(prec, dims, act, bs, opt, hb):
+    A = _A()
+    M = len(bs)
+    w = W.Workload("ragged", dims, act, hb, prec, N=2048, M=M, H=1, rounds=1, b0=max(bs), b_cap=max(bs) + 7, opt=opt,
+                   lr=0.05, momentum=0.9, test=W.TEST_IP, theta=0.9, data="teacher_mlp", seed=13)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    mixed = prec == W.PREC_BF16
+    orc = _oracle_for(w, X, y, x0, mixed=mixed)
+    tol = 2e-3 if mixed else 1e-4
+    try:
+        rows = _ragged_rows(w, bs)
+        full = W.step_indices(w, 3, 1, max(bs))                 # stale data of a full step in every buffer
+        rep.local_step(full, 0.0)
+        orc.local_step(full, 0.0)
+        rep.local_step_ragged(rows, w.lr)
+        orc.local_step(rows, w.lr)
+        gi, gn = rep.inner_product_test(w.theta), rep.norm_test_per_worker([0.2 + 0.1 * m for m in range(M)])
+        oi = orc.test(W.TEST_IP, theta=w.theta)
+        on = orc.test(W.TEST_NORM, eta=[0.2 + 0.1 * m for m in range(M)])
+        for m in range(M):
+            s = orc.stats[m]
+            assert gi[m].b == bs[m] == s["b"]
+            grad = rep.get_grad(m).astype(np.float64)
+            assert np.abs(grad - orc.grads[m]).max() <= (2e-3 if mixed else 1e-5) * np.abs(orc.grads[m]).max()
+            n, q = rep.get_per_sample(m, bs[m], want_q=True)
+            np.testing.assert_allclose(n, s["n"], rtol=5e-3 if mixed else 1e-4)
+            np.testing.assert_allclose(q, s["q"], rtol=2e-2 if mixed else 1e-3, atol=(2e-3 if mixed else 1e-5) * np.abs(s["q"]).max())
+            for name, got, want in (("S1", gi[m].sum_sq, s["S1"]), ("S2", gi[m].gbar_sq, s["S2"]),
+                                    ("S3", gi[m].sum_q2, s["S3"]), ("S4", gi[m].sum_q, s["S4"]),
+                                    ("loss", gi[m].loss_sum, s["loss_sum"])):
+                assert _rel(got, want) <= tol, (m, name, got, want)
+            if bs[m] > 2:
+                assert _rel(gn[m].ratio, on[m]["ratio"]) <= 5 * tol, (m, gn[m].ratio, on[m]["ratio"])
+                assert gn[m].T == on[m]["T"] or _near_boundary(on[m]["ratio"], bs[m], 5 * tol)
+                assert _rel(gi[m].ratio, oi[m]["ratio"]) <= 20 * tol
+            p = rep.get_params(m).astype(np.float64)
+            sel = np.ones(p.size, dtype=bool)
+            if opt == W.OPT_ADAGRAD:      # first step is lr * sign(g): compare where g is not rounding noise
+                sel = np.abs(orc.grads[m]) >= 1e-2 * np.abs(orc.grads[m]).max()
+            assert np.abs(p - orc.x[m])[sel].max() <= (1e-3 if mixed else 1e-5) * np.abs(orc.x[m]).max()
+        with pytest.raises(A.AbsError, match="equal local batch sizes"):
+            rep.cross_worker_test(0.5)
+    finally:
+        rep.close()
+
+
+def test_ragged_step_with_equal_sizes_is_bitwise_the_uniform_step():
+    A = _A()
+    w = _one_step_case((384, 256, 256, 100), W.ACT_GELU, W.PREC_BF16, 200, 3, opt=W.OPT_SHB, N=1024)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    idx = W.step_indices(w, 0, 0, 200)
+    out = []
+    for ragged in (False, True):
+        rep = A.Replicas.from_workload(w, X, y, x0)
+        try:
+            if ragged:
+                rep.local_step_ragged([idx[m] for m in range(3)], w.lr)
+            else:
+                rep.local_step(idx, w.lr)
+            r = rep.inner_product_test(w.theta)
+            out.append(([rep.get_params(m) for m in range(3)], [(t.sum_sq, t.gbar_sq, t.sum_q, t.sum_q2) for t in r]))
+        finally:
+            rep.close()
+    assert out[0][1] == out[1][1]
+    for m in range(3):
+        assert np.array_equal(out[0][0][m], out[1][0][m])
+
+
+def test_per_worker_schedule_lockstep_fp32():
+    """Alg. 1 with each worker keeping its own batch size (no max over workers) and its own eta."""
+    A = _A()
+    w = W.Workload("perworker", (64, 32, 10), W.ACT_RELU, True, W.PREC_F32, N=4096, M=4, H=3, rounds=4, b0=8,
+                   b_cap=256, opt=W.OPT_SGD, lr=0.1, test=W.TEST_NORM, eta=0.5, data="teacher_mlp", seed=17)
+    etas = [0.25, 0.4, 0.55, 0.7]
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    orc = _oracle_for(w, X, y, x0, mixed=False)
+    try:
+        bs = [w.b0] * w.M
+        seen = set()
+        for k in range(w.rounds):
+            for h in range(w.H):
+                rows = [W.batch_indices(w.seed, k, h, m, bs[m], w.N) for m in range(w.M)]
+                rep.local_step_ragged(rows, w.lr)
+                orc.local_step(rows, w.lr)
+                g, o = rep.norm_test_per_worker(etas), orc.test(W.TEST_NORM, eta=etas)
+                for m in range(w.M):
+                    assert _rel(g[m].ratio, o[m]["ratio"]) <= 2e-4, (k, h, m)
+                    assert g[m].T == o[m]["T"] or _near_boundary(o[m]["ratio"], bs[m], 2e-4)
+                nb_g = A.next_batch_size(g, bs, w.b_cap, sync_max=False)
+                nb_o = O.next_batch_size([r["T"] for r in o], bs, w.b_cap, sync_max=False)
+                for m in range(w.M):
+                    assert nb_g[m] == nb_o[m] or _near_boundary(o[m]["ratio"], bs[m], 2e-4)
+                bs = nb_o
+                seen.add(tuple(bs))
+            rep.average_replicas()
+            orc.average()
+        assert any(len(set(t)) > 1 for t in seen), seen          # the sizes did become ragged
+        for m in range(w.M):
+            p = rep.get_params(m).astype(np.float64)
+            assert np.abs(p - orc.x[m]).max() <= 1e-3 * np.abs(orc.x[m]).max()
+    finally:
+        rep.close()
+
+
+# ---------------------------------------------------------------------------------------------
 # structure, edge cases, error paths
 # ---------------------------------------------------------------------------------------------
 

@@ -358,3 +358,24 @@ def test_finite_population_factor_in_the_norm_test():
 def test_linear_lr_scaling():
     assert O.lr_linear_scaling(0.05, 2048, 256) == pytest.approx(0.4)
     assert O.lr_linear_scaling(0.05, 256, 256) == 0.05
+
+
+def test_ragged_workers_are_independent_single_worker_runs():
+    # a step with per-worker batch sizes equals M separate one-worker steps on the same batches
+    net, x, Xb, yb = _tiny((6, 5, 3), O.ACT_RELU, True, b=40, seed=21)
+    rows = [np.arange(0, 7), np.arange(7, 40), np.arange(3, 5)]
+    rep = O.Replicas(net, x, Xb, yb, 3, opt=O.OPT_SHB, momentum=0.9, want_ip=True)
+    rep.local_step(rows, 0.1)
+    res = rep.test(O.TEST_NORM, eta=[0.3, 0.5, 0.7])
+    for m, r in enumerate(rows):
+        one = O.Replicas(net, x, Xb, yb, 1, opt=O.OPT_SHB, momentum=0.9, want_ip=True)
+        one.local_step([r], 0.1)
+        assert rep.stats[m]["b"] == len(r)
+        for k in ("S1", "S2", "S3", "S4", "var"):
+            assert rep.stats[m][k] == one.stats[0][k]
+        np.testing.assert_array_equal(rep.x[m], one.x[0])
+        np.testing.assert_allclose(rep.grads[m], O.per_sample_gradients(net, x, Xb[r], yb[r]).mean(axis=0),
+                                   rtol=1e-11, atol=1e-15)
+        assert res[m] == O.norm_test(one.stats[0]["var"], one.stats[0]["S2"], len(r), [0.3, 0.5, 0.7][m])
+    assert O.next_batch_size([r["T"] for r in res], [7, 33, 2], 64, sync_max=False) == \
+        [min(64, max(r["T"], b)) for r, b in zip(res, [7, 33, 2])]
