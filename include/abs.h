@@ -119,6 +119,20 @@ abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const 
 abs_status abs_local_step(abs_ctx *ctx, const int32_t *idx_dev, int b, float lr);
 
 /*
+ * The same step as abs_local_step, with the batch of b samples processed in micro-batches of
+ * micro_b <= b_cap samples ("gradient accumulation", Sec. 6, for batches whose activations do
+ * not fit): b may exceed b_cap.  The gradient, S1 and the loss accumulate over the micro-batches
+ * and S2 is taken from the finished gradient; the inner products <g_i, gbar> need the gradient
+ * of the whole batch, so with ABS_STATS_IP the forward and backward passes run a second time.
+ * One optimizer update follows.  The result equals abs_local_step on the whole batch up to the
+ * order of floating-point additions.
+ *   idx_dev : device, int32 [M x b] (row stride b).   b % micro_b must not be 1.
+ * abs_get_per_sample afterwards returns the values of the micro-batches that lie wholly inside
+ * the first b_cap samples (all of them when b <= b_cap).
+ */
+abs_status abs_local_step_accumulated(abs_ctx *ctx, const int32_t *idx_dev, int b, int micro_b, float lr);
+
+/*
  * The same step with one local batch size per worker (eq. (test_stat) gives each worker its own
  * b^m before the practical rule takes their maximum; Sec. 3 allows heterogeneous workers).
  *   idx_dev : device, int32 [M x ldi]; worker m uses the first b_host[m] entries of row m.

@@ -26,6 +26,7 @@ EXPORTS = [
     "abs_layer_stats_workspace_bytes", "abs_average_bf16", "abs_destroy", "abs_last_error",
     "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
     "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
+    "abs_local_step_accumulated",
 ]
 
 
@@ -97,6 +98,7 @@ def load_library(reload: bool = False):
     lib.abs_lr_schedule.argtypes = [C.c_longlong, C.c_longlong, C.c_longlong, C.c_double, C.c_double,
                                     C.POINTER(C.c_double)]
     lib.abs_lr_linear_scaling.argtypes = [C.c_double, C.c_int64, C.c_int64, C.POINTER(C.c_double)]
+    lib.abs_local_step_accumulated.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float]
     lib.abs_local_step_ragged.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int), C.c_float]
     lib.abs_norm_test_per_worker.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(TestResult)]
     lib.abs_norm_test_fpc.argtypes = [C.c_void_p, C.c_double, C.c_int64, C.POINTER(TestResult)]
@@ -187,6 +189,12 @@ class Replicas:
     def local_step(self, idx: np.ndarray, lr: float):
         t, b = self.upload_indices(idx)
         self.local_step_dev(t, b, lr)
+
+    def local_step_accumulated(self, idx: np.ndarray, micro_b: int, lr: float):
+        """One step on an int32 [M, b] index array, processed micro_b samples at a time."""
+        t, b = self.upload_indices(idx)
+        self._idx_keep = t
+        _check(self._lib.abs_local_step_accumulated(self._ctx, t.data_ptr(), b, int(micro_b), float(lr)), self._ctx)
 
     def local_step_ragged(self, idx_rows, lr: float):
         """idx_rows: M index arrays of (possibly) different lengths, one per worker."""

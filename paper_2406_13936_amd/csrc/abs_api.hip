@@ -177,6 +177,7 @@ struct abs_ctx {
   long long t = 0;                  // local steps taken (Adam bias correction)
   int last_b = 0;                 // largest local batch size of the last step
   std::vector<int> last_bm;       // per worker
+  int last_ps = -1;               // per-sample outputs stored (accumulated steps; -1: all of them)
   bool last_ragged = false;
   bool have_stats = false;
   std::string err;
@@ -409,7 +410,24 @@ abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out,
 // One local step.  b is the largest local batch size; with b_host (M entries, each in [2, b]) the
 // workers' batches are ragged: worker m uses the first b_host[m] entries of row m of idx (row
 // stride ldi) and every kernel takes its group's own row count from the device copy `rows`.
-static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, int b, const int *b_host, float lr) {
+// Which parts of the step one call of local_step_impl runs.  A plain step runs all of them once;
+// a step accumulated over micro-batches runs the passes once per micro-batch for the gradient,
+// S1 and the loss, and (for the inner products, which need the batch gradient of the whole batch)
+// a second time per micro-batch, before the single update.
+struct StepPhase {
+  bool passes = true;    // gather, forward, loss head, backward-data
+  bool wgrad = true;     // batch gradient
+  bool nstats = true;    // S1 and the loss sum
+  bool s2 = true;        // ||gbar||^2
+  bool ip = true;        // inner products, S3, S4 (when the statistics mask asks for them)
+  bool update = true;
+  bool acc_grad = false, acc_n = false, acc_q = false;   // add to what earlier micro-batches left
+  int b_total = 0;       // divisor of the batch gradient (0: this call's b)
+  long long ps_off = 0;  // offset of this call's samples in the per-sample outputs (-1: not stored)
+};
+
+static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, int b, const int *b_host, float lr,
+                                  const StepPhase &ph = StepPhase()) {
   const Plan &pl = c->pl;
   const int L = pl.L, M = pl.M, isb = pl.bf16 ? 1 : 0;
   const int *rows = nullptr;
@@ -432,6 +450,9 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   };
   auto act_ptr = [&](size_t off) -> void * { return c->ws + off; };
 
+  const bool want_parts = ph.nstats;      // row-norm partials feed S1 only
+  const float inv_b = 1.0f / (float)(ph.b_total > 0 ? ph.b_total : b);
+  if (ph.passes) {
   // batch gather (Alg. 1: "sample the local batch")
   const void *Xsrc = pl.bf16 ? static_cast<const void *>(c->at<bf16_t>(pl.o_Xbf)) : static_cast<const void *>(c->X);
   { ProfScope ps_(c, T_GATHER, 0.0, 2.0 * M * b * pl.dims[0] * pl.esz);
@@ -453,10 +474,11 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       if (pl.bf16) {
         // ||a_i^l||^2 as per-tile partials out of the GEMM epilogue (summed by the statistics kernel)
         an_parts[l] = gemm_bf16_row_parts(b, pl.dims[l]);
-        p.part = c->at<float>(pl.o_an[l]); p.sPartg = cap * pl.rparts[l]; p.sPartTile = cap;
+        if (want_parts) { p.part = c->at<float>(pl.o_an[l]); p.sPartg = cap * pl.rparts[l]; p.sPartTile = cap; }
         HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
       } else {
         HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
+        if (!want_parts) continue;
         ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
         HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, rows, s));
       }
@@ -484,27 +506,29 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     if (pl.bf16) {
       // ||delta_i^{l-1}||^2 and (with biases) the column sums of delta^{l-1} as epilogue partials
       dn_parts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l - 1]);
-      p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap;
-      if (hb) {
+      if (want_parts) { p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap; }
+      if (hb && ph.wgrad) {
         p.cpart = c->at<float>(pl.o_colpart);
         p.sCpartg = (long long)gemm_bf16_col_parts(b, pl.dims[l - 1]) * pl.dims[l - 1];
       }
       HIPCHK(c, gemm(c, p, EPI_BWD, l));
-      if (hb) {
+      if (hb && ph.wgrad) {
         ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1]) * pl.dims[l - 1]);
         int tile_m = 0, ppt = 0;
         gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1]), &tile_m, &ppt);
         HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1]), M,
-                                        1.0f / (float)b, grad + pl.offB[l - 1], pl.Ppad, rows, tile_m, ppt, s));
+                                        inv_b, grad + pl.offB[l - 1], pl.Ppad, rows, tile_m, ppt, ph.acc_grad ? 1 : 0, s));
       }
     } else {
       HIPCHK(c, gemm(c, p, EPI_BWD, l));
+      if (!want_parts) continue;
       ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
       HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, rows, s));
     }
   }
+  }   // passes
   // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
-  const float inv_b = 1.0f / (float)b;
+  if (ph.wgrad)
   for (int l = 1; l <= L; ++l) {
     GemmP p;
     std::memset(&p, 0, sizeof(p));
@@ -512,19 +536,20 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     p.B = act_ptr(pl.o_A[l - 1]); p.sBg = cap * pl.ld[l - 1]; p.ldb = pl.ld[l - 1]; p.b_trans = 1;
     p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M; p.rows = rows; p.rows_is_k = 1;
     p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
-    p.alpha = inv_b;
+    p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
     if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
     HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
     if (hb && (!pl.bf16 || l == L)) {   // bf16 mode: layers below L got theirs from the backward epilogue
       ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
       HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad,
-                               c->at<float>(pl.o_colpart), rows, s));
+                               c->at<float>(pl.o_colpart), rows, ph.acc_grad ? 1 : 0, s));
     }
   }
   // inner products <g_i, gbar>
   StatsP sp;
   std::memset(&sp, 0, sizeof(sp));
-  if (pl.want_ip) {
+  const bool do_ip = pl.want_ip && ph.ip;
+  if (do_ip) {
     for (int l = 1; l <= L; ++l) {
       GemmP p;
       std::memset(&p, 0, sizeof(p));
@@ -555,6 +580,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   }
   // statistics
   sp.L = L; sp.has_bias = hb ? 1 : 0; sp.groups = M; sp.b = b; sp.want_ip = pl.want_ip ? 1 : 0; sp.rows = rows;
+  sp.do_n = ph.nstats ? 1 : 0; sp.do_q = do_ip ? 1 : 0; sp.acc_n = ph.acc_n ? 1 : 0; sp.acc_q = ph.acc_q ? 1 : 0;
   for (int l = 0; l < L; ++l) {
     sp.an[l] = c->at<float>(pl.o_an[l]); sp.dn[l] = c->at<float>(pl.o_dn[l + 1]);
     sp.an_parts[l] = an_parts[l]; sp.an_sg[l] = cap * pl.rparts[l];
@@ -562,11 +588,12 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   }
   sp.sNg = cap;
   sp.loss = c->at<float>(pl.o_loss);
-  sp.n_out = c->at<float>(pl.o_nout); sp.q_out = c->at<float>(pl.o_qout);
-  sp.grad = grad; sp.Ppad = pl.Ppad;
+  if (ph.ps_off >= 0) { sp.n_out = c->at<float>(pl.o_nout) + ph.ps_off; sp.q_out = c->at<float>(pl.o_qout) + ph.ps_off; }
+  sp.grad = ph.s2 ? grad : nullptr; sp.Ppad = pl.Ppad;
   sp.partials = c->at<double>(pl.o_partials); sp.stats = c->at<double>(pl.o_stats);
   { ProfScope ps_(c, T_STATS, 0.0, 4.0 * M * pl.Ppad);
   HIPCHK(c, launch_stats(sp, s)); }
+  if (!ph.update) return ABS_OK;
   // optimizer update (Alg. 1: "local SGD step ... or other inner optimizers")
   c->t += 1;
   UpdateP up;
@@ -584,10 +611,11 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   }
   { ProfScope ps_(c, T_UPDATE, 0.0, 1.0 * M * pl.P * (c->cfg.opt == ABS_OPT_SGD ? 12 : c->cfg.opt == ABS_OPT_ADAMW ? 28 : 20) + (pl.bf16 ? 2.0 * M * pl.P : 0.0));
   HIPCHK(c, launch_update(up, s)); }
-  c->last_b = b;
-  c->last_bm.assign(M, b);
+  c->last_b = ph.b_total > 0 ? ph.b_total : b;
+  c->last_bm.assign(M, c->last_b);
   if (b_host) c->last_bm.assign(b_host, b_host + M);
   c->last_ragged = b_host != nullptr;
+  c->last_ps = -1;
   c->have_stats = true;
   return ABS_OK;
 }
@@ -598,6 +626,53 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   if (b < 2 || b > c->pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
   return local_step_impl(c, idx_dev, b, b, nullptr, lr);
+}
+
+abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b, int micro_b, float lr) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
+  if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
+  const int cap = c->pl.cap;
+  if (micro_b < 2 || micro_b > cap) return cfail(c, ABS_EINVAL, "micro_b must be in [2, b_cap]");
+  if (b < 2) return cfail(c, ABS_EINVAL, "b must be at least 2");
+  if (b % micro_b == 1) return cfail(c, ABS_EINVAL, "the last micro-batch would hold a single sample");
+  const int nmb = (b + micro_b - 1) / micro_b;
+  // pass 1: batch gradient, S1 and the loss, micro-batch by micro-batch; S2 once the gradient is whole
+  for (int j = 0; j < nmb; ++j) {
+    const int off = j * micro_b, mb = b - off < micro_b ? b - off : micro_b;
+    StepPhase ph;
+    ph.ip = false; ph.update = false;
+    ph.s2 = j == nmb - 1;
+    ph.acc_grad = ph.acc_n = j > 0;
+    ph.b_total = b;
+    ph.ps_off = off + mb <= cap ? off : -1;
+    abs_status st = local_step_impl(c, idx_dev + off, b, mb, nullptr, lr, ph);
+    if (st != ABS_OK) return st;
+  }
+  // pass 2: <g_i, gbar> needs the gradient of the whole batch, so the passes run once more
+  if (c->pl.want_ip) {
+    for (int j = 0; j < nmb; ++j) {
+      const int off = j * micro_b, mb = b - off < micro_b ? b - off : micro_b;
+      StepPhase ph;
+      ph.wgrad = ph.nstats = ph.s2 = ph.update = false;
+      ph.acc_q = j > 0;
+      ph.b_total = b;
+      ph.ps_off = off + mb <= cap ? off : -1;
+      abs_status st = local_step_impl(c, idx_dev + off, b, mb, nullptr, lr, ph);
+      if (st != ABS_OK) return st;
+    }
+  }
+  StepPhase up;
+  up.passes = up.wgrad = up.nstats = up.s2 = up.ip = false;
+  up.b_total = b;
+  abs_status st = local_step_impl(c, idx_dev, b, micro_b, nullptr, lr, up);
+  if (st != ABS_OK) return st;
+  c->last_ps = 0;
+  for (int j = 0; j < nmb; ++j) {
+    const int off = j * micro_b, mb = b - off < micro_b ? b - off : micro_b;
+    if (off + mb <= cap) c->last_ps = off + mb;
+  }
+  return ABS_OK;
 }
 
 abs_status abs_local_step_ragged(abs_ctx *c, const int32_t *idx_dev, int ldi, const int *b_host, float lr) {
@@ -777,9 +852,9 @@ abs_status abs_get_per_sample(abs_ctx *c, int m, float *n_host, float *q_host) {
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
   if (q_host && !c->pl.want_ip) return cfail(c, ABS_ESTATE, "stats_mask lacks ABS_STATS_IP");
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  HIPCHK(c, hipMemcpy(n_host, c->at<float>(c->pl.o_nout) + (size_t)m * c->pl.cap, (size_t)c->last_bm[m] * sizeof(float), hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(n_host, c->at<float>(c->pl.o_nout) + (size_t)m * c->pl.cap, (size_t)(c->last_ps >= 0 ? c->last_ps : c->last_bm[m]) * sizeof(float), hipMemcpyDeviceToHost));
   if (q_host)
-    HIPCHK(c, hipMemcpy(q_host, c->at<float>(c->pl.o_qout) + (size_t)m * c->pl.cap, (size_t)c->last_bm[m] * sizeof(float), hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(q_host, c->at<float>(c->pl.o_qout) + (size_t)m * c->pl.cap, (size_t)(c->last_ps >= 0 ? c->last_ps : c->last_bm[m]) * sizeof(float), hipMemcpyDeviceToHost));
   return ABS_OK;
 }
 
@@ -880,6 +955,7 @@ abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M
     sp.an_parts[l] = sp.dn_parts[l] = 1; sp.an_sg[l] = sp.dn_sg[l] = b;
   }
   sp.L = L; sp.has_bias = 0; sp.groups = M; sp.b = b; sp.want_ip = 1; sp.sNg = b;
+  sp.do_n = sp.do_q = 1;
   sp.loss = loss;
   sp.n_out = n_out_dev ? n_out_dev : reinterpret_cast<float *>(ws + off[5]);
   sp.q_out = q_out_dev ? q_out_dev : reinterpret_cast<float *>(ws + off[6]);

@@ -43,6 +43,7 @@ struct GemmP {
   // grid.  Memory beyond a group's own rows is neither read nor written.
   const int *rows;
   int rows_is_k;
+  int accumulate;              // EPI_WGRAD: C = alpha * acc + C  (micro-batch accumulation)
 };
 
 // bf16 MFMA family (gemm_bf16.hip).  Returns the number of column partials that
@@ -81,13 +82,13 @@ hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, 
 enum { COLSUM_ROWS = 128 };
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups,
                           int b, float alpha, float *out, long long sOg, float *scratch, const int *rows,
-                          hipStream_t s);
+                          int accumulate, hipStream_t s);
 // second stage alone: out[g][j] = alpha * sum_r part[g][r][j], r < nsplit (partials from a GEMM epilogue).
 // With rows: alpha = 1 / rows[g] and only the first ceil(rows[g] / tile_m) * parts_per_tile partials
 // of group g exist.
 hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha,
                                  float *out, long long sOg, const int *rows, int tile_m, int parts_per_tile,
-                                 hipStream_t s);
+                                 int accumulate, hipStream_t s);
 // q[g][i] += sum_j D[g][i][j] * U[g][i][j]  (fp32 path of the inner products)
 hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U,
                              long long sUg, int ldu, int cols, int groups, int b, float *q,
@@ -110,6 +111,9 @@ struct StatsP {
   double *partials;         // scratch: [groups][5][PBLK]
   double *stats;            // out: [groups][8] = S1, S2, S3, S4, loss, 0,0,0
   const int *rows;          // optional per-group sample counts (device) replacing b
+  // which sums this launch produces: S1 and the loss (do_n), S3 and S4 (do_q; needs want_ip),
+  // S2 (grad != null); acc_n / acc_q add to the stored sums instead of replacing them
+  int do_n, do_q, acc_n, acc_q;
 };
 enum { STATS_PBLK = 256 };
 hipError_t launch_stats(const StatsP &p, hipStream_t s);

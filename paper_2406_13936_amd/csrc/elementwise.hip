@@ -167,7 +167,8 @@ __global__ void __launch_bounds__(256) col_sum_stage1(const T *__restrict__ X, l
 }
 __global__ void __launch_bounds__(256) col_sum_stage2(const float *__restrict__ part, int cols, int nsplit,
                                                       float alpha, float *__restrict__ out, long long sOg,
-                                                      const int *__restrict__ rows, int tile_m, int parts_per_tile) {
+                                                      const int *__restrict__ rows, int tile_m, int parts_per_tile,
+                                                      int accumulate) {
   const int g = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
   if (c >= cols) return;
   const float *p = part + (long long)g * nsplit * cols + c;
@@ -178,7 +179,8 @@ __global__ void __launch_bounds__(256) col_sum_stage2(const float *__restrict__ 
   }
   float s = 0.0f;
   for (int r = 0; r < ns; ++r) s += p[(long long)r * cols];
-  out[(long long)g * sOg + c] = alpha * s;
+  float *o = out + (long long)g * sOg + c;
+  *o = accumulate ? fmaf(alpha, s, *o) : alpha * s;
 }
 
 __global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, int ldd,
@@ -212,17 +214,19 @@ __global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p) {
   const int bg = p.rows ? p.rows[g] : p.b;
   for (int i = blockIdx.x * 256 + threadIdx.x; i < bg; i += 256 * STATS_PBLK) {
     const long long o = (long long)g * p.sNg + i;
-    float n = 0.0f;
-    for (int l = 0; l < p.L; ++l) {
-      float a = 0.0f, d = 0.0f;
-      for (int k = 0; k < p.an_parts[l]; ++k) a += p.an[l][(long long)g * p.an_sg[l] + (long long)k * p.sNg + i];
-      for (int k = 0; k < p.dn_parts[l]; ++k) d += p.dn[l][(long long)g * p.dn_sg[l] + (long long)k * p.sNg + i];
-      n = fmaf(d, a + hb, n);
+    if (p.do_n) {
+      float n = 0.0f;
+      for (int l = 0; l < p.L; ++l) {
+        float a = 0.0f, d = 0.0f;
+        for (int k = 0; k < p.an_parts[l]; ++k) a += p.an[l][(long long)g * p.an_sg[l] + (long long)k * p.sNg + i];
+        for (int k = 0; k < p.dn_parts[l]; ++k) d += p.dn[l][(long long)g * p.dn_sg[l] + (long long)k * p.sNg + i];
+        n = fmaf(d, a + hb, n);
+      }
+      if (p.n_out) p.n_out[o] = n;
+      s1 += (double)n;
+      sl += (double)p.loss[o];
     }
-    if (p.n_out) p.n_out[o] = n;
-    s1 += (double)n;
-    sl += (double)p.loss[o];
-    if (p.want_ip) {
+    if (p.do_q) {
       float q = 0.0f;
       for (int l = 0; l < p.L; ++l) {
         const float *qp = p.qpart[l] + (long long)g * p.sQg[l] + i;
@@ -259,15 +263,17 @@ __global__ void __launch_bounds__(256) stats_gradsq_kernel(const float *__restri
 }
 
 // Stage 2 (grid: groups): add the PBLK partials of each of the five sums in index order.
+// sel / acc: bit k set = sum k is produced by this launch / is added to the stored value.
 __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restrict__ partials,
-                                                          double *__restrict__ stats) {
+                                                          double *__restrict__ stats, int sel, int acc) {
   __shared__ double red[4];
   const int g = blockIdx.x;
   static_assert(STATS_PBLK == 256, "one partial per thread");
   for (int k = 0; k < 5; ++k) {
+    if (!((sel >> k) & 1)) continue;
     const double v = partials[((long long)g * 5 + k) * STATS_PBLK + threadIdx.x];
     const double r = block_sum<4>(v, red);
-    if (threadIdx.x == 0) stats[g * 8 + k] = r;
+    if (threadIdx.x == 0) stats[g * 8 + k] = ((acc >> k) & 1) ? stats[g * 8 + k] + r : r;
   }
 }
 
@@ -477,7 +483,8 @@ hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, 
 }
 
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
-                          float alpha, float *out, long long sOg, float *scratch, const int *rows, hipStream_t s) {
+                          float alpha, float *out, long long sOg, float *scratch, const int *rows, int accumulate,
+                          hipStream_t s) {
   const int nsplit = (b + COLSUM_ROWS - 1) / COLSUM_ROWS;
   const dim3 grid((cols + 63) / 64, nsplit, groups), blk(256);
   if (is_bf16)
@@ -488,14 +495,15 @@ hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int
                        scratch, nsplit, rows);
   // stage 1 writes every partial (zeros past a group's rows), so stage 2 adds all of them
   hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, scratch, cols, nsplit,
-                     alpha, out, sOg, rows, 0, 0);
+                     alpha, out, sOg, rows, 0, 0, accumulate);
   return hipGetLastError();
 }
 
 hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha, float *out,
-                                 long long sOg, const int *rows, int tile_m, int parts_per_tile, hipStream_t s) {
+                                 long long sOg, const int *rows, int tile_m, int parts_per_tile, int accumulate,
+                                 hipStream_t s) {
   hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, part, cols, nsplit,
-                     alpha, out, sOg, rows, tile_m, parts_per_tile);
+                     alpha, out, sOg, rows, tile_m, parts_per_tile, accumulate);
   return hipGetLastError();
 }
 
@@ -508,11 +516,17 @@ hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float
 }
 
 hipError_t launch_stats(const StatsP &p, hipStream_t s) {
-  hipLaunchKernelGGL(stats_samples_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p);
+  if (p.do_q && !p.want_ip) return hipErrorInvalidValue;
+  int sel = 0, acc = 0;
+  if (p.do_n) { sel |= 1 | 16; if (p.acc_n) acc |= 1 | 16; }
+  if (p.do_q) { sel |= 4 | 8; if (p.acc_q) acc |= 4 | 8; }
+  if (p.grad) sel |= 2;
+  if (!sel) return hipSuccess;
+  if (p.do_n || p.do_q) hipLaunchKernelGGL(stats_samples_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p);
   if (p.grad)
     hipLaunchKernelGGL(stats_gradsq_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.grad, p.Ppad,
                        p.partials);
-  hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats);
+  hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats, sel, acc);
   return hipGetLastError();
 }
 

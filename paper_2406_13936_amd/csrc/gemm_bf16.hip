@@ -468,6 +468,10 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
           o4[e] = (EPI == EPI_WGRAD) ? v * p.alpha : v + ((bias && n + e < p.Nd) ? bias[n + e] : 0.0f);
         }
         float *crow = static_cast<float *>(p.C) + (long long)g * p.sCg + (long long)m * p.ldc + n;
+        if (EPI == EPI_WGRAD && p.accumulate) {             // micro-batch accumulation: C += alpha * acc
+#pragma unroll
+          for (int e = 0; e < 4; ++e) if (n + e < p.Nd) o4[e] += crow[e];
+        }
         if (n + 4 <= p.Nd && (p.ldc & 3) == 0) {
           *reinterpret_cast<float4 *>(crow) = make_float4(o4[0], o4[1], o4[2], o4[3]);
         } else {

@@ -94,7 +94,10 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
           static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = o;
         }
       } else if (EPI == EPI_WGRAD) {
-        if (nin) static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = v * p.alpha;
+        if (nin) {
+          float *o = static_cast<float *>(p.C) + (long long)g * p.sCg + (long long)m * p.ldc + n;
+          *o = p.accumulate ? fmaf(v, p.alpha, *o) : v * p.alpha;
+        }
       }
     }
   }

@@ -417,6 +417,86 @@ def test_per_worker_schedule_lockstep_fp32():
 
 
 # ---------------------------------------------------------------------------------------------
+# gradient accumulation over micro-batches
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("prec,dims,act,b,micro,cap,opt,test", [
+    (W.PREC_F32, (72, 130, 66, 5), W.ACT_GELU, 150, 64, 150, W.OPT_SHB, W.TEST_AUG_IP),
+    (W.PREC_F32, (256, 10), W.ACT_NONE, 96, 32, 32, W.OPT_SGD, W.TEST_NORM),
+    (W.PREC_BF16, (384, 256, 256, 100), W.ACT_GELU, 700, 256, 256, W.OPT_ADAMW, W.TEST_AUG_IP),
+    (W.PREC_BF16, (784, 512, 512, 10), W.ACT_RELU, 300, 128, 300, W.OPT_SGD, W.TEST_NORM),
+    (W.PREC_BF16, (1024, 1024, 1024, 100), W.ACT_RELU, 2124, 1024, 1024, W.OPT_SHB, W.TEST_IP),   # 256x256 tiles
+])
+def test_accumulated_step_matches_full_batch_oracle(prec, dims, act, b, micro, cap, opt, test):
+    A = _A()
+    M = 2
+    w = W.Workload("accum", dims, act, True, prec, N=4096, M=M, H=1, rounds=1, b0=b, b_cap=cap, opt=opt, lr=0.02,
+                   momentum=0.9, weight_decay=0.05, test=test, eta=0.5, theta=0.9, nu=0.5,
+                   data="mixture" if len(dims) == 2 else "teacher_mlp", seed=19)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    mixed = prec == W.PREC_BF16
+    orc = _oracle_for(w, X, y, x0, mixed=mixed)
+    tol = 2e-3 if mixed else 1e-4
+    try:
+        idx = W.step_indices(w, 0, 0, b)
+        rep.local_step_accumulated(idx, micro, w.lr)
+        orc.local_step(idx, w.lr)                        # the oracle takes the whole batch at once
+        g, o = _gpu_test(rep, w), orc.test(test, w.eta, w.theta, w.nu)
+        stored = max(off + min(micro, b - off) for off in range(0, b, micro) if off + min(micro, b - off) <= cap)
+        for m in range(M):
+            s = orc.stats[m]
+            assert g[m].b == b
+            grad = rep.get_grad(m).astype(np.float64)
+            assert np.abs(grad - orc.grads[m]).max() <= (2e-3 if mixed else 1e-5) * np.abs(orc.grads[m]).max()
+            n, q = rep.get_per_sample(m, stored, want_q=test != W.TEST_NORM)
+            np.testing.assert_allclose(n, s["n"][:stored], rtol=5e-3 if mixed else 1e-4)
+            names = [("S1", g[m].sum_sq, s["S1"]), ("S2", g[m].gbar_sq, s["S2"]), ("loss", g[m].loss_sum, s["loss_sum"])]
+            if test != W.TEST_NORM:
+                np.testing.assert_allclose(q, s["q"][:stored], rtol=2e-2 if mixed else 1e-3,
+                                           atol=(2e-3 if mixed else 1e-5) * np.abs(s["q"]).max())
+                names += [("S3", g[m].sum_q2, s["S3"]), ("S4", g[m].sum_q, s["S4"])]
+            for name, got, want in names:
+                assert _rel(got, want) <= tol, (m, name, got, want)
+            assert _rel(g[m].ratio, o[m]["ratio"]) <= 20 * tol, (g[m].ratio, o[m]["ratio"])
+            p = rep.get_params(m).astype(np.float64)
+            sel = np.ones(p.size, dtype=bool)
+            if opt == W.OPT_ADAMW:
+                sel = np.abs(orc.grads[m]) >= 1e-2 * np.abs(orc.grads[m]).max()
+            assert np.abs(p - orc.x[m])[sel].max() <= (1e-3 if mixed else 1e-5) * np.abs(orc.x[m]).max()
+        with pytest.raises(A.AbsError, match="single sample"):
+            rep.local_step_accumulated(W.step_indices(w, 0, 1, 2 * micro + 1), micro, w.lr)
+        with pytest.raises(A.AbsError, match="micro_b"):
+            rep.local_step_accumulated(idx, cap + 1, w.lr)
+    finally:
+        rep.close()
+
+
+def test_accumulated_step_in_one_micro_batch_is_bitwise_the_plain_step():
+    A = _A()
+    w = _one_step_case((384, 256, 256, 100), W.ACT_GELU, W.PREC_BF16, 200, 2, opt=W.OPT_SHB, N=1024)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    idx = W.step_indices(w, 0, 0, 200)
+    out = []
+    for accumulated in (False, True):
+        rep = A.Replicas.from_workload(w, X, y, x0)
+        try:
+            if accumulated:
+                rep.local_step_accumulated(idx, 200, w.lr)
+            else:
+                rep.local_step(idx, w.lr)
+            r = rep.inner_product_test(w.theta)
+            out.append(([rep.get_params(m) for m in range(2)], [(t.sum_sq, t.gbar_sq, t.sum_q, t.sum_q2) for t in r]))
+        finally:
+            rep.close()
+    assert out[0][1] == out[1][1]
+    for m in range(2):
+        assert np.array_equal(out[0][0][m], out[1][0][m])
+
+
+# ---------------------------------------------------------------------------------------------
 # structure, edge cases, error paths
 # ---------------------------------------------------------------------------------------------
 
