@@ -15,8 +15,12 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
   __bf16 b = static_cast<__bf16>(f);
   return __builtin_bit_cast(uint16_t, b);
 }
+// two floats -> packed bfloat16 pair (lo in bits 0..15), one v_cvt_pk_bf16_f32
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
-  return static_cast<uint32_t>(f2bf(lo)) | (static_cast<uint32_t>(f2bf(hi)) << 16);
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 template <class T> struct Elem;
@@ -37,13 +41,13 @@ template <> struct Elem<bf16_t> {
 // exponential with the density, so value and derivative cost one v_exp and one v_rcp.
 __device__ __forceinline__ void gelu_fwd(float z, float &a, float &d) {
   const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
-  const float e = __expf(-x * x);                       // = exp(-z^2/2)
-  float poly = fmaf(1.061405429f, t, -1.453152027f);
-  poly = fmaf(poly, t, 1.421413741f);
-  poly = fmaf(poly, t, -0.284496736f);
-  poly = fmaf(poly, t, 0.254829592f);
-  const float half_erfc = 0.5f * poly * t * e;          // 0.5 erfc(|z|/sqrt 2)
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));         // v_rcp_f32, 1 ulp
+  const float e = __builtin_amdgcn_exp2f(z * z * -0.72134752044448170f);    // exp(-z^2/2) = 2^(-z^2 log2(e)/2)
+  float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);          // coefficients carry the 1/2 of erfc/2
+  poly = fmaf(poly, t, 0.5f * 1.421413741f);
+  poly = fmaf(poly, t, 0.5f * -0.284496736f);
+  poly = fmaf(poly, t, 0.5f * 0.254829592f);
+  const float half_erfc = poly * t * e;                 // 0.5 erfc(|z|/sqrt 2)
   const float cdf = z >= 0.0f ? 1.0f - half_erfc : half_erfc;
   a = z * cdf;
   d = fmaf(z * 0.39894228040143268f, e, cdf);

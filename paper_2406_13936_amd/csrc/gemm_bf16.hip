@@ -264,6 +264,24 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   constexpr int SIT = 32 * CPRW / 64;                       // chunks per lane per slice
   static_assert(32 * CPRW % 64 == 0, "staging slice");
   const int nw0 = n0 + wn * TN;                             // first column of this wave
+  const bool nfull = n0 + BN <= p.Nd;                       // no ragged columns in this tile (uniform)
+  // this lane's 4-column groups of the bias vector, loaded once for all row slices
+  float bv[NI][4][4];
+  if (EPI == EPI_FWD_ACT || EPI == EPI_IPDOT || EPI == EPI_LOGITS) {
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = nw0 + j * 32 + q * 8 + lhalf * 4;
+        if (bias && nfull) {
+          const float4 b4 = *reinterpret_cast<const float4 *>(bias + n);
+          bv[j][q][0] = b4.x; bv[j][q][1] = b4.y; bv[j][q][2] = b4.z; bv[j][q][3] = b4.w;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[j][q][e] = (bias && n + e < p.Nd) ? bias[n + e] : 0.0f;
+        }
+      }
+  }
 
   // global -> staging of rows [mrow0, mrow0+32) x this wave's TN columns of a bf16 matrix
   auto stage_in = [&](const bf16_t *src, int ld, int mrow0, int ncols) {
@@ -289,6 +307,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   auto piece = [&](int j, int q) -> bf16_t * { return stg + lcol * SLD + j * 32 + q * 8 + lhalf * 4; };
 
   if (EPI == EPI_FWD_ACT || EPI == EPI_BWD || EPI == EPI_IPDOT) __syncthreads();   // stages are dead
+  static_assert(32 * (TN / 4) % 64 == 0, "fp32 staging slice");
 
   float *red = reinterpret_cast<float *>(smem + NW * 32 * SLD);   // [WN][BM] row partials of the waves
   // add the WN waves' row partials in wave order and write part[g][tn][m]
@@ -325,9 +344,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
                                __uint_as_float(ev.y << 16), __uint_as_float(ev.y & 0xffff0000u)};
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
-            const float bv = (bias && n < p.Nd) ? bias[n] : 0.0f;
-            rs = fmaf(e4[e], acc[i][j][4 * q + e] + bv, rs);      // E is zero outside the matrix
+            rs = fmaf(e4[e], acc[i][j][4 * q + e] + bv[j][q][e], rs);   // E is zero outside the matrix
           }
         }
       rs += __shfl_xor(rs, 32, 64);                               // the two column halves of the row
@@ -353,9 +370,9 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
           float a4[4], d4[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
-            a4[e] = 0.0f; d4[e] = 0.0f;
-            if (n < p.Nd) act_fwd<ACT>(acc[i][j][4 * q + e] + (bias ? bias[n] : 0.0f), a4[e], d4[e]);
+            // columns beyond Nd: accumulator and bias are both zero there (operand rows past the
+            // matrix read as zeros), so phi(0) = 0 is what the pad columns of C receive
+            act_fwd<ACT>(acc[i][j][4 * q + e] + bv[j][q][e], a4[e], d4[e]);
           }
           uint2 apk;
           apk.x = pack2bf(a4[0], a4[1]); apk.y = pack2bf(a4[2], a4[3]);
@@ -410,10 +427,9 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
           float o4[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
             const float v = acc[i][j][4 * q + e];
             o4[e] = (ACT == ACT_RELU) ? (e4[e] > 0.0f ? v : 0.0f) : (ACT == ACT_GELU ? v * e4[e] : v);
-            if (n >= p.Nd) o4[e] = 0.0f;
+            if (!nfull && nw0 + j * 32 + q * 8 + lhalf * 4 + e >= p.Nd) o4[e] = 0.0f;
           }
           uint2 opk;
           opk.x = pack2bf(o4[0], o4[1]); opk.y = pack2bf(o4[2], o4[3]);
@@ -450,46 +466,64 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
     return;
   }
 
-  // fp32 outputs (weight gradient, logits): direct stores, four consecutive columns per lane
+  // fp32 outputs (weight gradient, logits).  A lane holds one row and groups of four columns, so
+  // direct stores would scatter 16-byte pieces over 32 rows per instruction; instead each wave
+  // passes its 32 x TN slice through an fp32 staging area in LDS and writes whole row segments
+  // (16 lanes x 16 bytes = 256 contiguous bytes per row).
+  constexpr int FLD = TN + 4;                               // staging row stride (floats)
+  constexpr int FCPR = TN / 4;                              // float4 chunks per staged row
+  constexpr int FIT = 32 * FCPR / 64;                       // chunks per lane per slice
+  float *stf = reinterpret_cast<float *>(smem) + wave * (32 * FLD);
+  float *Cg = static_cast<float *>(p.C) + (long long)g * p.sCg;
+  bf16_t *C2g = (EPI == EPI_WGRAD && p.C2) ? static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g : nullptr;
+  const bool vec_ok = (p.ldc & 3) == 0 && (!C2g || (p.ldc2 & 3) == 0);
+  const bool accumulate = EPI == EPI_WGRAD && p.accumulate;  // micro-batch accumulation: C += alpha * acc
+  __syncthreads();                                          // stages are dead
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
-    const int m = m0 + wm * TM + i * 32 + lcol;
-    if (m >= p.Md) continue;
+    const int mrow0 = m0 + wm * TM + i * 32;
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = nw0 + j * 32 + q * 8 + lhalf * 4;
-        if (n >= p.Nd) continue;
-        float o4[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float v = acc[i][j][4 * q + e];
-          o4[e] = (EPI == EPI_WGRAD) ? v * p.alpha : v + ((bias && n + e < p.Nd) ? bias[n + e] : 0.0f);
-        }
-        float *crow = static_cast<float *>(p.C) + (long long)g * p.sCg + (long long)m * p.ldc + n;
-        if (EPI == EPI_WGRAD && p.accumulate) {             // micro-batch accumulation: C += alpha * acc
-#pragma unroll
-          for (int e = 0; e < 4; ++e) if (n + e < p.Nd) o4[e] += crow[e];
-        }
-        if (n + 4 <= p.Nd && (p.ldc & 3) == 0) {
-          *reinterpret_cast<float4 *>(crow) = make_float4(o4[0], o4[1], o4[2], o4[3]);
+        float4 o;
+        if (EPI == EPI_WGRAD) {
+          o = make_float4(acc[i][j][4 * q] * p.alpha, acc[i][j][4 * q + 1] * p.alpha, acc[i][j][4 * q + 2] * p.alpha,
+                          acc[i][j][4 * q + 3] * p.alpha);
         } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) if (n + e < p.Nd) crow[e] = o4[e];
+          o = make_float4(acc[i][j][4 * q] + bv[j][q][0], acc[i][j][4 * q + 1] + bv[j][q][1],
+                          acc[i][j][4 * q + 2] + bv[j][q][2], acc[i][j][4 * q + 3] + bv[j][q][3]);
         }
-        if (EPI == EPI_WGRAD && p.C2) {
-          bf16_t *c2 = static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g + (long long)m * p.ldc2 + n;
-          if (n + 4 <= p.Nd && (p.ldc2 & 3) == 0) {
-            uint2 o;
-            o.x = pack2bf(o4[0], o4[1]); o.y = pack2bf(o4[2], o4[3]);
-            *reinterpret_cast<uint2 *>(c2) = o;
-          } else {
+        *reinterpret_cast<float4 *>(stf + lcol * FLD + j * 32 + q * 8 + lhalf * 4) = o;
+      }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) if (n + e < p.Nd) c2[e] = f2bf(o4[e]);
-          }
+    for (int it = 0; it < FIT; ++it) {
+      const int c = it * 64 + lane, row = c / FCPR, cc = c % FCPR;
+      const int m = mrow0 + row, n = nw0 + cc * 4;
+      if (m >= p.Md || n >= p.Nd) continue;
+      float4 v = *reinterpret_cast<const float4 *>(stf + row * FLD + cc * 4);
+      float *crow = Cg + (long long)m * p.ldc + n;
+      if (n + 4 <= p.Nd && vec_ok) {
+        if (accumulate) {
+          const float4 old = *reinterpret_cast<const float4 *>(crow);
+          v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+        }
+        *reinterpret_cast<float4 *>(crow) = v;
+        if (C2g) {
+          uint2 o;
+          o.x = pack2bf(v.x, v.y); o.y = pack2bf(v.z, v.w);
+          *reinterpret_cast<uint2 *>(C2g + (long long)m * p.ldc2 + n) = o;
+        }
+      } else {
+        const float v4[4] = {v.x, v.y, v.z, v.w};
+        for (int e = 0; e < 4; ++e) {
+          if (n + e >= p.Nd) break;
+          const float r = accumulate ? v4[e] + crow[e] : v4[e];
+          crow[e] = r;
+          if (C2g) C2g[(long long)m * p.ldc2 + n + e] = f2bf(r);
         }
       }
+    }
   }
 }
 
@@ -497,7 +531,9 @@ template <int BM, int BN, int BK, int WM, int WN, int NS, bool AT, bool BT, int 
 hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
   constexpr int NT = WM * WN * 64;
   constexpr size_t tile_bytes = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
-  constexpr size_t epi_bytes = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(bf16_t) + (size_t)WN * BM * sizeof(float);
+  constexpr size_t epi_bf16 = (size_t)WM * WN * 32 * (BN / WN + 8) * sizeof(bf16_t) + (size_t)WN * BM * sizeof(float);
+  constexpr size_t epi_f32 = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
+  constexpr size_t epi_bytes = epi_bf16 > epi_f32 ? epi_bf16 : epi_f32;
   constexpr size_t lds = tile_bytes > epi_bytes ? tile_bytes : epi_bytes;
   static_assert(lds <= 160 * 1024, "LDS budget");
   auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, NS, AT, BT, EPI, ACT>;
