@@ -283,17 +283,28 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
       }
   }
 
-  // global -> staging of rows [mrow0, mrow0+32) x this wave's TN columns of a bf16 matrix
-  auto stage_in = [&](const bf16_t *src, int ld, int mrow0, int ncols) {
+  // rows [mrow0, mrow0+32) x this wave's TN columns of a bf16 matrix: global -> registers (so the
+  // next slice can be in flight while the current one is processed), registers -> staging
+  auto load_slice = [&](const bf16_t *src, int ld, int mrow0, int ncols, uint4 (&r)[SIT]) {
 #pragma unroll
     for (int it = 0; it < SIT; ++it) {
       const int c = it * 64 + lane, row = c / CPRW, cc = c % CPRW;
-      uint4 v = make_uint4(0, 0, 0, 0);
+      r[it] = make_uint4(0, 0, 0, 0);
       if (mrow0 + row < p.Md && nw0 + cc * 8 < ncols)
-        v = *reinterpret_cast<const uint4 *>(src + (long long)(mrow0 + row) * ld + nw0 + cc * 8);
-      *reinterpret_cast<uint4 *>(stg + row * SLD + cc * 8) = v;
+        r[it] = *reinterpret_cast<const uint4 *>(src + (long long)(mrow0 + row) * ld + nw0 + cc * 8);
     }
   };
+  auto put_slice = [&](const uint4 (&r)[SIT]) {
+#pragma unroll
+    for (int it = 0; it < SIT; ++it) {
+      const int c = it * 64 + lane, row = c / CPRW, cc = c % CPRW;
+      *reinterpret_cast<uint4 *>(stg + row * SLD + cc * 8) = r[it];
+    }
+  };
+  uint4 ereg[2][SIT];
+  const bf16_t *Eg = p.E ? static_cast<const bf16_t *>(p.E) + (long long)g * p.sEg : nullptr;
+  constexpr bool USES_E = EPI == EPI_IPDOT || (EPI == EPI_BWD && ACT != ACT_NONE);
+  if (USES_E) load_slice(Eg, p.lde, m0 + wm * TM, p.Nd, ereg[0]);
   // staging -> global
   auto stage_out = [&](bf16_t *dst, int ld, int mrow0, int ncols) {
 #pragma unroll
@@ -329,11 +340,11 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   };
 
   if (EPI == EPI_IPDOT) {
-    const bf16_t *E = static_cast<const bf16_t *>(p.E) + (long long)g * p.sEg;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int mrow0 = m0 + wm * TM + i * 32;
-      stage_in(E, p.lde, mrow0, p.Nd);
+      if (i + 1 < MI) load_slice(Eg, p.lde, mrow0 + 32, p.Nd, ereg[(i + 1) & 1]);
+      put_slice(ereg[i & 1]);
       float rs = 0.0f;
 #pragma unroll
       for (int j = 0; j < NI; ++j)
@@ -399,20 +410,18 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
 
   if (EPI == EPI_BWD) {
     bf16_t *C = static_cast<bf16_t *>(p.C) + (long long)g * p.sCg;
-    const bf16_t *E = static_cast<const bf16_t *>(p.E) + (long long)g * p.sEg;
     const int ncols = p.pad_to_ld ? p.ldc : p.Nd;
-    float cs[NI][4][4];                                  // column sums over this wave's rows
+    static_assert(TN % 64 == 0 || TN == 32, "column sums: lanes map to columns");
+    float cs[(TN + 63) / 64];                            // column sums over this wave's rows, one column per lane
 #pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) cs[j][q][e] = 0.0f;
+    for (int c = 0; c < (TN + 63) / 64; ++c) cs[c] = 0.0f;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int mrow0 = m0 + wm * TM + i * 32;
-      const bool row_in = mrow0 + lcol < p.Md;
-      if (ACT != ACT_NONE) stage_in(E, p.lde, mrow0, p.Nd);
+      if (ACT != ACT_NONE) {
+        if (i + 1 < MI) load_slice(Eg, p.lde, mrow0 + 32, p.Nd, ereg[(i + 1) & 1]);
+        put_slice(ereg[i & 1]);
+      }
       float rs = 0.0f;
 #pragma unroll
       for (int j = 0; j < NI; ++j)
@@ -435,32 +444,32 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
           opk.x = pack2bf(o4[0], o4[1]); opk.y = pack2bf(o4[2], o4[3]);
           *reinterpret_cast<uint2 *>(piece(j, q)) = opk;      // each lane overwrites the piece it read
           rs += sq4(opk);
-          if (p.cpart && row_in) {                            // rows beyond the batch hold no signal
-            cs[j][q][0] += __uint_as_float(opk.x << 16); cs[j][q][1] += __uint_as_float(opk.x & 0xffff0000u);
-            cs[j][q][2] += __uint_as_float(opk.y << 16); cs[j][q][3] += __uint_as_float(opk.y & 0xffff0000u);
-          }
         }
       if (p.part) {
         rs += __shfl_xor(rs, 32, 64);
         if (lhalf == 0) red[wn * BM + wm * TM + i * 32 + lcol] = rs;
       }
       stage_out(C, p.ldc, mrow0, ncols);
+      if (p.cpart) {
+        // bias-gradient partials: a lane adds its column of the staged slice, rows in order (rows
+        // past the batch were computed from zero operands and hold zeros)
+#pragma unroll
+        for (int c = 0; c < (TN + 63) / 64; ++c) {
+          const int col = c * 64 + lane;
+          if (col < TN) {
+#pragma unroll
+            for (int r = 0; r < 32; ++r) cs[c] += bf2f(stg[r * SLD + col]);
+          }
+        }
+      }
     }
     if (p.cpart) {
-      // add over the 32 lanes that share a column group (fixed order: xor butterfly)
       float *cp = p.cpart + (long long)g * p.sCpartg + (long long)(tm * WM + wm) * p.Nd;
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float v = cs[j][q][e];
-#pragma unroll
-            for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-            const int n = nw0 + j * 32 + q * 8 + lhalf * 4 + e;
-            if (lcol == 0 && n < p.Nd) cp[n] = v;
-          }
+      for (int c = 0; c < (TN + 63) / 64; ++c) {
+        const int n = nw0 + c * 64 + lane;
+        if (c * 64 + lane < TN && n < p.Nd) cp[n] = cs[c];
+      }
     }
     if (p.part) finish_rows();
     return;
