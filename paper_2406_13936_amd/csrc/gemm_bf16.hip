@@ -71,7 +71,7 @@ struct Operand {
         kofs[i] = kc * 8;
         voff[i] = (row0 + row < rows) ? (uint32_t)((row0 + row) * ld + kc * 8) * 2u : OOB;
       } else {
-        const int kq = c / CH, ch = (c % CH) ^ (2 * (kq & 3));
+        const int kq = c / CH, ch = (c % CH) ^ ((4 * (kq & 3)) & (CH - 1));
         kofs[i] = kq;
         voff[i] = (row0 + ch * 8 < rows) ? (uint32_t)(kq * ld + row0 + ch * 8) * 2u : OOB;
       }
@@ -106,8 +106,10 @@ struct Frag {
       const int i16 = lane & 15, g16 = lane >> 4;
       const int rr = r0 + (g16 & 1) * 16 + 4 * (i16 & 3);     // first of this lane's 4 rows
       const int kq = (g16 >> 1) * 8 + (i16 >> 2);             // k within the 16-wide step
-      // the chunk swizzle 2*(k&3) does not depend on kk (16 | step) nor on the +4 of the 2nd read
-      const int ch = (rr >> 3) ^ (2 * (kq & 3));
+      // the chunk swizzle 4*(k&3) does not depend on kk (16 | step) nor on the +4 of the 2nd read.
+      // A 32-lane half of the read covers 4 values of k x 4 chunks (16 bytes each, two lanes per
+      // chunk): XOR-ing k&3 into chunk bits 2..3 spreads these 16 chunks over all 64 banks.
+      const int ch = (rr >> 3) ^ ((4 * (kq & 3)) & (CH - 1));
       tbase[0] = kq * ROWS + ch * 8 + (rr & 7);
       tbase[1] = tbase[0] + 4 * ROWS;
     }
