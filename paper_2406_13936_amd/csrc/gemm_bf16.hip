@@ -40,6 +40,28 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 namespace {
 
+// Epilogue outputs and the elementwise operand are touched once per launch: non-temporal accesses
+// keep them from displacing the operand tiles that other work-groups of the launch re-read from L2.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_once(const bf16_t *p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_once(bf16_t *p, uint4 v) {
+  const u32x4_t w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t *>(p));
+}
+__device__ __forceinline__ void st_once(bf16_t *p, uint2 v) {
+  const u32x2_t w = {v.x, v.y};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x2_t *>(p));
+}
+__device__ __forceinline__ void st_once(float *p, float4 v) {
+  const f32x4_t w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t *>(p));
+}
+
 constexpr uint32_t OOB = 0x80000000u;   // byte offset beyond any operand (operands are < 2 GiB)
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -293,7 +315,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
       const int c = it * 64 + lane, row = c / CPRW, cc = c % CPRW;
       r[it] = make_uint4(0, 0, 0, 0);
       if (mrow0 + row < p.Md && nw0 + cc * 8 < ncols)
-        r[it] = *reinterpret_cast<const uint4 *>(src + (long long)(mrow0 + row) * ld + nw0 + cc * 8);
+        r[it] = ld_once(src + (long long)(mrow0 + row) * ld + nw0 + cc * 8);
     }
   };
   auto put_slice = [&](const uint4 (&r)[SIT]) {
@@ -314,7 +336,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
       const int c = it * 64 + lane, row = c / CPRW, cc = c % CPRW;
       const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * SLD + cc * 8);
       if (mrow0 + row < p.Md && nw0 + cc * 8 < ncols)
-        *reinterpret_cast<uint4 *>(dst + (long long)(mrow0 + row) * ld + nw0 + cc * 8) = v;
+        st_once(dst + (long long)(mrow0 + row) * ld + nw0 + cc * 8, v);
     }
   };
   auto piece = [&](int j, int q) -> bf16_t * { return stg + lcol * SLD + j * 32 + q * 8 + lhalf * 4; };
@@ -519,11 +541,11 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
           const float4 old = *reinterpret_cast<const float4 *>(crow);
           v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
         }
-        *reinterpret_cast<float4 *>(crow) = v;
+        st_once(crow, v);
         if (C2g) {
           uint2 o;
           o.x = pack2bf(v.x, v.y); o.y = pack2bf(v.z, v.w);
-          *reinterpret_cast<uint2 *>(C2g + (long long)m * p.ldc2 + n) = o;
+          st_once(C2g + (long long)m * p.ldc2 + n, o);
         }
       } else {
         const float v4[4] = {v.x, v.y, v.z, v.w};
