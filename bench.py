@@ -256,12 +256,12 @@ def main():
         "config": {"workload": w.name, "dims": list(w.dims), "M": w.M, "H": w.H,
                    "local_batch": "adaptive from b0=%d" % w.b0 if a.adaptive else b_fixed,
                    "schedule": sched if a.adaptive else None,
-                   "optimizer": ["sgd", "shb", "adamw"][w.opt],
+                   "optimizer": ["sgd", "shb", "adamw", "adagrad"][w.opt],
                    "test": ["norm", "inner_product", "augmented_inner_product"][w.test]},
         "roofline": roof, "kernels": kernels,
     }
     if not a.no_cpu_baseline:
-        sb = a.cpu_sample_batch or {"config1": 512, "config2": 512, "config3": 64, "config4": 32}[a.workload]
+        sb = a.cpu_sample_batch or {"config1": 512, "config2": 512, "config3": 256, "config4": 128}[a.workload]
         out["cpu_baseline"] = cpu_baseline(w, X, y, x0, min(sb, w.b_cap))
     print(json.dumps(out))
 
