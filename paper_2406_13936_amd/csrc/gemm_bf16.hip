@@ -141,13 +141,33 @@ struct Frag {
       const int kc = kk * 2 + (threadIdx.x >> 5 & 1);
       return *reinterpret_cast<const bf16x8 *>(stage + base + ((kc ^ swz) << 3));
     } else {
-      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + tbase[0] + kk * 16 * ROWS));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + tbase[1] + kk * 16 * ROWS));
+      // Issued as inline assembly: through the builtin the compiler cannot tell that this read
+      // does not alias the direct-to-LDS loads in flight (they fill the other stage buffer) and
+      // puts s_waitcnt vmcnt(0) in front of every group of reads, which serialises the pipeline.
+      // The price is that the compiler no longer counts these reads in lgkmcnt: the main loop
+      // waits for them itself (wait_frags) before the MFMAs that use them.
+      const uint32_t a0 = (uint32_t)(uintptr_t)(lds_void *)(stage + tbase[0] + kk * 16 * ROWS);
+      const uint32_t a1 = (uint32_t)(uintptr_t)(lds_void *)(stage + tbase[1] + kk * 16 * ROWS);
+      s16x4 lo, hi;
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a0) : "memory");
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(a1) : "memory");
       const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       return __builtin_bit_cast(bf16x8, v);
     }
   }
 };
+
+// Wait until at most N LDS operations of this wave are outstanding, and make the fragments that
+// the following MFMAs read depend on that wait (needed where fragment reads are inline assembly).
+template <int N, int MI, int NI>
+__device__ __forceinline__ void wait_frags(bf16x8 (&a)[MI], bf16x8 (&b)[NI]) {
+  static_assert(N >= 0 && N <= 15, "lgkmcnt range");
+  __builtin_amdgcn_s_waitcnt(0xC07F | (N << 8));          // vmcnt, expcnt: no wait; lgkmcnt = N
+#pragma unroll
+  for (int i = 0; i < MI; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+  for (int j = 0; j < NI; ++j) asm volatile("" : "+v"(b[j]));
+}
 
 // ---- the kernel --------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WM, int WN, int NS, bool AT, bool BT, int EPI, int ACT>
@@ -246,20 +266,40 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
     // group's share of the next stage's global loads are issued before the MFMAs of group kk,
     // which then run as one raised-priority cluster
     bf16x8 af[2][MI], bfr[2][NI];
+    // transpose reads (untracked by the compiler's lgkmcnt accounting) go first, so that the
+    // newest outstanding reads are always the ones the compiler counts
+    if (BT && !AT) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bfr[0][j] = fb[j].read(S + BM * BK, 0);
+    }
 #pragma unroll
     for (int i = 0; i < MI; ++i) af[0][i] = fa[i].read(S, 0);
+    if (!(BT && !AT)) {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) bfr[0][j] = fb[j].read(S + BM * BK, 0);
+      for (int j = 0; j < NI; ++j) bfr[0][j] = fb[j].read(S + BM * BK, 0);
+    }
 #pragma unroll
     for (int kk = 0; kk < NPART; ++kk) {
       const int cur = kk & 1, nxt = cur ^ 1;
       if (kk + 1 < NPART) {
+        if (BT && !AT) {
+#pragma unroll
+          for (int j = 0; j < NI; ++j) bfr[nxt][j] = fb[j].read(S + BM * BK, kk + 1);
+        }
 #pragma unroll
         for (int i = 0; i < MI; ++i) af[nxt][i] = fa[i].read(S, kk + 1);
+        if (!(BT && !AT)) {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) bfr[nxt][j] = fb[j].read(S + BM * BK, kk + 1);
+          for (int j = 0; j < NI; ++j) bfr[nxt][j] = fb[j].read(S + BM * BK, kk + 1);
+        }
       }
       if (more) issue(kt + NS - 1, (kt + NS - 1) % NS, kk);
+      if (AT || BT) {
+        // LDS reads issued per MFMA group (transpose reads count two per fragment); the reads of
+        // group kk + 1, if any, are the newest ones and may stay outstanding
+        constexpr int RD = (AT ? 2 : 1) * MI + (BT ? 2 : 1) * NI;
+        if (kk + 1 < NPART) wait_frags<RD>(af[cur], bfr[cur]); else wait_frags<0>(af[cur], bfr[cur]);
+      }
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_setprio(1);
 #pragma unroll
