@@ -29,6 +29,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+COPY_GBS = 6700.0              # fastest plain copy measured on this machine (non-temporal, 16 B per thread)
 
 
 def parse():
@@ -219,8 +220,11 @@ def main():
              "share": v["total_ms"] / (dt * 1e3)}
         if v["flops"] > 0:
             e["tflops"] = v["flops"] / (v["total_ms"] * 1e-3) / 1e12
+            e["frac_of_mfma_peak"] = e["tflops"] / PEAK_BF16_TFLOPS
         if v["bytes"] > 0:
             e["gbs"] = v["bytes"] / (v["total_ms"] * 1e-3) / 1e9
+            e["frac_of_hbm_peak"] = e["gbs"] / PEAK_HBM_GBS
+            e["frac_of_copy"] = e["gbs"] / COPY_GBS        # against the fastest plain copy measured here
         kernels[k] = e
     roof = None
     if gemms and w.prec == W.PREC_BF16:

@@ -606,6 +606,61 @@ def test_identical_samples_give_zero_variance_and_smallest_batch():
         rep.close()
 
 
+@pytest.mark.parametrize("prec", [W.PREC_F32, W.PREC_BF16])
+def test_single_worker_is_plain_minibatch_sgd(prec):
+    """M = 1 (the adaptive-sampling method for one worker, Sec. 4.1): the average is the identity,
+    the cross-worker estimator is undefined, the step equals the oracle's."""
+    A = _A()
+    w = W.Workload("single", (48, 32, 6), W.ACT_GELU, True, prec, N=256, M=1, H=1, rounds=1, b0=40, b_cap=40,
+                   opt=W.OPT_SGD, lr=0.1, test=W.TEST_NORM, eta=0.5, data="teacher_mlp", seed=23)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    orc = _oracle_for(w, X, y, x0, mixed=prec == W.PREC_BF16)
+    tol = 2e-3 if prec == W.PREC_BF16 else 1e-4
+    try:
+        idx = W.step_indices(w, 0, 0, 40)
+        rep.local_step(idx, w.lr)
+        orc.local_step(idx, w.lr)
+        g, o = rep.norm_test(w.eta)[0], orc.test(W.TEST_NORM, eta=w.eta)[0]
+        assert _rel(g.sum_sq, orc.stats[0]["S1"]) <= tol and _rel(g.gbar_sq, orc.stats[0]["S2"]) <= tol
+        assert _rel(g.ratio, o["ratio"]) <= 10 * tol
+        before = rep.get_params(0)
+        rep.average_replicas()
+        assert np.array_equal(before, rep.get_params(0))
+        assert np.abs(before - orc.x[0]).max() <= (1e-3 if prec == W.PREC_BF16 else 1e-5) * np.abs(orc.x[0]).max()
+        with pytest.raises(A.AbsError, match="M >= 2"):
+            rep.cross_worker_test(0.5)
+    finally:
+        rep.close()
+
+
+def test_many_workers_ragged_sizes_beyond_one_argument_block():
+    """M = 70 workers (the per-worker sizes travel to the device in blocks of 64 kernel arguments)."""
+    A = _A()
+    M = 70
+    w = W.Workload("many", (24, 16, 4), W.ACT_RELU, True, W.PREC_F32, N=512, M=M, H=1, rounds=1, b0=20, b_cap=24,
+                   opt=W.OPT_SGD, lr=0.1, test=W.TEST_NORM, eta=0.5, data="teacher_mlp", seed=29)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    orc = _oracle_for(w, X, y, x0, mixed=False)
+    try:
+        bs = [2 + (7 * m) % 23 for m in range(M)]
+        rows = _ragged_rows(w, bs)
+        rep.local_step_ragged(rows, w.lr)
+        orc.local_step(rows, w.lr)
+        g = rep.norm_test(w.eta)
+        for m in range(M):
+            assert g[m].b == bs[m]
+            assert _rel(g[m].sum_sq, orc.stats[m]["S1"]) <= 1e-4 and _rel(g[m].gbar_sq, orc.stats[m]["S2"]) <= 1e-4
+        for m in (0, 63, 64, 69):
+            p = rep.get_params(m).astype(np.float64)
+            assert np.abs(p - orc.x[m]).max() <= 1e-5 * np.abs(orc.x[m]).max()
+    finally:
+        rep.close()
+
+
 def test_norm_test_with_finite_population_factor():
     A = _A()
     w = W.Workload("fpc", (40, 24, 5), W.ACT_RELU, True, W.PREC_F32, N=96, M=3, H=1, rounds=1, b0=24,
