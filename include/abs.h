@@ -199,7 +199,8 @@ abs_status abs_get_params(abs_ctx *ctx, int m, float *out_host);
 abs_status abs_set_params(abs_ctx *ctx, int m, const float *in_host);
 abs_status abs_get_grad(abs_ctx *ctx, int m, float *out_host);    /* last local batch gradient */
 /* Per-sample ||g_i||^2 (and <g_i,gbar> if gathered; else q_host may be NULL) of worker m
- * for the most recent step: host, b floats each. */
+ * for the most recent step: host, b floats each (b^m after a ragged step; see
+ * abs_local_step_accumulated for what an accumulated step keeps). */
 abs_status abs_get_per_sample(abs_ctx *ctx, int m, float *n_host, float *q_host);
 
 /* Linear scaling of the learning rate with the batch size (Sec. 6.1): lr_ref * b / b_ref. */
@@ -241,7 +242,8 @@ abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *hip_stream
  * context's stream.  abs_profile_read synchronises, folds the elapsed times into per-kernel
  * totals (accumulated since abs_profile_enable) and returns one entry per kernel class that ran:
  * calls, total milliseconds, and the algorithmic work of those calls (flops for the matrix-core
- * GEMMs: 2 m n k per replica; bytes for the bandwidth-bound kernels).   out : host.
+ * GEMMs: 2 m n k per replica, with the largest b^m for every replica after a ragged step; bytes
+ * for the bandwidth-bound kernels).   out : host.
  */
 typedef struct {
   char name[32];
