@@ -36,7 +36,7 @@ struct Plan {
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
   size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
-  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0;
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0;
   size_t total = 0;
 };
 
@@ -137,6 +137,7 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
   pl.o_stats = take((size_t)pl.M * 8 * 8);
   pl.o_rows = take((size_t)pl.M * sizeof(int));
+  pl.o_sqwave = take((size_t)pl.M * (pl.Ppad / 256) * sizeof(float));
   pl.o_cw = take((2 * STATS_PBLK + 8) * 8);
   pl.total = off;
 }
@@ -589,10 +590,17 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   sp.sNg = cap;
   sp.loss = c->at<float>(pl.o_loss);
   if (ph.ps_off >= 0) { sp.n_out = c->at<float>(pl.o_nout) + ph.ps_off; sp.q_out = c->at<float>(pl.o_qout) + ph.ps_off; }
-  sp.grad = ph.s2 ? grad : nullptr; sp.Ppad = pl.Ppad;
+  sp.Ppad = pl.Ppad;
   sp.partials = c->at<double>(pl.o_partials); sp.stats = c->at<double>(pl.o_stats);
-  { ProfScope ps_(c, T_STATS, 0.0, 4.0 * M * pl.Ppad);
-  HIPCHK(c, launch_stats(sp, s)); }
+  // When this call both finishes the gradient and updates, the update kernel gathers ||gbar||^2 on
+  // its way through the gradient (none of the statistics depends on the parameters, so the update
+  // may run first); otherwise a separate pass over the gradient does.
+  const bool s2_in_update = ph.s2 && ph.update;
+  sp.grad = (ph.s2 && !s2_in_update) ? grad : nullptr;
+  if (!s2_in_update) {
+    ProfScope ps_(c, T_STATS, 0.0, ph.s2 ? 4.0 * M * pl.Ppad : 0.0);
+    HIPCHK(c, launch_stats(sp, s));
+  }
   if (!ph.update) return ABS_OK;
   // optimizer update (Alg. 1: "local SGD step ... or other inner optimizers")
   c->t += 1;
@@ -609,8 +617,14 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     up.c1 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta1, (double)c->t)));
     up.c2 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta2, (double)c->t)));
   }
+  if (s2_in_update) up.sq_wave = c->at<float>(pl.o_sqwave);
   { ProfScope ps_(c, T_UPDATE, 0.0, 1.0 * M * pl.P * (c->cfg.opt == ABS_OPT_SGD ? 12 : c->cfg.opt == ABS_OPT_ADAMW ? 28 : 20) + (pl.bf16 ? 2.0 * M * pl.P : 0.0));
   HIPCHK(c, launch_update(up, s)); }
+  if (s2_in_update) {
+    sp.sq_wave = up.sq_wave; sp.n_sq_wave = pl.Ppad / 256;
+    ProfScope ps_(c, T_STATS, 0.0, 4.0 * M * (pl.Ppad / 256));
+    HIPCHK(c, launch_stats(sp, s));
+  }
   c->last_b = ph.b_total > 0 ? ph.b_total : b;
   c->last_bm.assign(M, c->last_b);
   if (b_host) c->last_bm.assign(b_host, b_host + M);

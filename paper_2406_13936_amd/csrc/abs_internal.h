@@ -110,6 +110,8 @@ struct StatsP {
   long long Ppad;
   double *partials;         // scratch: [groups][5][PBLK]
   double *stats;            // out: [groups][8] = S1, S2, S3, S4, loss, 0,0,0
+  const float *sq_wave;     // alternative source of S2 (grad must be null): per-wavefront sums of g^2 left by the
+  long long n_sq_wave;      //   update kernel, n_sq_wave per group (one per 256 consecutive parameters)
   const int *rows;          // optional per-group sample counts (device) replacing b
   // which sums this launch produces: S1 and the loss (do_n), S3 and S4 (do_q; needs want_ip),
   // S2 (grad != null); acc_n / acc_q add to the stored sums instead of replacing them
@@ -121,6 +123,7 @@ hipError_t launch_stats(const StatsP &p, hipStream_t s);
 struct UpdateP {
   float *x; const float *g; float *v; float *m; bf16_t *shadow;
   long long n;              // total elements (groups * Ppad)
+  float *sq_wave;           // optional: sq_wave[i / 256] = sum of g^2 over parameters [256 i', 256 i' + 256)
   int opt; float lr, momentum, beta1, beta2, eps, wd, c1, c2;  // c = 1/(1-beta^t)
 };
 hipError_t launch_update(const UpdateP &p, hipStream_t s);

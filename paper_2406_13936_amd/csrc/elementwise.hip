@@ -294,6 +294,18 @@ __global__ void __launch_bounds__(256) stats_gradsq_kernel(const float *__restri
   if (threadIdx.x == 0) partials[((long long)g * 5 + 1) * STATS_PBLK + blockIdx.x] = r;
 }
 
+// Stage 1b': the same sum from the per-wavefront partials left by the update kernel.
+__global__ void __launch_bounds__(256) stats_gradsq_parts_kernel(const float *__restrict__ sq_wave, long long per_group,
+                                                                 double *__restrict__ partials) {
+  __shared__ double red[4];
+  const int g = blockIdx.y;
+  const float *p = sq_wave + (long long)g * per_group;
+  double s = 0.0;
+  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < per_group; i += 256LL * STATS_PBLK) s += (double)p[i];
+  const double r = block_sum<4>(s, red);
+  if (threadIdx.x == 0) partials[((long long)g * 5 + 1) * STATS_PBLK + blockIdx.x] = r;
+}
+
 // Stage 2 (grid: groups): add the PBLK partials of each of the five sums in index order.
 // sel / acc: bit k set = sum k is produced by this launch / is added to the stored value.
 __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restrict__ partials,
@@ -310,13 +322,20 @@ __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restri
 }
 
 // ---- optimizer update ------------------------------------------------------------------------
-template <int OPT, bool SHADOW>
+// With SQ the kernel also leaves, per wavefront (256 consecutive parameters), the sum of the squared
+// gradient entries it read: ||gbar||^2 then costs no second pass over the gradient.  (SQ launches use
+// a grid that covers the data in one pass, and n is a multiple of 256, so wavefronts are whole.)
+template <int OPT, bool SHADOW, bool SQ>
 __global__ void __launch_bounds__(256) update_kernel(const UpdateP p) {
   const long long n4 = p.n / 4;
   const long long stride = (long long)gridDim.x * 256;
   for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n4; i += stride) {
     float4 x = ld_stream(reinterpret_cast<const float4 *>(p.x) + i);
     const float4 g = ld_stream(reinterpret_cast<const float4 *>(p.g) + i);
+    if (SQ) {
+      const float t = wave_sum(fmaf(g.x, g.x, fmaf(g.y, g.y, fmaf(g.z, g.z, g.w * g.w))));
+      if ((threadIdx.x & 63) == 0) p.sq_wave[i >> 6] = t;
+    }
     float xs[4] = {x.x, x.y, x.z, x.w};
     const float gs[4] = {g.x, g.y, g.z, g.w};
     if (OPT == OPT_SGD) {
@@ -552,11 +571,15 @@ hipError_t launch_stats(const StatsP &p, hipStream_t s) {
   int sel = 0, acc = 0;
   if (p.do_n) { sel |= 1 | 16; if (p.acc_n) acc |= 1 | 16; }
   if (p.do_q) { sel |= 4 | 8; if (p.acc_q) acc |= 4 | 8; }
-  if (p.grad) sel |= 2;
+  if (p.grad && p.sq_wave) return hipErrorInvalidValue;
+  if (p.grad || p.sq_wave) sel |= 2;
   if (!sel) return hipSuccess;
   if (p.do_n || p.do_q) hipLaunchKernelGGL(stats_samples_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p);
   if (p.grad)
     hipLaunchKernelGGL(stats_gradsq_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.grad, p.Ppad,
+                       p.partials);
+  if (p.sq_wave)
+    hipLaunchKernelGGL(stats_gradsq_parts_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.sq_wave, p.n_sq_wave,
                        p.partials);
   hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats, sel, acc);
   return hipGetLastError();
@@ -565,11 +588,14 @@ hipError_t launch_stats(const StatsP &p, hipStream_t s) {
 hipError_t launch_update(const UpdateP &p, hipStream_t s) {
   // one 16-byte vector per thread and a grid as large as the data: measured fastest on MI355X
   const dim3 grid(grid_for(p.n / 4, 256, 1 << 30)), blk(256);
-  const bool sh = p.shadow != nullptr;
+  const bool sh = p.shadow != nullptr, sq = p.sq_wave != nullptr;
+  if (sq && (p.n & 255)) return hipErrorInvalidValue;
 #define ABS_UPD(O)                                                                  \
   do {                                                                              \
-    if (sh) hipLaunchKernelGGL((update_kernel<O, true>), grid, blk, 0, s, p);       \
-    else hipLaunchKernelGGL((update_kernel<O, false>), grid, blk, 0, s, p);         \
+    if (sh && sq) hipLaunchKernelGGL((update_kernel<O, true, true>), grid, blk, 0, s, p);        \
+    else if (sh) hipLaunchKernelGGL((update_kernel<O, true, false>), grid, blk, 0, s, p);        \
+    else if (sq) hipLaunchKernelGGL((update_kernel<O, false, true>), grid, blk, 0, s, p);        \
+    else hipLaunchKernelGGL((update_kernel<O, false, false>), grid, blk, 0, s, p);               \
   } while (0)
   if (p.opt == OPT_SGD) ABS_UPD(OPT_SGD);
   else if (p.opt == OPT_SHB) ABS_UPD(OPT_SHB);
