@@ -790,3 +790,55 @@ def test_statistics_alone_on_wide_layers_large_tiles():
     got = p.float().cpu().numpy()
     for m in (0, 17, 31):
         assert (got[m] != want).mean() < 2e-3 and np.abs(got[m] - want).max() <= 2 ** -7 * np.abs(want).max()
+
+
+def test_statistics_stress_full_size_sampled_replicas():
+    """The statistics-only workload at its full size (32 replicas x 4 stacked 4096x4096 layers, b = 8192):
+    two replicas, drawn from the seeded host generator, are recomputed by the oracle's definitions in fp64;
+    the 32-way bf16 average of 4 x 4096^2 parameters per replica is checked on sampled ranges."""
+    import torch
+    A = _A()
+    M, L, b, d = 32, 4, 8192, 4096
+    sampled = (3, 17)
+    dev = torch.device("cuda")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(31)
+    a_list = [torch.randn((M, b, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(L)]
+    d_list = [torch.randn((M, b, d), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(L)]
+    for m in sampled:
+        for l in range(L):
+            av, dv = W.stats_stress_layer(0, m, l, b, d, d)
+            a_list[l][m].copy_(torch.from_numpy(av).to(dev))
+            d_list[l][m].copy_(torch.from_numpy(dv).to(dev))
+    res, n, q, _ = A.layer_stats(a_list, d_list, want_per_sample=True)
+    n, q = n.cpu().numpy(), q.cpu().numpy()
+    for m in range(M):
+        assert res[m].b == b and res[m].sum_sq >= b * res[m].gbar_sq                  # Jensen
+        assert _rel(res[m].sum_q, b * res[m].gbar_sq) <= 2e-2                          # sum_i <g_i, gbar> = b ||gbar||^2
+    for m in sampled:
+        n_o, q_o, S2 = np.zeros(b), np.zeros(b), 0.0
+        for l in range(L):
+            av = a_list[l][m].float().cpu().numpy().astype(np.float64)
+            dv = d_list[l][m].float().cpu().numpy().astype(np.float64)
+            G = dv.T @ av / b
+            n_o += (dv ** 2).sum(1) * (av ** 2).sum(1)
+            q_o += (dv * (av @ O.bf16_round(G).T)).sum(1)
+            S2 += float((G ** 2).sum())
+        np.testing.assert_allclose(n[m], n_o, rtol=1e-4)
+        np.testing.assert_allclose(q[m], q_o, rtol=2e-3, atol=2e-4 * np.abs(q_o).max())
+        assert _rel(res[m].sum_sq, n_o.sum()) <= 1e-4
+        assert _rel(res[m].gbar_sq, S2) <= 1e-4
+        assert _rel(res[m].sum_q, q_o.sum()) <= 1e-3
+        assert _rel(res[m].sum_q2, (q_o ** 2).sum()) <= 1e-3
+    del a_list, d_list
+    P = L * d * d
+    params = (torch.randn((M, P), generator=gen, device=dev, dtype=torch.float32) / 64).to(torch.bfloat16)
+    ranges = [(0, 1 << 20), (P // 2 + 12345 // 8 * 8, P // 2 + 12345 // 8 * 8 + (1 << 20)), (P - (1 << 20), P)]
+    before = [params[:, s0:s1].float().cpu().numpy().astype(np.float64) for s0, s1 in ranges]
+    A.average_bf16(params)
+    torch.cuda.synchronize()
+    for (s0, s1), ref in zip(ranges, before):
+        want = O.bf16_round(ref.sum(axis=0) / M)
+        for m in (0, 13, 31):
+            got = params[m, s0:s1].float().cpu().numpy()
+            assert (got != want).mean() < 2e-3 and np.abs(got - want).max() <= 2 ** -7 * np.abs(want).max()
