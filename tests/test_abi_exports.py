@@ -84,3 +84,17 @@ def test_linear_lr_scaling_on_the_host():
     assert B.lr_linear_scaling(0.05, 2048, 256) == pytest.approx(0.4)
     with pytest.raises(B.AbsError):
         B.lr_linear_scaling(0.05, 0, 256)
+
+
+def test_null_context_is_rejected_by_every_stepping_entry_point():
+    from paper_2406_13936_amd import binding as B
+    lib = B.load_library()
+    lib.abs_local_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_float]
+    assert lib.abs_local_step(None, None, 4, C.c_float(0.1)) == 1                     # ABS_EINVAL
+    assert lib.abs_local_step_ragged(None, None, 4, None, C.c_float(0.1)) == 1
+    assert lib.abs_local_step_accumulated(None, None, 8, 4, C.c_float(0.1)) == 1
+    assert lib.abs_norm_test(None, 0.5, None) == 1
+    assert lib.abs_norm_test_per_worker(None, None, None) == 1
+    assert lib.abs_norm_test_fpc(None, 0.5, 10, None) == 1
+    assert lib.abs_average_replicas(None) == 1
+    assert b"NULL" in lib.abs_last_error(None)
