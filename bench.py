@@ -128,24 +128,9 @@ def stats_stress(a, np, torch, A, W):
     }
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py: this build measures one GPU; all M worker replicas are batched on it and the "
-              "replica average is an in-device mean (no collective). Run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-    import paper_2406_13936_amd as A
-    from paper_2406_13936_amd import workloads as W
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(3)
-    if a.workload == "config5":
-        print(json.dumps(stats_stress(a, np, torch, A, W)))
-        return
-    w = getattr(W, a.workload)()
+def measure(a, wname, np, torch, A, W, with_cpu):
+    """Time a.steps steps of workload `wname` (inputs resident in HBM) and return the result line as a dict."""
+    w = getattr(W, wname)()
     X, y = W.make_dataset(w)
     x0 = W.make_x0(w)
     rep = A.Replicas.from_workload(w, X, y, x0)
@@ -185,7 +170,7 @@ def main():
             rep.average_replicas()
         return nb
 
-    if a.pmc_probe:
+    if a.pmc_probe and with_cpu is not None:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         src.zero_()
@@ -237,7 +222,7 @@ def main():
                 "flops_per_launch": v["flops"] / v["calls"]}
         # HBM bytes per launch from the committed rocprofv3 --pmc summary of this same command
         # (FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel); null when no summary covers it
-        tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.json" % a.workload)
+        tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.json" % wname)
         if os.path.exists(tpath) and not a.adaptive and not a.batch:
             try:
                 tj = json.load(open(tpath))
@@ -264,9 +249,37 @@ def main():
                    "test": ["norm", "inner_product", "augmented_inner_product"][w.test]},
         "roofline": roof, "kernels": kernels,
     }
-    if not a.no_cpu_baseline:
-        sb = a.cpu_sample_batch or {"config1": 512, "config2": 512, "config3": 256, "config4": 128}[a.workload]
+    if with_cpu:
+        sb = a.cpu_sample_batch or {"config1": 512, "config2": 4096, "config3": 1024, "config4": 512}[wname]
         out["cpu_baseline"] = cpu_baseline(w, X, y, x0, min(sb, w.b_cap))
+    return out
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU; all M worker replicas are batched on it and the "
+              "replica average is an in-device mean (no collective). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2406_13936_amd as A
+    from paper_2406_13936_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(3)
+    if a.workload == "config5":
+        print(json.dumps(stats_stress(a, np, torch, A, W)))
+        return
+    out = measure(a, a.workload, np, torch, A, W, not a.no_cpu_baseline)
+    if a.workload == "config3" and not a.adaptive and not a.batch:
+        # the medium configuration (MLP 784-512-512-10, M = 8) at its cap, same contract, for reference
+        o2 = measure(a, "config2", np, torch, A, W, False)
+        out["also"] = {o2["config"]["workload"]: {
+            "value": o2["value"], "unit": o2["unit"], "ms_per_step": o2["ms_per_step"],
+            "local_batch": o2["config"]["local_batch"], "M": o2["config"]["M"],
+            "all_gemms_tflops": (o2.get("roofline") or {}).get("all_gemms_tflops")}}
     print(json.dumps(out))
 
 
