@@ -31,6 +31,7 @@ struct Plan {
   long long P = 0, Ppad = 0;
   int M = 0, cap = 0;
   int qparts[MAXL] = {0};
+  size_t colpart_per = 0;              // floats of column-partial scratch per replica
   int rparts[MAXL + 1] = {0};          // partial vectors kept for the row norms of width dims[l]
   // byte offsets into the workspace
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
@@ -128,10 +129,12 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
     for (int l = 1; l <= pl.L; ++l) mx = pl.dims[l] > mx ? pl.dims[l] : mx;
     size_t per = (size_t)((pl.cap + COLSUM_ROWS - 1) / COLSUM_ROWS) * mx;      // standalone column sums
     for (int l = 1; l < pl.L; ++l) {                                           // backward-epilogue partials
-      const size_t rows = pl.dims[l] > 64 ? (size_t)std::max((pl.cap + 255) / 256 * 2, 16)
-                                          : (size_t)((pl.cap + 127) / 128 * 4);
+      // rows of partials per replica: at most ceil(b / 128) * 4 for any tile shape the GEMM may pick
+      // (128-row tiles of 4 wave rows; the other shapes write fewer)
+      const size_t rows = (size_t)((pl.cap + 127) / 128 * 4);
       per = std::max(per, rows * pl.dims[l]);
     }
+    pl.colpart_per = per;
     pl.o_colpart = take((size_t)pl.M * per * 4);
   }
   pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
@@ -235,7 +238,7 @@ struct ProfScope {
 };
 
 hipError_t gemm(abs_ctx *c, const GemmP &p, int epi, int layer) {
-  const int shape = c->pl.bf16 ? gemm_bf16_tile_shape(p.Md, p.Nd) : 1;
+  const int shape = c->pl.bf16 ? gemm_bf16_tile_shape(p.Md, p.Nd, p.groups) : 1;
   ProfScope ps(c, T_GEMM0 + (epi * 3 + shape) * T_LAYERS + layer, 2.0 * p.Md * p.Nd * p.Kd * p.groups, 0.0);
   return c->pl.bf16 ? launch_gemm_bf16(p, epi, c->stream) : launch_gemm_f32(p, epi, c->stream);
 }
@@ -474,7 +477,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       if (pl.gelu) { p.C2 = act_ptr(pl.o_Dact[l]); p.sC2g = cap * pl.ld[l]; p.ldc2 = pl.ld[l]; }
       if (pl.bf16) {
         // ||a_i^l||^2 as per-tile partials out of the GEMM epilogue (summed by the statistics kernel)
-        an_parts[l] = gemm_bf16_row_parts(b, pl.dims[l]);
+        an_parts[l] = gemm_bf16_row_parts(b, pl.dims[l], M);
         if (want_parts) { p.part = c->at<float>(pl.o_an[l]); p.sPartg = cap * pl.rparts[l]; p.sPartTile = cap; }
         HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
       } else {
@@ -506,18 +509,19 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     p.sEg = cap * pl.ld[l - 1]; p.lde = pl.ld[l - 1];
     if (pl.bf16) {
       // ||delta_i^{l-1}||^2 and (with biases) the column sums of delta^{l-1} as epilogue partials
-      dn_parts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l - 1]);
+      dn_parts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l - 1], M);
       if (want_parts) { p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap; }
       if (hb && ph.wgrad) {
         p.cpart = c->at<float>(pl.o_colpart);
-        p.sCpartg = (long long)gemm_bf16_col_parts(b, pl.dims[l - 1]) * pl.dims[l - 1];
+        p.sCpartg = (long long)gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1];
+        if ((size_t)p.sCpartg > pl.colpart_per) return cfail(c, ABS_ENOMEM, "column-partial scratch too small for this tile shape");
       }
       HIPCHK(c, gemm(c, p, EPI_BWD, l));
       if (hb && ph.wgrad) {
-        ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1]) * pl.dims[l - 1]);
+        ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1]);
         int tile_m = 0, ppt = 0;
-        gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1]), &tile_m, &ppt);
-        HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1]), M,
+        gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1], M), &tile_m, &ppt);
+        HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1], M), M,
                                         inv_b, grad + pl.offB[l - 1], pl.Ppad, rows, tile_m, ppt, ph.acc_grad ? 1 : 0, s));
       }
     } else {
@@ -564,7 +568,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         p.part = c->at<float>(pl.o_qpart[l - 1]);
         p.sPartg = cap * pl.qparts[l - 1]; p.sPartTile = cap;
         HIPCHK(c, gemm(c, p, EPI_IPDOT, l));
-        sp.qpart[l - 1] = p.part; sp.nparts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l]);
+        sp.qpart[l - 1] = p.part; sp.nparts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l], M);
         sp.sQg[l - 1] = p.sPartg; sp.sQpart[l - 1] = cap;
       } else {
         p.B = grad + pl.offW[l];
@@ -964,7 +968,7 @@ abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M
     p.E = delta_dev[l]; p.sEg = sd; p.lde = out_dims[l];
     p.part = reinterpret_cast<float *>(ws + off[9 + l]); p.sPartg = (long long)b * np; p.sPartTile = b;
     HIPCHK(nc, launch_gemm_bf16(p, EPI_IPDOT, s));
-    sp.qpart[l] = p.part; sp.nparts[l] = gemm_bf16_row_parts(b, out_dims[l]); sp.sQg[l] = p.sPartg; sp.sQpart[l] = b;
+    sp.qpart[l] = p.part; sp.nparts[l] = gemm_bf16_row_parts(b, out_dims[l], M); sp.sQg[l] = p.sPartg; sp.sQpart[l] = b;
     sp.an[l] = an + (size_t)l * M * b; sp.dn[l] = dn + (size_t)l * M * b;
     sp.an_parts[l] = sp.dn_parts[l] = 1; sp.an_sg[l] = sp.dn_sg[l] = b;
   }

@@ -52,10 +52,10 @@ hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s);
 int gemm_bf16_ipdot_parts(int Nd);
 // Exact number of row partials (tiles along n) and of column-partial rows (tiles along m times
 // wave rows) that the bf16 family writes for an Md x Nd output.
-int gemm_bf16_row_parts(int Md, int Nd);
-int gemm_bf16_col_parts(int Md, int Nd);
-// Tile shape the bf16 family uses for an Md x Nd output: 0 = 128x64, 1 = 128x128, 2 = 256x256.
-int gemm_bf16_tile_shape(int Md, int Nd);
+int gemm_bf16_row_parts(int Md, int Nd, int groups);
+int gemm_bf16_col_parts(int Md, int Nd, int groups);
+// Tile shape the bf16 family uses for an Md x Nd output over `groups` replicas: 0 = 128x64, 1 = 128x128, 2 = 256x256.
+int gemm_bf16_tile_shape(int Md, int Nd, int groups);
 // fp32 SIMT family (gemm_f32.hip); EPI_IPDOT is not offered (U is materialised instead).
 hipError_t launch_gemm_f32(const GemmP &p, int epi, hipStream_t s);
 

@@ -630,10 +630,14 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
 // otherwise a 128x128 (or 128x64 for narrow outputs) tile.
 template <bool AT, bool BT, int EPI, int ACT>
 hipError_t launch_shape(const GemmP &p, hipStream_t s) {
-  switch (gemm_bf16_tile_shape(p.Md, p.Nd)) {
+  switch (gemm_bf16_tile_shape(p.Md, p.Nd, p.groups)) {
     case 0: return launch_cfg<128, 64, 64, 4, 1, 3, AT, BT, EPI, ACT>(p, s);
     case 2: return launch_cfg<256, 256, 64, 2, 4, 2, AT, BT, EPI, ACT>(p, s);
-    default: return launch_cfg<128, 128, 64, 2, 2, 3, AT, BT, EPI, ACT>(p, s);
+    default:
+      // short reductions: two stages (64 KB) so that two work-groups share a CU; long ones (few tiles,
+      // one work-group per CU anyway): three stages
+      if (p.Kd <= 1024) return launch_cfg<128, 128, 64, 2, 2, 2, AT, BT, EPI, ACT>(p, s);
+      return launch_cfg<128, 128, 64, 2, 2, 3, AT, BT, EPI, ACT>(p, s);
   }
 }
 
@@ -651,20 +655,26 @@ hipError_t launch_act(const GemmP &p, hipStream_t s) {
 
 }  // namespace
 
-int gemm_bf16_tile_shape(int Md, int Nd) {
+int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
   if (Nd <= 64) return 0;
   if (Md >= 1024 && Nd >= 1024) return 2;
+  // mid-sized outputs: the large tile only if it still gives every CU a work-group
+  if (Md >= 512 && Nd >= 512) {
+    const long long tiles = (long long)((Md + 255) / 256) * ((Nd + 255) / 256) * groups;
+    if (tiles >= 256) return 2;
+  }
   return 1;
 }
 
-int gemm_bf16_row_parts(int Md, int Nd) {
+int gemm_bf16_row_parts(int Md, int Nd, int groups) {
   const int bn[3] = {64, 128, 256};
-  return (Nd + bn[gemm_bf16_tile_shape(Md, Nd)] - 1) / bn[gemm_bf16_tile_shape(Md, Nd)];
+  const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
+  return (Nd + bn[sh] - 1) / bn[sh];
 }
 
-int gemm_bf16_col_parts(int Md, int Nd) {
+int gemm_bf16_col_parts(int Md, int Nd, int groups) {
   const int bm[3] = {128, 128, 256}, wm[3] = {4, 2, 2};
-  const int sh = gemm_bf16_tile_shape(Md, Nd);
+  const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
   return (Md + bm[sh] - 1) / bm[sh] * wm[sh];
 }
 
