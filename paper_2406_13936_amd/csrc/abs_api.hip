@@ -37,7 +37,8 @@ struct Plan {
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
   size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
-  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0;
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_kpart = 0;
+  size_t kpart_floats = 0;             // scratch for the partial products of a split weight-gradient reduction
   size_t total = 0;
 };
 
@@ -141,6 +142,14 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   pl.o_stats = take((size_t)pl.M * 8 * 8);
   pl.o_rows = take((size_t)pl.M * sizeof(int));
   pl.o_sqwave = take((size_t)pl.M * (pl.Ppad / 256) * sizeof(float));
+  if (pl.bf16) {
+    // a split is only taken when the un-split launch has fewer than 192 tiles, and never makes more than
+    // 512 (tile, slice) pairs of at most 128 x 128 or 256 x 256 outputs each
+    size_t mx = 0;
+    for (int l = 1; l <= pl.L; ++l) mx = std::max(mx, (size_t)pl.dims[l] * pl.dims[l - 1]);
+    pl.kpart_floats = std::min((size_t)8 * pl.M * mx, (size_t)512 * 65536);
+    pl.o_kpart = take(pl.kpart_floats * sizeof(float));
+  }
   pl.o_cw = take((2 * STATS_PBLK + 8) * 8);
   pl.total = off;
 }
@@ -543,7 +552,27 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
     p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
     if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
+    if (pl.bf16 && p.ldc == p.Nd && (p.Nd & 3) == 0) {
+      // few output tiles and a long reduction (small layers, or any layer while b is the long side): cut
+      // the reduction into slices so that the launch fills the chip, and add the slices in order afterwards
+      const int sh = gemm_bf16_tile_shape(p.Md, p.Nd, M);
+      const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
+      const long long tiles = (long long)((p.Md + te - 1) / te) * ((p.Nd + tn_e - 1) / tn_e) * M;
+      const int KT = (b + 63) / 64;
+      long long S = std::min<long long>(std::min<long long>(8, 512 / std::max<long long>(tiles, 1)), KT / 4);
+      while (S > 1 && (size_t)S * M * p.Md * p.Nd > pl.kpart_floats) --S;
+      if (tiles < 192 && S > 1) {
+        p.ksplit = (int)S;
+        p.kchunk = (int)(((KT + S - 1) / S) * 64);
+        p.kpart = c->at<float>(pl.o_kpart);
+      }
+    }
     HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
+    if (p.ksplit > 1) {
+      ProfScope ps_(c, T_COLSUM, 0.0, (4.0 * p.ksplit + 6.0) * M * p.Md * p.Nd);
+      HIPCHK(c, launch_splitk_finish(p.kpart, p.ksplit, M, (long long)p.Md * p.Nd, inv_b, rows, static_cast<float *>(p.C),
+                                     p.sCg, static_cast<bf16_t *>(p.C2), p.sC2g, p.accumulate, s));
+    }
     if (hb && (!pl.bf16 || l == L)) {   // bf16 mode: layers below L got theirs from the backward epilogue
       ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
       HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad,

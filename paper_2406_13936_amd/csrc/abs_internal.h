@@ -44,6 +44,11 @@ struct GemmP {
   const int *rows;
   int rows_is_k;
   int accumulate;              // EPI_WGRAD: C = alpha * acc + C  (micro-batch accumulation)
+  // Split reduction (EPI_WGRAD of the bf16 family, optional): ksplit > 1 cuts k into ksplit slices of
+  // kchunk elements; slice sp of group g writes its raw partial product to
+  // kpart[(g * ksplit + sp) * Md * Nd] (row-major, ld = Nd) and C / C2 are left to launch_splitk_finish.
+  int ksplit, kchunk;
+  float *kpart;
 };
 
 // bf16 MFMA family (gemm_bf16.hip).  Returns the number of column partials that
@@ -133,6 +138,10 @@ hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s
 hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials,
                                double *out, hipStream_t s);
 hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);
+// C[g][e] = alpha * sum_sp kpart[(g * ksplit + sp) * mn + e]  (+ C[g][e] if accumulate), slices added in order;
+// C2 (bf16, may be null) gets the rounded result; rows (may be null): alpha = 1 / rows[g].  mn multiple of 4.
+hipError_t launch_splitk_finish(const float *kpart, int ksplit, int groups, long long mn, float alpha, const int *rows,
+                                float *C, long long sCg, bf16_t *C2, long long sC2g, int accumulate, hipStream_t s);
 // dst[0..n) = v[0..n): the values travel as kernel arguments, so the host array may be reused at once
 enum { SET_INTS_MAX = 64 };
 hipError_t launch_set_ints(const int *v_host, int n, int *dst, hipStream_t s);

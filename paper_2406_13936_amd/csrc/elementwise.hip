@@ -469,6 +469,31 @@ __global__ void __launch_bounds__(256) copy_probe_kernel(const uint4 *__restrict
   if (i < n16) dst[i] = src[i];
 }
 
+__global__ void __launch_bounds__(256) splitk_finish_kernel(const float *__restrict__ kpart, int ksplit, long long mn,
+                                                            float alpha, const int *__restrict__ rows,
+                                                            float *__restrict__ C, long long sCg, bf16_t *__restrict__ C2,
+                                                            long long sC2g, int accumulate) {
+  const int g = blockIdx.y;
+  const long long i = blockIdx.x * 256LL + threadIdx.x;          // float4 index inside the group
+  if (i * 4 >= mn) return;
+  if (rows) alpha = 1.0f / (float)rows[g];
+  const float *p = kpart + (long long)g * ksplit * mn + i * 4;
+  float4 s = ld_stream(reinterpret_cast<const float4 *>(p));
+  for (int sp = 1; sp < ksplit; ++sp) {
+    const float4 v = ld_stream(reinterpret_cast<const float4 *>(p + (long long)sp * mn));
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
+  float4 *c = reinterpret_cast<float4 *>(C + (long long)g * sCg) + i;
+  if (accumulate) { const float4 o = *c; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+  *c = s;
+  if (C2) {
+    uint2 o;
+    o.x = pack2bf(s.x, s.y); o.y = pack2bf(s.z, s.w);
+    reinterpret_cast<uint2 *>(C2 + (long long)g * sC2g)[i] = o;
+  }
+}
+
 struct IntsArg { int v[SET_INTS_MAX]; };
 __global__ void set_ints_kernel(const IntsArg a, int n, int *__restrict__ dst) {
   if ((int)threadIdx.x < n) dst[threadIdx.x] = a.v[threadIdx.x];
@@ -629,6 +654,14 @@ hipError_t launch_copy_probe(const void *src, void *dst, long long bytes, hipStr
   if (n16 <= 0) return hipSuccess;
   hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
                      static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_finish(const float *kpart, int ksplit, int groups, long long mn, float alpha, const int *rows,
+                                float *C, long long sCg, bf16_t *C2, long long sC2g, int accumulate, hipStream_t s) {
+  if (mn & 3) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((mn / 4 + 255) / 256), groups), dim3(256), 0, s, kpart, ksplit,
+                     mn, alpha, rows, C, sCg, C2, sC2g, accumulate);
   return hipGetLastError();
 }
 

@@ -192,8 +192,10 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   const int lb = (bid & 7) * chunk + (bid >> 3);
   if (lb >= nblk) return;
   const int per_g = tilesM * tilesN;
-  const int g = lb / per_g;
-  const int t = lb - g * per_g;
+  const int vg = lb / per_g;                      // group, or (group, k-slice) pair of a split reduction
+  const int t = lb - vg * per_g;
+  const int ksplit = (EPI == EPI_WGRAD && pin.ksplit > 1) ? pin.ksplit : 1;
+  const int g = vg / ksplit, ksl = vg - g * ksplit;
   const int tm = t / tilesN, tn = t - tm * tilesN;
   const int m0 = tm * BM, n0 = tn * BN;
   GemmP p = pin;
@@ -202,13 +204,22 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
     if (p.rows_is_k) { p.Kd = r; p.alpha = 1.0f / (float)r; } else p.Md = r;
     if (m0 >= p.Md) return;                       // uniform over the block, before any barrier
   }
+  long long kofsA = 0, kofsB = 0;                 // element offsets of this block's k-slice
+  if (EPI == EPI_WGRAD && ksplit > 1) {
+    const int k0 = ksl * p.kchunk;
+    int kd = p.Kd - k0;
+    kd = kd < 0 ? 0 : (kd > p.kchunk ? p.kchunk : kd);
+    p.Kd = kd;                                    // an empty slice runs no k-tile and writes zeros
+    kofsA = AT ? (long long)k0 * p.lda : k0;
+    kofsB = BT ? (long long)k0 * p.ldb : k0;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
-  const bf16_t *A = static_cast<const bf16_t *>(p.A) + (long long)g * p.sAg;
-  const bf16_t *B = static_cast<const bf16_t *>(p.B) + (long long)g * p.sBg;
+  const bf16_t *A = static_cast<const bf16_t *>(p.A) + (long long)g * p.sAg + kofsA;
+  const bf16_t *B = static_cast<const bf16_t *>(p.B) + (long long)g * p.sBg + kofsB;
   // range = the operand's extent in memory: rows*ld (k-contiguous) or K*ld (row-contiguous)
   const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<bf16_t *>(A), 0, (int)((long long)(AT ? p.Kd : p.Md) * p.lda * 2), 0x00020000);
@@ -549,8 +560,13 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   float *stf = reinterpret_cast<float *>(smem) + wave * (32 * FLD);
   float *Cg = static_cast<float *>(p.C) + (long long)g * p.sCg;
   bf16_t *C2g = (EPI == EPI_WGRAD && p.C2) ? static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g : nullptr;
+  bool accumulate = EPI == EPI_WGRAD && p.accumulate;        // micro-batch accumulation: C += alpha * acc
+  if (EPI == EPI_WGRAD && ksplit > 1) {                      // raw partial product of this k-slice
+    Cg = p.kpart + (long long)vg * p.Md * p.Nd;
+    p.ldc = p.Nd; p.alpha = 1.0f;
+    C2g = nullptr; accumulate = false;
+  }
   const bool vec_ok = (p.ldc & 3) == 0 && (!C2g || (p.ldc2 & 3) == 0);
-  const bool accumulate = EPI == EPI_WGRAD && p.accumulate;  // micro-batch accumulation: C += alpha * acc
   __syncthreads();                                          // stages are dead
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
@@ -618,7 +634,7 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
     attr_set = true;
   }
   const int tilesM = (p.Md + BM - 1) / BM, tilesN = (p.Nd + BN - 1) / BN;
-  const long long nblk = (long long)tilesM * tilesN * p.groups;
+  const long long nblk = (long long)tilesM * tilesN * p.groups * ((EPI == EPI_WGRAD && p.ksplit > 1) ? p.ksplit : 1);
   if (nblk <= 0) return hipSuccess;
   if (nblk > 0x3fffffff) return hipErrorInvalidValue;
   const int chunk = (int)((nblk + 7) / 8);
@@ -702,6 +718,9 @@ hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s) {
   const long long abytes = (long long)(p.a_trans ? p.Kd : p.Md) * p.lda * 2;
   const long long bbytes = (long long)(p.b_trans ? p.Kd : p.Nd) * p.ldb * 2;
   if (abytes >= (1LL << 31) || bbytes >= (1LL << 31)) return hipErrorInvalidValue;
+  if (p.ksplit > 1 && (epi != EPI_WGRAD || !p.kpart || p.kchunk <= 0 || (p.kchunk & 63) ||
+                       (long long)p.kchunk * p.ksplit < p.Kd || (p.Nd & 3)))
+    return hipErrorInvalidValue;
   if (!p.a_trans && !p.b_trans) {
     if (epi == EPI_FWD_ACT) return launch_act<false, false, EPI_FWD_ACT>(p, s);
     if (epi == EPI_LOGITS) return launch_act<false, false, EPI_LOGITS>(p, s);
