@@ -29,6 +29,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PROF_EVERY = 4                 # per-kernel events on every 4th timed step
 COPY_GBS = 6700.0              # fastest plain copy measured on this machine (non-temporal, 16 B per thread)
 
 
@@ -187,22 +188,29 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     samples = 0
     sched = []
     t0 = time.perf_counter()
+    sampled = 0
     for s in range(a.warmup, total):
         samples += w.M * b
         sched.append(b)
+        # per-kernel HIP events on every PROF_EVERY-th step of the timed region only: two events per launch cost
+        # a few microseconds each, which would distort steps that take a few hundred
+        on = (s - a.warmup) % PROF_EVERY == 0
+        rep.profile_pause(not on)
+        sampled += on
         nb = run(s, b)
         b = nb if a.adaptive else b
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = rep.profile_read()
     rep.profile_enable(False)
+    scale = a.steps / max(sampled, 1)                  # sampled steps -> all timed steps (for the shares)
 
     # dominant kernel = the matrix-core GEMM class with the largest total time
     gemms = {k: v for k, v in prof.items() if k.startswith("gemm_")}
     kernels = {}
     for k, v in prof.items():
         e = {"calls": v["calls"], "avg_ms": v["total_ms"] / v["calls"],
-             "share": v["total_ms"] / (dt * 1e3)}
+             "share": v["total_ms"] * scale / (dt * 1e3)}
         if v["flops"] > 0:
             e["tflops"] = v["flops"] / (v["total_ms"] * 1e-3) / 1e12
             e["frac_of_mfma_peak"] = e["tflops"] / PEAK_BF16_TFLOPS
@@ -250,7 +258,7 @@ def measure(a, wname, np, torch, A, W, with_cpu):
         "roofline": roof, "kernels": kernels,
     }
     if with_cpu:
-        sb = a.cpu_sample_batch or {"config1": 512, "config2": 4096, "config3": 1024, "config4": 512}[wname]
+        sb = a.cpu_sample_batch or {"config1": 512, "config2": 4096, "config3": 2048, "config4": 1024}[wname]
         out["cpu_baseline"] = cpu_baseline(w, X, y, x0, min(sb, w.b_cap))
     return out
 

@@ -252,6 +252,10 @@ typedef struct {
 } abs_profile_entry;
 abs_status abs_profile_enable(abs_ctx *ctx, int on);
 abs_status abs_profile_read(abs_ctx *ctx, int max_entries, abs_profile_entry *out, int *n_entries);
+/* Suspend (paused != 0) or resume the bracketing without synchronising and without clearing the totals, so
+ * that a caller can sample some steps of a timed run and leave the others unperturbed (two events per
+ * launch cost a few microseconds, which matters when a whole step takes a few hundred). */
+abs_status abs_profile_pause(abs_ctx *ctx, int paused);
 
 /* Plain device-to-device copy kernel (one 16-byte vector per thread), bytes a multiple of 16,
  * both pointers 16-byte aligned.  It moves a known number of bytes, so its hardware-counter

@@ -26,7 +26,7 @@ EXPORTS = [
     "abs_layer_stats_workspace_bytes", "abs_average_bf16", "abs_destroy", "abs_last_error",
     "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
     "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
-    "abs_local_step_accumulated",
+    "abs_local_step_accumulated", "abs_profile_pause",
 ]
 
 
@@ -104,6 +104,7 @@ def load_library(reload: bool = False):
     lib.abs_norm_test_fpc.argtypes = [C.c_void_p, C.c_double, C.c_int64, C.POINTER(TestResult)]
     lib.abs_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.abs_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.abs_profile_pause.argtypes = [C.c_void_p, C.c_int]
     lib.abs_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(ProfileEntry), C.POINTER(C.c_int)]
     _lib = lib
     return lib
@@ -264,6 +265,9 @@ class Replicas:
 
     def profile_enable(self, on: bool = True):
         _check(self._lib.abs_profile_enable(self._ctx, int(bool(on))), self._ctx)
+
+    def profile_pause(self, paused: bool = True):
+        _check(self._lib.abs_profile_pause(self._ctx, int(bool(paused))), self._ctx)
 
     def profile_read(self):
         """{kernel class: dict(calls, total_ms, flops, bytes)} accumulated since profile_enable."""

@@ -395,6 +395,12 @@ abs_status abs_profile_enable(abs_ctx *c, int on) {
   return ABS_OK;
 }
 
+abs_status abs_profile_pause(abs_ctx *c, int paused) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  c->prof_on = paused == 0;       // no synchronisation, totals and pending records are kept
+  return ABS_OK;
+}
+
 abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out, int *n_entries) {
   if (!c || !out || !n_entries) return fail(ABS_EINVAL, "NULL argument");
   HIPCHK(c, hipStreamSynchronize(c->stream));
