@@ -151,7 +151,10 @@ class Replicas:
                       int(stats_mask), _stream_ptr(), None, 0)
         nbytes = C.c_size_t(0)
         _check(self._lib.abs_workspace_bytes(C.byref(cfg), N, C.byref(nbytes)))
-        self._ws = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=dev)
+        # 4 KiB of canary bytes behind the workspace: guard_intact() tells whether a kernel wrote past its end
+        self._guard = 4096
+        self._ws = torch.empty(nbytes.value + 256 + self._guard, dtype=torch.uint8, device=dev)
+        self._ws[-self._guard:].fill_(0xA5)
         base = (self._ws.data_ptr() + 255) // 256 * 256
         cfg.workspace, cfg.workspace_bytes = base, nbytes.value
         self.workspace_bytes = nbytes.value
@@ -265,6 +268,11 @@ class Replicas:
 
     def profile_enable(self, on: bool = True):
         _check(self._lib.abs_profile_enable(self._ctx, int(bool(on))), self._ctx)
+
+    def guard_intact(self) -> bool:
+        """True if the canary bytes behind the workspace still hold their pattern."""
+        self._torch.cuda.synchronize()
+        return bool((self._ws[-self._guard:] == 0xA5).all().item())
 
     def profile_pause(self, paused: bool = True):
         _check(self._lib.abs_profile_pause(self._ctx, int(bool(paused))), self._ctx)

@@ -493,6 +493,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       if (pl.bf16) {
         // ||a_i^l||^2 as per-tile partials out of the GEMM epilogue (summed by the statistics kernel)
         an_parts[l] = gemm_bf16_row_parts(b, pl.dims[l], M);
+        if (an_parts[l] > pl.rparts[l]) return cfail(c, ABS_ENOMEM, "row-partial scratch too small for this tile shape");
         if (want_parts) { p.part = c->at<float>(pl.o_an[l]); p.sPartg = cap * pl.rparts[l]; p.sPartTile = cap; }
         HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
       } else {
@@ -525,6 +526,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     if (pl.bf16) {
       // ||delta_i^{l-1}||^2 and (with biases) the column sums of delta^{l-1} as epilogue partials
       dn_parts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l - 1], M);
+      if (dn_parts[l - 1] > pl.rparts[l - 1]) return cfail(c, ABS_ENOMEM, "row-partial scratch too small for this tile shape");
       if (want_parts) { p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap; }
       if (hb && ph.wgrad) {
         p.cpart = c->at<float>(pl.o_colpart);
@@ -604,6 +606,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         p.sPartg = cap * pl.qparts[l - 1]; p.sPartTile = cap;
         HIPCHK(c, gemm(c, p, EPI_IPDOT, l));
         sp.qpart[l - 1] = p.part; sp.nparts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l], M);
+        if (sp.nparts[l - 1] > pl.qparts[l - 1]) return cfail(c, ABS_ENOMEM, "inner-product scratch too small for this tile shape");
         sp.sQg[l - 1] = p.sPartg; sp.sQpart[l - 1] = cap;
       } else {
         p.B = grad + pl.offW[l];

@@ -316,6 +316,7 @@ def test_full_size_at_the_cap_sampled_replicas(cfg, sampled):
         got = rep.get_params(w.M // 3)
         assert np.array_equal(got, rep.get_params(0)) and np.array_equal(got, rep.get_params(w.M - 1))
         assert np.abs(got - acc / w.M).max() <= 1e-6 * np.abs(acc / w.M).max()
+        assert rep.guard_intact()
     finally:
         rep.close()
 
@@ -842,3 +843,34 @@ def test_statistics_stress_full_size_sampled_replicas():
         for m in (0, 13, 31):
             got = params[m, s0:s1].float().cpu().numpy()
             assert (got != want).mean() < 2e-3 and np.abs(got - want).max() <= 2 ** -7 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("dims,act", [((784, 512, 512, 10), W.ACT_RELU), ((136, 264, 72, 100), W.ACT_GELU)])
+def test_batch_size_sweep_keeps_every_scratch_piece_in_bounds(dims, act):
+    """Every tile shape the GEMMs pick between b = 2 and the cap must fit the scratch pieces sized at
+    initialisation: the library refuses a step whose partials would not fit, and nothing is written past
+    the workspace; the statistics of replica 0 are checked against the oracle at every size."""
+    A = _A()
+    cap = 4096
+    w = W.Workload("sweep", dims, act, True, W.PREC_BF16, N=4096, M=8, H=1, rounds=1, b0=2, b_cap=cap, opt=W.OPT_SGD,
+                   lr=0.0, test=W.TEST_IP, theta=0.9, data="teacher_mlp", seed=37)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    net = O.Net(w.dims, w.act, w.has_bias)
+    try:
+        for b in (2, 63, 127, 128, 129, 511, 512, 1023, 1024, 1100, 2047, 2049, 4095, 4096):
+            idx = W.step_indices(w, 0, 1, b)
+            rep.local_step(idx, 0.0)                                  # lr = 0: the parameters stay at x0
+            g = rep.inner_product_test(w.theta)
+            one = O.Replicas(net, x0, X[idx[0]], y[idx[0]], 1, mixed=True, want_ip=True)
+            one.local_step([np.arange(b)], 0.0)
+            s = one.stats[0]
+            for name, got, want in (("S1", g[0].sum_sq, s["S1"]), ("S2", g[0].gbar_sq, s["S2"]),
+                                    ("S3", g[0].sum_q2, s["S3"]), ("S4", g[0].sum_q, s["S4"])):
+                assert _rel(got, want) <= 3e-3, (b, name, got, want)
+            grad = rep.get_grad(7).astype(np.float64)
+            assert np.isfinite(grad).all()
+            assert rep.guard_intact(), b
+    finally:
+        rep.close()
