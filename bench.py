@@ -46,6 +46,7 @@ def parse():
                     help="also run the library's plain copy kernel once on 2 x 1 GiB (the known-traffic "
                          "reference for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--no-also", action="store_true", help="skip the reference measurement of config 2 (profiling runs)")
     return ap.parse_args()
 
 
@@ -281,7 +282,7 @@ def main():
         print(json.dumps(stats_stress(a, np, torch, A, W)))
         return
     out = measure(a, a.workload, np, torch, A, W, not a.no_cpu_baseline)
-    if a.workload == "config3" and not a.adaptive and not a.batch:
+    if a.workload == "config3" and not a.adaptive and not a.batch and not a.no_also:
         # the medium configuration (MLP 784-512-512-10, M = 8) at its cap, same contract, for reference
         o2 = measure(a, "config2", np, torch, A, W, False)
         out["also"] = {o2["config"]["workload"]: {
