@@ -46,6 +46,8 @@ def parse():
                     help="also run the library's plain copy kernel once on 2 x 1 GiB (the known-traffic "
                          "reference for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--graphs", action="store_true",
+                    help="replay captured HIP graphs on the steps that are not bracketed by events (fixed batch size)")
     ap.add_argument("--no-also", action="store_true", help="skip the reference measurement of config 2 (profiling runs)")
     return ap.parse_args()
 
@@ -135,6 +137,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     w = getattr(W, wname)()
     X, y = W.make_dataset(w)
     x0 = W.make_x0(w)
+    if a.graphs:
+        torch.cuda.set_stream(torch.cuda.Stream())     # stream capture needs a created stream (default priority)
     rep = A.Replicas.from_workload(w, X, y, x0)
     b_fixed = a.batch or w.b_cap
 
@@ -166,7 +170,10 @@ def measure(a, wname, np, torch, A, W, with_cpu):
             t, _ = rep.upload_indices(np.ascontiguousarray(idx_dev[s][:, :b]))
         else:
             t = idx_dev[s]
-        rep.local_step_dev(t, b, w.lr)
+        if a.graphs:
+            rep.local_step_graphed_dev(t, b, w.lr)
+        else:
+            rep.local_step_dev(t, b, w.lr)
         nb = test_and_rule(b)
         if (s + 1) % w.H == 0:
             rep.average_replicas()
@@ -244,7 +251,10 @@ def measure(a, wname, np, torch, A, W, with_cpu):
         allt = sum(v["total_ms"] for v in gemms.values())
         roof["all_gemms_tflops"] = allf / (allt * 1e-3) / 1e12
         roof["all_gemms_frac"] = roof["all_gemms_tflops"] / PEAK_BF16_TFLOPS
+    n_graphs = rep.graph_count()
     rep.close()
+    if a.graphs:
+        torch.cuda.set_stream(torch.cuda.default_stream())
 
     out = {
         "metric": "local-step samples/sec (all replicas, incl. batch test)",
@@ -258,6 +268,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
                    "test": ["norm", "inner_product", "augmented_inner_product"][w.test]},
         "roofline": roof, "kernels": kernels,
     }
+    if a.graphs:
+        out["config"]["hip_graphs"] = n_graphs
     if with_cpu:
         sb = a.cpu_sample_batch or {"config1": 512, "config2": 4096, "config3": 2048, "config4": 1024}[wname]
         out["cpu_baseline"] = cpu_baseline(w, X, y, x0, min(sb, w.b_cap))

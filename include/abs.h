@@ -119,6 +119,18 @@ abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const 
 abs_status abs_local_step(abs_ctx *ctx, const int32_t *idx_dev, int b, float lr);
 
 /*
+ * abs_local_step for callers that repeat a batch size (for those that cannot afford the launch overhead of
+ * some forty kernels per step: small models, small batches).  The first step at a given b runs directly, the
+ * second is captured into a HIP graph, later ones replay it; one small launch in front of the graph carries
+ * idx_dev, lr and the optimizer's step-dependent scalars into fixed device locations.  Results are bitwise
+ * those of abs_local_step.  Graphs of up to 8 batch sizes are kept (least recently used dropped).  Steps are
+ * run directly, without capture, while abs_profile_enable is on or when the context uses the legacy default
+ * stream (stream capture needs a created stream); abs_graph_count tells how many graphs exist.
+ */
+abs_status abs_local_step_graphed(abs_ctx *ctx, const int32_t *idx_dev, int b, float lr);
+abs_status abs_graph_count(const abs_ctx *ctx, int *n /*host*/);
+
+/*
  * The same step as abs_local_step, with the batch of b samples processed in micro-batches of
  * micro_b <= b_cap samples ("gradient accumulation", Sec. 6, for batches whose activations do
  * not fit): b may exceed b_cap.  The gradient, S1 and the loss accumulate over the micro-batches

@@ -26,7 +26,7 @@ EXPORTS = [
     "abs_layer_stats_workspace_bytes", "abs_average_bf16", "abs_destroy", "abs_last_error",
     "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
     "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
-    "abs_local_step_accumulated", "abs_profile_pause",
+    "abs_local_step_accumulated", "abs_profile_pause", "abs_local_step_graphed", "abs_graph_count",
 ]
 
 
@@ -98,6 +98,8 @@ def load_library(reload: bool = False):
     lib.abs_lr_schedule.argtypes = [C.c_longlong, C.c_longlong, C.c_longlong, C.c_double, C.c_double,
                                     C.POINTER(C.c_double)]
     lib.abs_lr_linear_scaling.argtypes = [C.c_double, C.c_int64, C.c_int64, C.POINTER(C.c_double)]
+    lib.abs_local_step_graphed.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_float]
+    lib.abs_graph_count.argtypes = [C.c_void_p, C.POINTER(C.c_int)]
     lib.abs_local_step_accumulated.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float]
     lib.abs_local_step_ragged.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int), C.c_float]
     lib.abs_norm_test_per_worker.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(TestResult)]
@@ -189,6 +191,16 @@ class Replicas:
         """idx_dev: device int32 tensor holding M*b contiguous indices."""
         self._idx_keep = idx_dev
         _check(self._lib.abs_local_step(self._ctx, idx_dev.data_ptr(), int(b), float(lr)), self._ctx)
+
+    def local_step_graphed_dev(self, idx_dev, b: int, lr: float):
+        """As local_step_dev, replaying a captured HIP graph once this batch size has been seen twice."""
+        self._idx_keep = idx_dev
+        _check(self._lib.abs_local_step_graphed(self._ctx, idx_dev.data_ptr(), int(b), float(lr)), self._ctx)
+
+    def graph_count(self) -> int:
+        n = C.c_int(0)
+        _check(self._lib.abs_graph_count(self._ctx, C.byref(n)), self._ctx)
+        return n.value
 
     def local_step(self, idx: np.ndarray, lr: float):
         t, b = self.upload_indices(idx)

@@ -37,7 +37,7 @@ struct Plan {
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
   size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
-  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_kpart = 0;
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_kpart = 0, o_idx = 0, o_scal = 0;
   size_t kpart_floats = 0;             // scratch for the partial products of a split weight-gradient reduction
   size_t total = 0;
 };
@@ -151,6 +151,8 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
     pl.o_kpart = take(pl.kpart_floats * sizeof(float));
   }
   pl.o_cw = take((2 * STATS_PBLK + 8) * 8);
+  pl.o_idx = take((size_t)pl.M * pl.cap * sizeof(int32_t));      // inputs of replayed (graph) steps
+  pl.o_scal = take(256);
   pl.total = off;
 }
 
@@ -193,6 +195,10 @@ struct abs_ctx {
   int last_ps = -1;               // per-sample outputs stored (accumulated steps; -1: all of them)
   bool last_ragged = false;
   bool have_stats = false;
+  // captured steps (abs_local_step_graphed): one executable graph per batch size, a few kept
+  struct GraphSlot { int b; hipGraphExec_t exec; long long last_use; };
+  std::vector<GraphSlot> graphs;
+  std::vector<int> graph_warm;      // batch sizes that ran once eagerly (kernel attributes are set)
   std::string err;
 
   template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
@@ -382,6 +388,7 @@ abs_status abs_destroy(abs_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   if (c->host_stats) (void)hipHostFree(c->host_stats);
   for (ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.exec);
   delete c;
   return ABS_OK;
 }
@@ -429,6 +436,16 @@ abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out,
 // One local step.  b is the largest local batch size; with b_host (M entries, each in [2, b]) the
 // workers' batches are ragged: worker m uses the first b_host[m] entries of row m of idx (row
 // stride ldi) and every kernel takes its group's own row count from the device copy `rows`.
+// Host-side record of the step just enqueued (what the tests and getters refer to).
+static void note_step(abs_ctx *c, int b, const int *b_host) {
+  c->last_b = b;
+  c->last_bm.assign(c->pl.M, b);
+  if (b_host) c->last_bm.assign(b_host, b_host + c->pl.M);
+  c->last_ragged = b_host != nullptr;
+  c->last_ps = -1;
+  c->have_stats = true;
+}
+
 // Which parts of the step one call of local_step_impl runs.  A plain step runs all of them once;
 // a step accumulated over micro-batches runs the passes once per micro-batch for the gradient,
 // S1 and the loss, and (for the inner products, which need the batch gradient of the whole batch)
@@ -442,6 +459,8 @@ struct StepPhase {
   bool update = true;
   bool acc_grad = false, acc_n = false, acc_q = false;   // add to what earlier micro-batches left
   int b_total = 0;       // divisor of the batch gradient (0: this call's b)
+  float c1 = 1.0f, c2 = 1.0f;   // Adam bias corrections 1 / (1 - beta^t) of this step (set by the caller)
+  const float *scal = nullptr;  // device {lr, c1, c2} for replayable launches (then lr / c1 / c2 here are unused)
   long long ps_off = 0;  // offset of this call's samples in the per-sample outputs (-1: not stored)
 };
 
@@ -645,7 +664,6 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   }
   if (!ph.update) return ABS_OK;
   // optimizer update (Alg. 1: "local SGD step ... or other inner optimizers")
-  c->t += 1;
   UpdateP up;
   std::memset(&up, 0, sizeof(up));
   up.x = xm; up.g = grad;
@@ -655,10 +673,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   up.n = (long long)M * pl.Ppad;
   up.opt = c->cfg.opt; up.lr = lr; up.momentum = c->cfg.momentum;
   up.beta1 = c->cfg.beta1; up.beta2 = c->cfg.beta2; up.eps = c->cfg.eps; up.wd = c->cfg.weight_decay;
-  if (c->cfg.opt == ABS_OPT_ADAMW) {
-    up.c1 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta1, (double)c->t)));
-    up.c2 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta2, (double)c->t)));
-  }
+  up.c1 = ph.c1; up.c2 = ph.c2; up.scal = ph.scal;
   if (s2_in_update) up.sq_wave = c->at<float>(pl.o_sqwave);
   { ProfScope ps_(c, T_UPDATE, 0.0, 1.0 * M * pl.P * (c->cfg.opt == ABS_OPT_SGD ? 12 : c->cfg.opt == ABS_OPT_ADAMW ? 28 : 20) + (pl.bf16 ? 2.0 * M * pl.P : 0.0));
   HIPCHK(c, launch_update(up, s)); }
@@ -667,13 +682,17 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     ProfScope ps_(c, T_STATS, 0.0, 4.0 * M * (pl.Ppad / 256));
     HIPCHK(c, launch_stats(sp, s));
   }
-  c->last_b = ph.b_total > 0 ? ph.b_total : b;
-  c->last_bm.assign(M, c->last_b);
-  if (b_host) c->last_bm.assign(b_host, b_host + M);
-  c->last_ragged = b_host != nullptr;
-  c->last_ps = -1;
-  c->have_stats = true;
+  note_step(c, ph.b_total > 0 ? ph.b_total : b, b_host);
   return ABS_OK;
+}
+
+// One more optimizer step is about to be taken: advance the counter and return Adam's bias corrections.
+static void next_update(abs_ctx *c, StepPhase &ph) {
+  c->t += 1;
+  if (c->cfg.opt == ABS_OPT_ADAMW) {
+    ph.c1 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta1, (double)c->t)));
+    ph.c2 = (float)(1.0 / (1.0 - std::pow((double)c->cfg.beta2, (double)c->t)));
+  }
 }
 
 abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
@@ -681,7 +700,66 @@ abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
   if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
   if (b < 2 || b > c->pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
-  return local_step_impl(c, idx_dev, b, b, nullptr, lr);
+  StepPhase ph;
+  next_update(c, ph);
+  return local_step_impl(c, idx_dev, b, b, nullptr, lr, ph);
+}
+
+abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
+  if (b < 2 || b > c->pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
+  if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
+  // event brackets cannot be captured, nor can work on the legacy default stream: run such steps directly
+  if (c->prof_on || c->stream == nullptr) return abs_local_step(c, idx_dev, b, lr);
+  const Plan &pl = c->pl;
+  StepPhase ph;
+  next_update(c, ph);
+  int32_t *idx_in = c->at<int32_t>(pl.o_idx);
+  float *scal = c->at<float>(pl.o_scal);
+  ph.scal = scal;
+  // the only launch whose arguments change from step to step: it carries them into fixed device locations
+  HIPCHK(c, launch_stage_step_inputs(idx_dev, idx_in, (long long)pl.M * b, lr, ph.c1, ph.c2, scal, c->stream));
+  abs_ctx::GraphSlot *slot = nullptr;
+  for (auto &g : c->graphs) if (g.b == b) slot = &g;
+  if (!slot) {
+    bool warm = false;
+    for (int w : c->graph_warm) warm = warm || w == b;
+    if (!warm) {
+      // first step at this batch size: run it directly, which also sets the attributes of every kernel
+      // variant this size uses (not something to do inside a capture)
+      c->graph_warm.push_back(b);
+      return local_step_impl(c, idx_in, b, b, nullptr, lr, ph);
+    }
+    hipGraph_t graph = nullptr;
+    HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+    abs_status st = local_step_impl(c, idx_in, b, b, nullptr, lr, ph);
+    hipError_t e = hipStreamEndCapture(c->stream, &graph);
+    if (st != ABS_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
+    if (e != hipSuccess || !graph) return cfail(c, ABS_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return cfail(c, ABS_EHIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
+    if (c->graphs.size() >= 8) {                                  // keep a few sizes: drop the least recently used
+      size_t old = 0;
+      for (size_t i = 1; i < c->graphs.size(); ++i) if (c->graphs[i].last_use < c->graphs[old].last_use) old = i;
+      (void)hipGraphExecDestroy(c->graphs[old].exec);
+      c->graphs.erase(c->graphs.begin() + old);
+    }
+    c->graphs.push_back({b, exec, 0});
+    slot = &c->graphs.back();
+  }
+  slot->last_use = c->t;
+  HIPCHK(c, hipGraphLaunch(slot->exec, c->stream));
+  note_step(c, b, nullptr);
+  return ABS_OK;
+}
+
+abs_status abs_graph_count(const abs_ctx *c, int *n) {
+  if (!c || !n) return fail(ABS_EINVAL, "NULL argument");
+  *n = (int)c->graphs.size();
+  return ABS_OK;
 }
 
 abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b, int micro_b, float lr) {
@@ -721,6 +799,7 @@ abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b,
   StepPhase up;
   up.passes = up.wgrad = up.nstats = up.s2 = up.ip = false;
   up.b_total = b;
+  next_update(c, up);
   abs_status st = local_step_impl(c, idx_dev, b, micro_b, nullptr, lr, up);
   if (st != ABS_OK) return st;
   c->last_ps = 0;
@@ -741,7 +820,9 @@ abs_status abs_local_step_ragged(abs_ctx *c, const int32_t *idx_dev, int ldi, co
     if (b_host[m] > bmax) bmax = b_host[m];
   }
   if (ldi < bmax) return cfail(c, ABS_EINVAL, "ldi must be >= max_m b[m]");
-  return local_step_impl(c, idx_dev, ldi, bmax, b_host, lr);
+  StepPhase ph;
+  next_update(c, ph);
+  return local_step_impl(c, idx_dev, ldi, bmax, b_host, lr, ph);
 }
 
 static abs_status norm_test_impl(abs_ctx *c, const double *eta_m, double eta_all, int64_t n_total,

@@ -130,6 +130,8 @@ struct UpdateP {
   long long n;              // total elements (groups * Ppad)
   float *sq_wave;           // optional: sq_wave[i / 256] = sum of g^2 over parameters [256 i', 256 i' + 256)
   int opt; float lr, momentum, beta1, beta2, eps, wd, c1, c2;  // c = 1/(1-beta^t)
+  const float *scal;        // optional (device): {lr, c1, c2} read from memory instead of the fields above, so
+                            //   that a captured launch can be replayed with new values
 };
 hipError_t launch_update(const UpdateP &p, hipStream_t s);
 hipError_t launch_average_f32(float *x, bf16_t *shadow, int groups, long long Ppad, hipStream_t s);
@@ -142,6 +144,9 @@ hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);
 // C2 (bf16, may be null) gets the rounded result; rows (may be null): alpha = 1 / rows[g].  mn multiple of 4.
 hipError_t launch_splitk_finish(const float *kpart, int ksplit, int groups, long long mn, float alpha, const int *rows,
                                 float *C, long long sCg, bf16_t *C2, long long sC2g, int accumulate, hipStream_t s);
+// Inputs of a replayed step: idx_dst[0..n) = idx_src[0..n), scal[0..3) = {lr, c1, c2}
+hipError_t launch_stage_step_inputs(const int32_t *idx_src, int32_t *idx_dst, long long n, float lr, float c1, float c2,
+                                    float *scal, hipStream_t s);
 // dst[0..n) = v[0..n): the values travel as kernel arguments, so the host array may be reused at once
 enum { SET_INTS_MAX = 64 };
 hipError_t launch_set_ints(const int *v_host, int n, int *dst, hipStream_t s);

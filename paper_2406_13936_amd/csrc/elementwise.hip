@@ -326,7 +326,9 @@ __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restri
 // gradient entries it read: ||gbar||^2 then costs no second pass over the gradient.  (SQ launches use
 // a grid that covers the data in one pass, and n is a multiple of 256, so wavefronts are whole.)
 template <int OPT, bool SHADOW, bool SQ>
-__global__ void __launch_bounds__(256) update_kernel(const UpdateP p) {
+__global__ void __launch_bounds__(256) update_kernel(const UpdateP pin) {
+  UpdateP p = pin;
+  if (p.scal) { p.lr = p.scal[0]; p.c1 = p.scal[1]; p.c2 = p.scal[2]; }     // uniform loads
   const long long n4 = p.n / 4;
   const long long stride = (long long)gridDim.x * 256;
   for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n4; i += stride) {
@@ -492,6 +494,14 @@ __global__ void __launch_bounds__(256) splitk_finish_kernel(const float *__restr
     o.x = pack2bf(s.x, s.y); o.y = pack2bf(s.z, s.w);
     reinterpret_cast<uint2 *>(C2 + (long long)g * sC2g)[i] = o;
   }
+}
+
+__global__ void __launch_bounds__(256) stage_step_inputs_kernel(const int32_t *__restrict__ src, int32_t *__restrict__ dst,
+                                                                long long n, float lr, float c1, float c2,
+                                                                float *__restrict__ scal) {
+  const long long stride = (long long)gridDim.x * 256;
+  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+  if (blockIdx.x == 0 && threadIdx.x == 0) { scal[0] = lr; scal[1] = c1; scal[2] = c2; }
 }
 
 struct IntsArg { int v[SET_INTS_MAX]; };
@@ -662,6 +672,13 @@ hipError_t launch_splitk_finish(const float *kpart, int ksplit, int groups, long
   if (mn & 3) return hipErrorInvalidValue;
   hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((mn / 4 + 255) / 256), groups), dim3(256), 0, s, kpart, ksplit,
                      mn, alpha, rows, C, sCg, C2, sC2g, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_stage_step_inputs(const int32_t *idx_src, int32_t *idx_dst, long long n, float lr, float c1, float c2,
+                                    float *scal, hipStream_t s) {
+  hipLaunchKernelGGL(stage_step_inputs_kernel, dim3(grid_for(n, 256, 1024)), dim3(256), 0, s, idx_src, idx_dst, n, lr, c1,
+                     c2, scal);
   return hipGetLastError();
 }
 

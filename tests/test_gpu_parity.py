@@ -874,3 +874,44 @@ def test_batch_size_sweep_keeps_every_scratch_piece_in_bounds(dims, act):
             assert rep.guard_intact(), b
     finally:
         rep.close()
+
+
+@pytest.mark.parametrize("prec,opt", [(W.PREC_BF16, W.OPT_ADAMW), (W.PREC_F32, W.OPT_SHB)])
+def test_graph_replayed_steps_are_bitwise_the_direct_steps(prec, opt):
+    """abs_local_step_graphed against abs_local_step on twin replica sets: every step (first direct, second
+    captured, later ones replayed, two batch sizes interleaved, changing indices, learning rate and Adam
+    step count, tests and replica averages between the replays) must leave bitwise the same statistics
+    and parameters."""
+    import torch
+    A = _A()
+    w = W.Workload("graph", (136, 72, 10), W.ACT_GELU, True, prec, N=1024, M=4, H=3, rounds=1, b0=32, b_cap=64, opt=opt,
+                   lr=0.01, momentum=0.9, weight_decay=0.05, test=W.TEST_IP, theta=0.9, data="teacher_mlp", seed=41)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    side = torch.cuda.Stream()                 # stream capture needs a created stream (default priority)
+    with torch.cuda.stream(side):
+        ref = A.Replicas.from_workload(w, X, y, x0)
+        rep = A.Replicas.from_workload(w, X, y, x0)
+        try:
+            sizes = [32, 32, 32, 48, 32, 48, 48, 32, 64, 48, 32, 32]
+            for s, b in enumerate(sizes):
+                idx = W.step_indices(w, s, 0, b)
+                lr = 0.01 * (1 + s % 3)
+                t1, _ = ref.upload_indices(idx)
+                t2, _ = rep.upload_indices(idx)
+                ref.local_step_dev(t1, b, lr)
+                rep.local_step_graphed_dev(t2, b, lr)
+                g1, g2 = ref.inner_product_test(w.theta), rep.inner_product_test(w.theta)
+                for m in range(w.M):
+                    assert (g1[m].sum_sq, g1[m].gbar_sq, g1[m].sum_q, g1[m].sum_q2, g1[m].loss_sum) == \
+                           (g2[m].sum_sq, g2[m].gbar_sq, g2[m].sum_q, g2[m].sum_q2, g2[m].loss_sum), (s, m)
+                if (s + 1) % w.H == 0:
+                    ref.average_replicas()
+                    rep.average_replicas()
+                for m in (0, w.M - 1):
+                    assert np.array_equal(ref.get_params(m), rep.get_params(m)), (s, m)
+            assert rep.graph_count() == 2 and ref.graph_count() == 0      # 32 and 48 were seen twice; 64 only once
+            assert rep.guard_intact()
+        finally:
+            ref.close()
+            rep.close()
