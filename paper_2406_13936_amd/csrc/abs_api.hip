@@ -140,7 +140,7 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   }
   pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
   pl.o_stats = take((size_t)pl.M * 8 * 8);
-  pl.o_rows = take((size_t)pl.M * sizeof(int));
+  pl.o_rows = take((size_t)2 * pl.M * sizeof(int));          // per-group row counts, then the launch order
   pl.o_sqwave = take((size_t)pl.M * (pl.Ppad / 256) * sizeof(float));
   if (pl.bf16) {
     // a split is only taken when the un-split launch has fewer than 192 tiles, and never makes more than
@@ -150,7 +150,7 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
     pl.kpart_floats = std::min((size_t)8 * pl.M * mx, (size_t)512 * 65536);
     pl.o_kpart = take(pl.kpart_floats * sizeof(float));
   }
-  pl.o_cw = take((2 * STATS_PBLK + 8) * 8);
+  pl.o_cw = take((2 * (size_t)cross_worker_blocks(pl.Ppad) + 8) * 8);
   pl.o_idx = take((size_t)pl.M * pl.cap * sizeof(int32_t));      // inputs of replayed (graph) steps
   pl.o_scal = take(256);
   pl.total = off;
@@ -468,11 +468,26 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
                                   const StepPhase &ph = StepPhase()) {
   const Plan &pl = c->pl;
   const int L = pl.L, M = pl.M, isb = pl.bf16 ? 1 : 0;
-  const int *rows = nullptr;
+  const int *rows = nullptr, *gperm = nullptr;
   if (b_host) {
+    // row counts, and an order of the groups in which each of the 8 XCDs (which take contiguous ranges of
+    // that order) gets about the same number of rows: sort by size, deal in snake order
+    std::vector<int> both(2 * (size_t)M);
+    std::copy(b_host, b_host + M, both.begin());
+    std::vector<int> order(M);
+    for (int m = 0; m < M; ++m) order[m] = m;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return b_host[x] > b_host[y]; });
+    std::vector<std::vector<int>> deal(8);
+    for (int i = 0; i < M; ++i) {
+      const int r = i / 8, j = i % 8;
+      deal[(r & 1) ? 7 - j : j].push_back(order[i]);
+    }
+    int pos = 0;
+    for (int x = 0; x < 8; ++x) for (int gidx : deal[x]) both[M + pos++] = gidx;
     int *rows_dev = c->at<int>(pl.o_rows);
-    HIPCHK(c, launch_set_ints(b_host, M, rows_dev, c->stream));
+    HIPCHK(c, launch_set_ints(both.data(), 2 * M, rows_dev, c->stream));
     rows = rows_dev;
+    if (M >= 8) gperm = rows_dev + M;
   }
   int an_parts[MAXL + 1], dn_parts[MAXL + 2];
   for (int l = 0; l <= MAXL; ++l) an_parts[l] = dn_parts[l] = 1;
@@ -503,7 +518,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     std::memset(&p, 0, sizeof(p));
     p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
     p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1];
-    p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows;
+    p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows; p.gperm = gperm;
     if (hb) { p.bias = xm + pl.offB[l]; p.sBiasg = pl.Ppad; }
     p.act = c->cfg.act;
     if (l < L) {
@@ -537,7 +552,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     std::memset(&p, 0, sizeof(p));
     p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l];
     p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1]; p.b_trans = 1;
-    p.Md = b; p.Nd = pl.dims[l - 1]; p.Kd = pl.dims[l]; p.groups = M; p.rows = rows;
+    p.Md = b; p.Nd = pl.dims[l - 1]; p.Kd = pl.dims[l]; p.groups = M; p.rows = rows; p.gperm = gperm;
     p.C = act_ptr(pl.o_Dl[l - 1]); p.sCg = cap * pl.ld[l - 1]; p.ldc = pl.ld[l - 1]; p.pad_to_ld = 1;
     p.act = c->cfg.act;
     p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
@@ -575,7 +590,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     std::memset(&p, 0, sizeof(p));
     p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l]; p.a_trans = 1;
     p.B = act_ptr(pl.o_A[l - 1]); p.sBg = cap * pl.ld[l - 1]; p.ldb = pl.ld[l - 1]; p.b_trans = 1;
-    p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M; p.rows = rows; p.rows_is_k = 1;
+    p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M; p.rows = rows; p.gperm = gperm; p.rows_is_k = 1;
     p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
     p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
     if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
@@ -615,7 +630,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       GemmP p;
       std::memset(&p, 0, sizeof(p));
       p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
-      p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows;
+      p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows; p.gperm = gperm;
       p.ldb = pl.dims[l - 1]; p.sBg = pl.Ppad;
       if (hb) { p.bias = grad + pl.offB[l]; p.sBiasg = pl.Ppad; }
       if (pl.bf16) {

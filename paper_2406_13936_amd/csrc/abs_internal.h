@@ -43,6 +43,10 @@ struct GemmP {
   // grid.  Memory beyond a group's own rows is neither read nor written.
   const int *rows;
   int rows_is_k;
+  // Optional (device, bf16 family): the order in which the launch walks the groups.  Work-group ids are dealt
+  // to the XCDs in contiguous ranges of groups, so with ragged groups the host orders them such that every
+  // XCD gets about the same number of rows.
+  const int *gperm;
   int accumulate;              // EPI_WGRAD: C = alpha * acc + C  (micro-batch accumulation)
   // Split reduction (EPI_WGRAD of the bf16 family, optional): ksplit > 1 cuts k into ksplit slices of
   // kchunk elements; slice sp of group g writes its raw partial product to
@@ -136,7 +140,9 @@ struct UpdateP {
 hipError_t launch_update(const UpdateP &p, hipStream_t s);
 hipError_t launch_average_f32(float *x, bf16_t *shadow, int groups, long long Ppad, hipStream_t s);
 hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s);
-// cross-worker statistics: out[0] = sum_m ||g^m||^2, out[1] = ||mean_m g^m||^2
+// cross-worker statistics: out[0] = sum_m ||g^m||^2, out[1] = ||mean_m g^m||^2;
+// partials: 2 * cross_worker_blocks(Ppad) doubles of scratch
+int cross_worker_blocks(long long Ppad);
 hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials,
                                double *out, hipStream_t s);
 hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);

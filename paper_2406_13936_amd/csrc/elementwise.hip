@@ -433,32 +433,40 @@ __global__ void __launch_bounds__(256) average_bf16_kernel(bf16_t *__restrict__ 
   }
 }
 
-// sum_m ||g^m||^2 and ||mean_m g^m||^2 over the padded gradient block (Alg. 2 statistics)
+// sum_m ||g^m||^2 and ||mean_m g^m||^2 over the padded gradient block (Alg. 2 statistics).
+// Stage 1 (data-sized grid): a thread owns four consecutive parameters, reads them from every worker's
+// gradient (in worker order) and adds its two contributions; one pair of partials per block.
+// Stage 2 (one block): the block partials are added in index order.
 __global__ void __launch_bounds__(256) cross_worker_kernel(const float *__restrict__ grad, int groups,
-                                                           long long Ppad, double *__restrict__ partials) {
+                                                           long long Ppad, double *__restrict__ partials, int nblocks) {
   __shared__ double red[4];
+  const long long n4 = Ppad / 4;
+  const long long i = blockIdx.x * 256LL + threadIdx.x;
   double ss = 0.0, sm = 0.0;
-  const double invM = 1.0 / (double)groups;
-  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < Ppad; i += 256LL * STATS_PBLK) {
-    double s = 0.0;
+  if (i < n4) {
+    double sx = 0.0, sy = 0.0, sz = 0.0, sw = 0.0;
     for (int g = 0; g < groups; ++g) {
-      const double v = (double)grad[(long long)g * Ppad + i];
-      s += v;
-      ss += v * v;
+      const float4 v = ld_stream(reinterpret_cast<const float4 *>(grad + (long long)g * Ppad) + i);
+      const double x = v.x, y = v.y, z = v.z, w = v.w;
+      sx += x; sy += y; sz += z; sw += w;
+      ss += x * x + y * y + z * z + w * w;
     }
-    s *= invM;
-    sm += s * s;
+    const double inv = 1.0 / (double)groups;
+    sx *= inv; sy *= inv; sz *= inv; sw *= inv;
+    sm = sx * sx + sy * sy + sz * sz + sw * sw;
   }
   double r = block_sum<4>(ss, red);
   if (threadIdx.x == 0) partials[blockIdx.x] = r;
   r = block_sum<4>(sm, red);
-  if (threadIdx.x == 0) partials[STATS_PBLK + blockIdx.x] = r;
+  if (threadIdx.x == 0) partials[nblocks + blockIdx.x] = r;
 }
-__global__ void __launch_bounds__(256) cross_worker_final_kernel(const double *__restrict__ partials,
+__global__ void __launch_bounds__(256) cross_worker_final_kernel(const double *__restrict__ partials, int nblocks,
                                                                  double *__restrict__ out) {
   __shared__ double red[4];
   for (int k = 0; k < 2; ++k) {
-    const double r = block_sum<4>(partials[k * STATS_PBLK + threadIdx.x], red);
+    double s = 0.0;
+    for (int i = threadIdx.x; i < nblocks; i += 256) s += partials[(long long)k * nblocks + i];
+    const double r = block_sum<4>(s, red);
     if (threadIdx.x == 0) out[k] = r;
   }
 }
@@ -654,10 +662,13 @@ hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s
 
 hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials, double *out,
                                hipStream_t s) {
-  hipLaunchKernelGGL(cross_worker_kernel, dim3(STATS_PBLK), dim3(256), 0, s, g, groups, Ppad, partials);
-  hipLaunchKernelGGL(cross_worker_final_kernel, dim3(1), dim3(256), 0, s, partials, out);
+  const int nblocks = cross_worker_blocks(Ppad);
+  hipLaunchKernelGGL(cross_worker_kernel, dim3(nblocks), dim3(256), 0, s, g, groups, Ppad, partials, nblocks);
+  hipLaunchKernelGGL(cross_worker_final_kernel, dim3(1), dim3(256), 0, s, partials, nblocks, out);
   return hipGetLastError();
 }
+
+int cross_worker_blocks(long long Ppad) { return (int)((Ppad / 4 + 255) / 256); }
 
 hipError_t launch_copy_probe(const void *src, void *dst, long long bytes, hipStream_t s) {
   const long long n16 = bytes / 16;

@@ -195,7 +195,8 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   const int vg = lb / per_g;                      // group, or (group, k-slice) pair of a split reduction
   const int t = lb - vg * per_g;
   const int ksplit = (EPI == EPI_WGRAD && pin.ksplit > 1) ? pin.ksplit : 1;
-  const int g = vg / ksplit, ksl = vg - g * ksplit;
+  const int gv = vg / ksplit, ksl = vg - gv * ksplit;
+  const int g = pin.gperm ? pin.gperm[gv] : gv;   // position in the launch order -> group
   const int tm = t / tilesN, tn = t - tm * tilesN;
   const int m0 = tm * BM, n0 = tn * BN;
   GemmP p = pin;
@@ -562,7 +563,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   bf16_t *C2g = (EPI == EPI_WGRAD && p.C2) ? static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g : nullptr;
   bool accumulate = EPI == EPI_WGRAD && p.accumulate;        // micro-batch accumulation: C += alpha * acc
   if (EPI == EPI_WGRAD && ksplit > 1) {                      // raw partial product of this k-slice
-    Cg = p.kpart + (long long)vg * p.Md * p.Nd;
+    Cg = p.kpart + ((long long)g * ksplit + ksl) * p.Md * p.Nd;
     p.ldc = p.Nd; p.alpha = 1.0f;
     C2g = nullptr; accumulate = false;
   }
