@@ -229,21 +229,29 @@ def measure(a, wname, np, torch, A, W, with_cpu):
         kernels[k] = e
     roof = None
     if gemms and w.prec == W.PREC_BF16:
-        name = max(gemms, key=lambda k: gemms[k]["total_ms"])
-        v = gemms[name]
+        # Launch classes as a kernel trace sees them: one kernel symbol per (epilogue, tile shape), whatever the
+        # layer.  The dominant kernel is the class with the largest total time; its average launch duration is
+        # what `rocprofv3 --kernel-trace --stats` reports for that symbol.
+        classes = {}
+        for k, v in gemms.items():
+            cname = k.rsplit("_L", 1)[0]
+            ce = classes.setdefault(cname, {"total_ms": 0.0, "flops": 0.0, "calls": 0, "layers": []})
+            ce["total_ms"] += v["total_ms"]; ce["flops"] += v["flops"]; ce["calls"] += v["calls"]; ce["layers"].append(k)
+        name = max(classes, key=lambda k: classes[k]["total_ms"])
+        v = classes[name]
         ach = v["flops"] / (v["total_ms"] * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": name, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
                 "avg_launch_ms": v["total_ms"] / v["calls"], "launches": v["calls"],
-                "flops_per_launch": v["flops"] / v["calls"]}
-        # HBM bytes per launch from the committed rocprofv3 --pmc summary of this same command
-        # (FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel); null when no summary covers it
+                "flops_per_launch": v["flops"] / v["calls"], "layers": sorted(v["layers"])}
+        # HBM bytes per launch (mean over the class's layers) from the committed rocprofv3 --pmc summary of this
+        # same command (FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel); null when no summary covers it
         tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.json" % wname)
         if os.path.exists(tpath) and not a.adaptive and not a.batch:
             try:
-                tj = json.load(open(tpath))
-                if name in tj.get("kernels", {}):
-                    roof["traffic"] = tj["kernels"][name]["hbm_bytes_per_launch"]
+                tj = json.load(open(tpath)).get("kernels", {})
+                if all(k in tj for k in v["layers"]):
+                    roof["traffic"] = sum(tj[k]["hbm_bytes_per_launch"] for k in v["layers"]) / len(v["layers"])
                     roof["traffic_source"] = "profiles/" + os.path.basename(tpath)
             except Exception:
                 pass
