@@ -506,119 +506,120 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   const bool want_parts = ph.nstats;      // row-norm partials feed S1 only
   const float inv_b = 1.0f / (float)(ph.b_total > 0 ? ph.b_total : b);
   if (ph.passes) {
-  // batch gather (Alg. 1: "sample the local batch")
-  const void *Xsrc = pl.bf16 ? static_cast<const void *>(c->at<bf16_t>(pl.o_Xbf)) : static_cast<const void *>(c->X);
-  { ProfScope ps_(c, T_GATHER, 0.0, 2.0 * M * b * pl.dims[0] * pl.esz);
-  HIPCHK(c, launch_gather_rows(isb, Xsrc, pl.dims[0], (int)c->N, idx_dev, ldi, M, b, act_ptr(pl.o_A[0]), cap * pl.ld[0],
-                               pl.ld[0], c->at<float>(pl.o_an[0]), cap, rows, s)); }
+    // batch gather (Alg. 1: "sample the local batch")
+    const void *Xsrc = pl.bf16 ? static_cast<const void *>(c->at<bf16_t>(pl.o_Xbf)) : static_cast<const void *>(c->X);
+    { ProfScope ps_(c, T_GATHER, 0.0, 2.0 * M * b * pl.dims[0] * pl.esz);
+    HIPCHK(c, launch_gather_rows(isb, Xsrc, pl.dims[0], (int)c->N, idx_dev, ldi, M, b, act_ptr(pl.o_A[0]), cap * pl.ld[0],
+                                 pl.ld[0], c->at<float>(pl.o_an[0]), cap, rows, s)); }
 
-  // forward
-  for (int l = 1; l <= L; ++l) {
-    GemmP p;
-    std::memset(&p, 0, sizeof(p));
-    p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
-    p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1];
-    p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows; p.gperm = gperm;
-    if (hb) { p.bias = xm + pl.offB[l]; p.sBiasg = pl.Ppad; }
-    p.act = c->cfg.act;
-    if (l < L) {
-      p.C = act_ptr(pl.o_A[l]); p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l]; p.pad_to_ld = 1;
-      if (pl.gelu) { p.C2 = act_ptr(pl.o_Dact[l]); p.sC2g = cap * pl.ld[l]; p.ldc2 = pl.ld[l]; }
-      if (pl.bf16) {
-        // ||a_i^l||^2 as per-tile partials out of the GEMM epilogue (summed by the statistics kernel)
-        an_parts[l] = gemm_bf16_row_parts(b, pl.dims[l], M);
-        if (an_parts[l] > pl.rparts[l]) return cfail(c, ABS_ENOMEM, "row-partial scratch too small for this tile shape");
-        if (want_parts) { p.part = c->at<float>(pl.o_an[l]); p.sPartg = cap * pl.rparts[l]; p.sPartTile = cap; }
-        HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
+    // forward
+    for (int l = 1; l <= L; ++l) {
+      GemmP p;
+      std::memset(&p, 0, sizeof(p));
+      p.A = act_ptr(pl.o_A[l - 1]); p.sAg = cap * pl.ld[l - 1]; p.lda = pl.ld[l - 1];
+      p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1];
+      p.Md = b; p.Nd = pl.dims[l]; p.Kd = pl.dims[l - 1]; p.groups = M; p.rows = rows; p.gperm = gperm;
+      if (hb) { p.bias = xm + pl.offB[l]; p.sBiasg = pl.Ppad; }
+      p.act = c->cfg.act;
+      if (l < L) {
+        p.C = act_ptr(pl.o_A[l]); p.sCg = cap * pl.ld[l]; p.ldc = pl.ld[l]; p.pad_to_ld = 1;
+        if (pl.gelu) { p.C2 = act_ptr(pl.o_Dact[l]); p.sC2g = cap * pl.ld[l]; p.ldc2 = pl.ld[l]; }
+        if (pl.bf16) {
+          // ||a_i^l||^2 as per-tile partials out of the GEMM epilogue (summed by the statistics kernel)
+          an_parts[l] = gemm_bf16_row_parts(b, pl.dims[l], M);
+          if (an_parts[l] > pl.rparts[l]) return cfail(c, ABS_ENOMEM, "row-partial scratch too small for this tile shape");
+          if (want_parts) { p.part = c->at<float>(pl.o_an[l]); p.sPartg = cap * pl.rparts[l]; p.sPartTile = cap; }
+          HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
+        } else {
+          HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
+          if (!want_parts) continue;
+          ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
+          HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, rows, s));
+        }
       } else {
-        HIPCHK(c, gemm(c, p, EPI_FWD_ACT, l));
+        p.C = c->at<float>(pl.o_Z); p.sCg = cap * pl.ld[L]; p.ldc = pl.ld[L];
+        HIPCHK(c, gemm(c, p, EPI_LOGITS, l));
+      }
+    }
+    // loss head: per-sample backprop signal of the last layer
+    { ProfScope ps_(c, T_SOFTMAX, 0.0, 1.0 * M * b * pl.ld[L] * (4 + pl.esz));
+    HIPCHK(c, launch_softmax_ce(isb, c->at<float>(pl.o_Z), cap * pl.ld[L], pl.ld[L], pl.dims[L], c->y, (int)c->N, idx_dev, ldi, M, b,
+                                act_ptr(pl.o_Dl[L]), cap * pl.ld[L], pl.ld[L], c->at<float>(pl.o_dn[L]),
+                                c->at<float>(pl.o_loss), cap, rows, s)); }
+    // backward-data
+    for (int l = L; l >= 2; --l) {
+      GemmP p;
+      std::memset(&p, 0, sizeof(p));
+      p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l];
+      p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1]; p.b_trans = 1;
+      p.Md = b; p.Nd = pl.dims[l - 1]; p.Kd = pl.dims[l]; p.groups = M; p.rows = rows; p.gperm = gperm;
+      p.C = act_ptr(pl.o_Dl[l - 1]); p.sCg = cap * pl.ld[l - 1]; p.ldc = pl.ld[l - 1]; p.pad_to_ld = 1;
+      p.act = c->cfg.act;
+      p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
+      p.sEg = cap * pl.ld[l - 1]; p.lde = pl.ld[l - 1];
+      if (pl.bf16) {
+        // ||delta_i^{l-1}||^2 and (with biases) the column sums of delta^{l-1} as epilogue partials
+        dn_parts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l - 1], M);
+        if (dn_parts[l - 1] > pl.rparts[l - 1]) return cfail(c, ABS_ENOMEM, "row-partial scratch too small for this tile shape");
+        if (want_parts) { p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap; }
+        if (hb && ph.wgrad) {
+          p.cpart = c->at<float>(pl.o_colpart);
+          p.sCpartg = (long long)gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1];
+          if ((size_t)p.sCpartg > pl.colpart_per) return cfail(c, ABS_ENOMEM, "column-partial scratch too small for this tile shape");
+        }
+        HIPCHK(c, gemm(c, p, EPI_BWD, l));
+        if (hb && ph.wgrad) {
+          ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1]);
+          int tile_m = 0, ppt = 0;
+          gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1], M), &tile_m, &ppt);
+          HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1], M), M,
+                                          inv_b, grad + pl.offB[l - 1], pl.Ppad, rows, tile_m, ppt, ph.acc_grad ? 1 : 0, s));
+        }
+      } else {
+        HIPCHK(c, gemm(c, p, EPI_BWD, l));
         if (!want_parts) continue;
-        ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
-        HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l], pl.ld[l], M, b, c->at<float>(pl.o_an[l]), cap, rows, s));
+        ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
+        HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, rows, s));
       }
-    } else {
-      p.C = c->at<float>(pl.o_Z); p.sCg = cap * pl.ld[L]; p.ldc = pl.ld[L];
-      HIPCHK(c, gemm(c, p, EPI_LOGITS, l));
     }
-  }
-  // loss head: per-sample backprop signal of the last layer
-  { ProfScope ps_(c, T_SOFTMAX, 0.0, 1.0 * M * b * pl.ld[L] * (4 + pl.esz));
-  HIPCHK(c, launch_softmax_ce(isb, c->at<float>(pl.o_Z), cap * pl.ld[L], pl.ld[L], pl.dims[L], c->y, (int)c->N, idx_dev, ldi, M, b,
-                              act_ptr(pl.o_Dl[L]), cap * pl.ld[L], pl.ld[L], c->at<float>(pl.o_dn[L]),
-                              c->at<float>(pl.o_loss), cap, rows, s)); }
-  // backward-data
-  for (int l = L; l >= 2; --l) {
-    GemmP p;
-    std::memset(&p, 0, sizeof(p));
-    p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l];
-    p.B = wptr(l); p.sBg = pl.Ppad; p.ldb = pl.dims[l - 1]; p.b_trans = 1;
-    p.Md = b; p.Nd = pl.dims[l - 1]; p.Kd = pl.dims[l]; p.groups = M; p.rows = rows; p.gperm = gperm;
-    p.C = act_ptr(pl.o_Dl[l - 1]); p.sCg = cap * pl.ld[l - 1]; p.ldc = pl.ld[l - 1]; p.pad_to_ld = 1;
-    p.act = c->cfg.act;
-    p.E = pl.gelu ? act_ptr(pl.o_Dact[l - 1]) : act_ptr(pl.o_A[l - 1]);
-    p.sEg = cap * pl.ld[l - 1]; p.lde = pl.ld[l - 1];
-    if (pl.bf16) {
-      // ||delta_i^{l-1}||^2 and (with biases) the column sums of delta^{l-1} as epilogue partials
-      dn_parts[l - 1] = gemm_bf16_row_parts(b, pl.dims[l - 1], M);
-      if (dn_parts[l - 1] > pl.rparts[l - 1]) return cfail(c, ABS_ENOMEM, "row-partial scratch too small for this tile shape");
-      if (want_parts) { p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap; }
-      if (hb && ph.wgrad) {
-        p.cpart = c->at<float>(pl.o_colpart);
-        p.sCpartg = (long long)gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1];
-        if ((size_t)p.sCpartg > pl.colpart_per) return cfail(c, ABS_ENOMEM, "column-partial scratch too small for this tile shape");
-      }
-      HIPCHK(c, gemm(c, p, EPI_BWD, l));
-      if (hb && ph.wgrad) {
-        ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1]);
-        int tile_m = 0, ppt = 0;
-        gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1], M), &tile_m, &ppt);
-        HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1], M), M,
-                                        inv_b, grad + pl.offB[l - 1], pl.Ppad, rows, tile_m, ppt, ph.acc_grad ? 1 : 0, s));
-      }
-    } else {
-      HIPCHK(c, gemm(c, p, EPI_BWD, l));
-      if (!want_parts) continue;
-      ProfScope ps_(c, T_ROWNORM, 0.0, 1.0 * M * b * pl.ld[l - 1] * pl.esz);
-      HIPCHK(c, launch_row_sqnorm(isb, p.C, p.sCg, pl.ld[l - 1], pl.ld[l - 1], M, b, c->at<float>(pl.o_dn[l - 1]), cap, rows, s));
-    }
-  }
   }   // passes
   // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
-  if (ph.wgrad)
-  for (int l = 1; l <= L; ++l) {
-    GemmP p;
-    std::memset(&p, 0, sizeof(p));
-    p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l]; p.a_trans = 1;
-    p.B = act_ptr(pl.o_A[l - 1]); p.sBg = cap * pl.ld[l - 1]; p.ldb = pl.ld[l - 1]; p.b_trans = 1;
-    p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M; p.rows = rows; p.gperm = gperm; p.rows_is_k = 1;
-    p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
-    p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
-    if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
-    if (pl.bf16 && p.ldc == p.Nd && (p.Nd & 3) == 0) {
-      // few output tiles and a long reduction (small layers, or any layer while b is the long side): cut
-      // the reduction into slices so that the launch fills the chip, and add the slices in order afterwards
-      const int sh = gemm_bf16_tile_shape(p.Md, p.Nd, M);
-      const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
-      const long long tiles = (long long)((p.Md + te - 1) / te) * ((p.Nd + tn_e - 1) / tn_e) * M;
-      const int KT = (b + 63) / 64;
-      long long S = std::min<long long>(std::min<long long>(8, 512 / std::max<long long>(tiles, 1)), KT / 4);
-      while (S > 1 && (size_t)S * M * p.Md * p.Nd > pl.kpart_floats) --S;
-      if (tiles < 192 && S > 1) {
-        p.ksplit = (int)S;
-        p.kchunk = (int)(((KT + S - 1) / S) * 64);
-        p.kpart = c->at<float>(pl.o_kpart);
+  if (ph.wgrad) {
+    for (int l = 1; l <= L; ++l) {
+      GemmP p;
+      std::memset(&p, 0, sizeof(p));
+      p.A = act_ptr(pl.o_Dl[l]); p.sAg = cap * pl.ld[l]; p.lda = pl.ld[l]; p.a_trans = 1;
+      p.B = act_ptr(pl.o_A[l - 1]); p.sBg = cap * pl.ld[l - 1]; p.ldb = pl.ld[l - 1]; p.b_trans = 1;
+      p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M; p.rows = rows; p.gperm = gperm; p.rows_is_k = 1;
+      p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
+      p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
+      if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
+      if (pl.bf16 && p.ldc == p.Nd && (p.Nd & 3) == 0) {
+        // few output tiles and a long reduction (small layers, or any layer while b is the long side): cut
+        // the reduction into slices so that the launch fills the chip, and add the slices in order afterwards
+        const int sh = gemm_bf16_tile_shape(p.Md, p.Nd, M);
+        const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
+        const long long tiles = (long long)((p.Md + te - 1) / te) * ((p.Nd + tn_e - 1) / tn_e) * M;
+        const int KT = (b + 63) / 64;
+        long long S = std::min<long long>(std::min<long long>(8, 512 / std::max<long long>(tiles, 1)), KT / 4);
+        while (S > 1 && (size_t)S * M * p.Md * p.Nd > pl.kpart_floats) --S;
+        if (tiles < 192 && S > 1) {
+          p.ksplit = (int)S;
+          p.kchunk = (int)(((KT + S - 1) / S) * 64);
+          p.kpart = c->at<float>(pl.o_kpart);
+        }
       }
-    }
-    HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
-    if (p.ksplit > 1) {
-      ProfScope ps_(c, T_COLSUM, 0.0, (4.0 * p.ksplit + 6.0) * M * p.Md * p.Nd);
-      HIPCHK(c, launch_splitk_finish(p.kpart, p.ksplit, M, (long long)p.Md * p.Nd, inv_b, rows, static_cast<float *>(p.C),
-                                     p.sCg, static_cast<bf16_t *>(p.C2), p.sC2g, p.accumulate, s));
-    }
-    if (hb && (!pl.bf16 || l == L)) {   // bf16 mode: layers below L got theirs from the backward epilogue
-      ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
-      HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad,
-                               c->at<float>(pl.o_colpart), rows, ph.acc_grad ? 1 : 0, s));
+      HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
+      if (p.ksplit > 1) {
+        ProfScope ps_(c, T_COLSUM, 0.0, (4.0 * p.ksplit + 6.0) * M * p.Md * p.Nd);
+        HIPCHK(c, launch_splitk_finish(p.kpart, p.ksplit, M, (long long)p.Md * p.Nd, inv_b, rows, static_cast<float *>(p.C),
+                                       p.sCg, static_cast<bf16_t *>(p.C2), p.sC2g, p.accumulate, s));
+      }
+      if (hb && (!pl.bf16 || l == L)) {   // bf16 mode: layers below L got theirs from the backward epilogue
+        ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
+        HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad,
+                                 c->at<float>(pl.o_colpart), rows, ph.acc_grad ? 1 : 0, s));
+      }
     }
   }
   // inner products <g_i, gbar>
