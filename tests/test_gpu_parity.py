@@ -918,3 +918,52 @@ def test_graph_replayed_steps_are_bitwise_the_direct_steps(prec, opt):
         finally:
             ref.close()
             rep.close()
+
+
+@pytest.mark.parametrize("case", range(14))
+def test_random_small_configurations(case):
+    """Seeded random shapes (depth, widths, activation, bias, precision, optimizer, workers, batch sizes,
+    uniform or ragged): one step against the oracle."""
+    A = _A()
+    rng = np.random.default_rng(1000 + case)
+    prec = W.PREC_BF16 if case % 2 == 0 else W.PREC_F32
+    L = int(rng.integers(1, 5))
+    mult = 8 if prec == W.PREC_BF16 else 1
+    dims = [int(rng.integers(1, 40)) * mult for _ in range(L)] + [int(rng.integers(2, 130))]
+    act = int(rng.integers(0, 3))
+    hb = bool(rng.integers(0, 2))
+    opt = int(rng.integers(0, 4))
+    M = int(rng.integers(1, 10))
+    cap = int(rng.integers(4, 700))
+    ragged = bool(rng.integers(0, 2))
+    bs = [int(rng.integers(2, cap + 1)) for _ in range(M)] if ragged else [int(rng.integers(2, cap + 1))] * M
+    test = W.TEST_AUG_IP if rng.integers(0, 2) else W.TEST_NORM
+    w = W.Workload("rand%d" % case, tuple(dims), act, hb, prec, N=1024, M=M, H=1, rounds=1, b0=max(bs), b_cap=cap, opt=opt,
+                   lr=0.02, momentum=0.9, weight_decay=0.05, test=test, eta=0.5, theta=0.9, nu=0.5,
+                   data="teacher_mlp", seed=100 + case)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    mixed = prec == W.PREC_BF16
+    orc = _oracle_for(w, X, y, x0, mixed=mixed)
+    tol = 3e-3 if mixed else 2e-4
+    try:
+        rows = _ragged_rows(w, bs)
+        if ragged:
+            rep.local_step_ragged(rows, w.lr)
+        else:
+            rep.local_step(np.stack(rows), w.lr)
+        orc.local_step(rows, w.lr)
+        g = _gpu_test(rep, w)
+        for m in range(M):
+            s = orc.stats[m]
+            names = [("S1", g[m].sum_sq, s["S1"]), ("S2", g[m].gbar_sq, s["S2"]), ("loss", g[m].loss_sum, s["loss_sum"])]
+            if test != W.TEST_NORM:
+                names += [("S3", g[m].sum_q2, s["S3"]), ("S4", g[m].sum_q, s["S4"])]
+            for name, got, want in names:
+                assert abs(got - want) <= tol * max(abs(want), 1e-12) + 1e-12, (case, m, name, got, want, dims, bs)
+            grad = rep.get_grad(m).astype(np.float64)
+            assert np.abs(grad - orc.grads[m]).max() <= (3e-3 if mixed else 2e-5) * max(np.abs(orc.grads[m]).max(), 1e-12)
+        assert rep.guard_intact()
+    finally:
+        rep.close()
