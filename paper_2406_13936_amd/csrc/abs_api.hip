@@ -189,6 +189,7 @@ struct abs_ctx {
   const int32_t *y = nullptr;
   long long N = 0;
   double *host_stats = nullptr;     // pinned, M*8 + 8 doubles
+  double *host_stats_dev = nullptr; // the same memory as the device sees it (the statistics kernel writes there)
   long long t = 0;                  // local steps taken (Adam bias correction)
   int last_b = 0;                 // largest local batch size of the last step
   std::vector<int> last_bm;       // per worker
@@ -278,9 +279,10 @@ void ceil_ratio(double num, double den, int b, double &ratio, long long &T) {
 
 abs_status read_stats(abs_ctx *c) {
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
-  HIPCHK(c, hipMemcpyAsync(c->host_stats, c->at<double>(c->pl.o_stats), (size_t)c->pl.M * 8 * sizeof(double),
-                           hipMemcpyDeviceToHost, c->stream));
-  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (!c->host_stats_dev)
+    HIPCHK(c, hipMemcpyAsync(c->host_stats, c->at<double>(c->pl.o_stats), (size_t)c->pl.M * 8 * sizeof(double),
+                             hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));      // the statistics kernel has written the pinned mirror itself
   return ABS_OK;
 }
 
@@ -356,8 +358,12 @@ abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const 
   c->X = X_dev; c->y = y_dev; c->N = N;
   const Plan &pl = c->pl;
   auto bail = [&](const std::string &m) { g_err = m; if (c->host_stats) (void)hipHostFree(c->host_stats); delete c; return ABS_EHIP; };
-  hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&c->host_stats), ((size_t)pl.M * 8 + 8) * sizeof(double), hipHostMallocDefault);
+  hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&c->host_stats), ((size_t)pl.M * 8 + 8) * sizeof(double), hipHostMallocMapped);
   if (e != hipSuccess) { c->host_stats = nullptr; return bail(std::string("hipHostMalloc: ") + hipGetErrorString(e)); }
+  std::memset(c->host_stats, 0, ((size_t)pl.M * 8 + 8) * sizeof(double));
+  void *hs_dev = nullptr;
+  if (hipHostGetDevicePointer(&hs_dev, c->host_stats, 0) == hipSuccess) c->host_stats_dev = static_cast<double *>(hs_dev);
+  else (void)hipGetLastError();                   // no mapping: read_stats copies instead
   // zero parameters, gradient and optimizer state (including their padding)
   const size_t MP = (size_t)pl.M * pl.Ppad;
   if ((e = launch_fill_zero(c->at<void>(pl.o_xm), MP * 4, c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
@@ -669,6 +675,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   if (ph.ps_off >= 0) { sp.n_out = c->at<float>(pl.o_nout) + ph.ps_off; sp.q_out = c->at<float>(pl.o_qout) + ph.ps_off; }
   sp.Ppad = pl.Ppad;
   sp.partials = c->at<double>(pl.o_partials); sp.stats = c->at<double>(pl.o_stats);
+  sp.stats_host = c->host_stats_dev;
   // When this call both finishes the gradient and updates, the update kernel gathers ||gbar||^2 on
   // its way through the gradient (none of the statistics depends on the parameters, so the update
   // may run first); otherwise a separate pass over the gradient does.

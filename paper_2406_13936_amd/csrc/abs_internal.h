@@ -119,6 +119,8 @@ struct StatsP {
   long long Ppad;
   double *partials;         // scratch: [groups][5][PBLK]
   double *stats;            // out: [groups][8] = S1, S2, S3, S4, loss, 0,0,0
+  double *stats_host;       // optional mirror in device-visible pinned host memory (same layout): the host then
+                            //   needs a stream synchronisation only, no copy
   const float *sq_wave;     // alternative source of S2 (grad must be null): per-wavefront sums of g^2 left by the
   long long n_sq_wave;      //   update kernel, n_sq_wave per group (one per 256 consecutive parameters)
   const int *rows;          // optional per-group sample counts (device) replacing b

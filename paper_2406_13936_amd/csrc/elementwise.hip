@@ -309,7 +309,8 @@ __global__ void __launch_bounds__(256) stats_gradsq_parts_kernel(const float *__
 // Stage 2 (grid: groups): add the PBLK partials of each of the five sums in index order.
 // sel / acc: bit k set = sum k is produced by this launch / is added to the stored value.
 __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restrict__ partials,
-                                                          double *__restrict__ stats, int sel, int acc) {
+                                                          double *__restrict__ stats, double *__restrict__ stats_host,
+                                                          int sel, int acc) {
   __shared__ double red[4];
   const int g = blockIdx.x;
   static_assert(STATS_PBLK == 256, "one partial per thread");
@@ -317,7 +318,11 @@ __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restri
     if (!((sel >> k) & 1)) continue;
     const double v = partials[((long long)g * 5 + k) * STATS_PBLK + threadIdx.x];
     const double r = block_sum<4>(v, red);
-    if (threadIdx.x == 0) stats[g * 8 + k] = ((acc >> k) & 1) ? stats[g * 8 + k] + r : r;
+    if (threadIdx.x == 0) {
+      const double v = ((acc >> k) & 1) ? stats[g * 8 + k] + r : r;
+      stats[g * 8 + k] = v;
+      if (stats_host) stats_host[g * 8 + k] = v;
+    }
   }
 }
 
@@ -624,7 +629,7 @@ hipError_t launch_stats(const StatsP &p, hipStream_t s) {
   if (p.sq_wave)
     hipLaunchKernelGGL(stats_gradsq_parts_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.sq_wave, p.n_sq_wave,
                        p.partials);
-  hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats, sel, acc);
+  hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats, p.stats_host, sel, acc);
   return hipGetLastError();
 }
 
