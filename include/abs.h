@@ -245,8 +245,11 @@ abs_status abs_layer_stats_workspace_bytes(int L, const int *in_dims, const int 
                                            int M, int b, size_t *bytes);
 
 /* Mean over M replicas of a bf16 parameter block, written back to all M (fp32 sum in
- * replica order, one rounding):  params_dev : device, bf16 [M x n]; n multiple of 8. */
-abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *hip_stream);
+ * replica order, one rounding):  params_dev : device, bf16 [M x n]; n multiple of 8.
+ * scratch_dev : device, n bf16 values, 16-byte aligned, caller-owned, or NULL.  With a scratch buffer a
+ * large block is averaged in two passes (read all replicas, then write all replicas); the result is the
+ * same bit for bit, HBM serves the two pure streams faster than their mixture. */
+abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *scratch_dev, void *hip_stream);
 
 /*
  * Per-kernel timing (measurement aid; not part of the method).  While enabled, every kernel

@@ -93,7 +93,7 @@ def load_library(reload: bool = False):
                                     C.c_void_p, C.c_void_p]
     lib.abs_layer_stats_workspace_bytes.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int),
                                                     C.c_int, C.c_int, C.POINTER(C.c_size_t)]
-    lib.abs_average_bf16.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
+    lib.abs_average_bf16.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p]
     lib.abs_destroy.argtypes = [C.c_void_p]
     lib.abs_lr_schedule.argtypes = [C.c_longlong, C.c_longlong, C.c_longlong, C.c_double, C.c_double,
                                     C.POINTER(C.c_double)]
@@ -361,8 +361,12 @@ def copy_probe(src, dst):
     _check(lib.abs_copy_probe(src.data_ptr(), dst.data_ptr(), nbytes, _stream_ptr()))
 
 
-def average_bf16(params):
-    """In-place mean over dim 0 of a contiguous bf16 device tensor [M, n]."""
+def average_bf16(params, scratch=None):
+    """In-place mean over dim 0 of a contiguous bf16 device tensor [M, n]; `scratch` (bf16, n elements,
+    optional) lets a large block be averaged in two passes."""
     lib = load_library()
     M, n = int(params.shape[0]), int(params[0].numel())
-    _check(lib.abs_average_bf16(params.data_ptr(), M, n, _stream_ptr()))
+    if scratch is not None:
+        assert scratch.is_contiguous() and scratch.numel() >= n and scratch.element_size() == 2
+    _check(lib.abs_average_bf16(params.data_ptr(), M, n, scratch.data_ptr() if scratch is not None else None,
+                                _stream_ptr()))

@@ -37,7 +37,7 @@ struct Plan {
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
   size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
-  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_kpart = 0, o_idx = 0, o_scal = 0;
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_kpart = 0, o_idx = 0, o_scal = 0, o_mean = 0;
   size_t kpart_floats = 0;             // scratch for the partial products of a split weight-gradient reduction
   size_t total = 0;
 };
@@ -153,6 +153,7 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   pl.o_cw = take((2 * (size_t)cross_worker_blocks(pl.Ppad) + 8) * 8);
   pl.o_idx = take((size_t)pl.M * pl.cap * sizeof(int32_t));      // inputs of replayed (graph) steps
   pl.o_scal = take(256);
+  pl.o_mean = take((size_t)pl.Ppad * sizeof(float));          // the mean between the two passes of a large average
   pl.total = off;
 }
 
@@ -965,7 +966,8 @@ abs_status abs_average_replicas(abs_ctx *c) {
   const Plan &pl = c->pl;
   {
     ProfScope ps_(c, T_AVERAGE, 0.0, (double)pl.M * pl.P * (pl.bf16 ? 10.0 : 8.0));
-    HIPCHK(c, launch_average_f32(c->at<float>(pl.o_xm), pl.bf16 ? c->at<bf16_t>(pl.o_xs) : nullptr, pl.M, pl.Ppad, c->stream));
+    HIPCHK(c, launch_average_f32(c->at<float>(pl.o_xm), pl.bf16 ? c->at<bf16_t>(pl.o_xs) : nullptr, c->at<float>(pl.o_mean), pl.M, pl.Ppad,
+                                 c->stream));
   }
   return ABS_OK;
 }
@@ -1150,12 +1152,14 @@ abs_status abs_copy_probe(const void *src_dev, void *dst_dev, int64_t bytes, voi
   return ABS_OK;
 }
 
-abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *hip_stream) {
+abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *scratch_dev, void *hip_stream) {
   if (!params_dev) return fail(ABS_EINVAL, "params_dev is NULL");
   if (M < 1 || n < 8 || (n % 8)) return fail(ABS_EINVAL, "M < 1 or n not a positive multiple of 8");
-  if (reinterpret_cast<uintptr_t>(params_dev) & 15) return fail(ABS_EINVAL, "params_dev must be 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(params_dev) | reinterpret_cast<uintptr_t>(scratch_dev)) & 15)
+    return fail(ABS_EINVAL, "params_dev and scratch_dev must be 16-byte aligned");
   abs_ctx *nc = nullptr;
-  HIPCHK(nc, launch_average_bf16(static_cast<bf16_t *>(params_dev), M, n, static_cast<hipStream_t>(hip_stream)));
+  HIPCHK(nc, launch_average_bf16(static_cast<bf16_t *>(params_dev), static_cast<bf16_t *>(scratch_dev), M, n,
+                                 static_cast<hipStream_t>(hip_stream)));
   return ABS_OK;
 }
 

@@ -140,8 +140,8 @@ struct UpdateP {
                             //   that a captured launch can be replayed with new values
 };
 hipError_t launch_update(const UpdateP &p, hipStream_t s);
-hipError_t launch_average_f32(float *x, bf16_t *shadow, int groups, long long Ppad, hipStream_t s);
-hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s);
+hipError_t launch_average_f32(float *x, bf16_t *shadow, float *mean, int groups, long long Ppad, hipStream_t s);
+hipError_t launch_average_bf16(bf16_t *x, bf16_t *mean, int groups, long long n, hipStream_t s);
 // cross-worker statistics: out[0] = sum_m ||g^m||^2, out[1] = ||mean_m g^m||^2;
 // partials: 2 * cross_worker_blocks(Ppad) doubles of scratch
 int cross_worker_blocks(long long Ppad);

@@ -438,6 +438,64 @@ __global__ void __launch_bounds__(256) average_bf16_kernel(bf16_t *__restrict__ 
   }
 }
 
+// Two-pass form of the same averages for blocks far beyond the caches: the first kernel only reads
+// (all replicas, same order of additions, same division) and leaves the mean in a buffer of one replica's
+// size, the second only writes (its one read, the mean, comes from the caches).  HBM serves a pure read
+// stream and a pure write stream faster than their mixture, which more than pays for the extra buffer.
+__global__ void __launch_bounds__(256) average_f32_reduce_kernel(const float *__restrict__ x, float *__restrict__ mean,
+                                                                 int groups, long long Ppad) {
+  const long long i = blockIdx.x * 256LL + threadIdx.x;
+  if (i >= Ppad / 4) return;
+  const float Mf = (float)groups;
+  float4 s = ld_stream(reinterpret_cast<const float4 *>(x) + i);
+  for (int g = 1; g < groups; ++g) {
+    const float4 v = ld_stream(reinterpret_cast<const float4 *>(x + (long long)g * Ppad) + i);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  s.x /= Mf; s.y /= Mf; s.z /= Mf; s.w /= Mf;
+  reinterpret_cast<float4 *>(mean)[i] = s;
+}
+template <bool SHADOW>
+__global__ void __launch_bounds__(256) average_f32_spread_kernel(const float *__restrict__ mean, float *__restrict__ x,
+                                                                 bf16_t *__restrict__ shadow, int groups, long long Ppad) {
+  const long long i = blockIdx.x * 256LL + threadIdx.x;
+  if (i >= Ppad / 4) return;
+  const float4 s = reinterpret_cast<const float4 *>(mean)[i];
+  uint2 o;
+  if (SHADOW) { o.x = pack2bf(s.x, s.y); o.y = pack2bf(s.z, s.w); }
+  for (int g = 0; g < groups; ++g) {
+    st_stream(reinterpret_cast<float4 *>(x + (long long)g * Ppad) + i, s);
+    if (SHADOW) st_stream(reinterpret_cast<uint2 *>(shadow + (long long)g * Ppad) + i, o);
+  }
+}
+__global__ void __launch_bounds__(256) average_bf16_reduce_kernel(const bf16_t *__restrict__ x, bf16_t *__restrict__ mean,
+                                                                  int groups, long long n) {
+  const long long i = blockIdx.x * 256LL + threadIdx.x;
+  if (i >= n / 8) return;
+  const float Mf = (float)groups;
+  float s[8];
+  Vec<bf16_t>::load_stream(x + i * 8, s);
+  for (int g = 1; g < groups; ++g) {
+    float v[8];
+    Vec<bf16_t>::load_stream(x + (long long)g * n + i * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s[k] += v[k];
+  }
+  uint4 o;
+  o.x = pack2bf(s[0] / Mf, s[1] / Mf);
+  o.y = pack2bf(s[2] / Mf, s[3] / Mf);
+  o.z = pack2bf(s[4] / Mf, s[5] / Mf);
+  o.w = pack2bf(s[6] / Mf, s[7] / Mf);
+  reinterpret_cast<uint4 *>(mean)[i] = o;
+}
+__global__ void __launch_bounds__(256) average_bf16_spread_kernel(const bf16_t *__restrict__ mean, bf16_t *__restrict__ x,
+                                                                  int groups, long long n) {
+  const long long i = blockIdx.x * 256LL + threadIdx.x;
+  if (i >= n / 8) return;
+  const uint4 o = reinterpret_cast<const uint4 *>(mean)[i];
+  for (int g = 0; g < groups; ++g) st_stream(reinterpret_cast<uint4 *>(x + (long long)g * n + i * 8), o);
+}
+
 // sum_m ||g^m||^2 and ||mean_m g^m||^2 over the padded gradient block (Alg. 2 statistics).
 // Stage 1 (data-sized grid): a thread owns four consecutive parameters, reads them from every worker's
 // gradient (in worker order) and adds its two contributions; one pair of partials per block.
@@ -653,15 +711,30 @@ hipError_t launch_update(const UpdateP &p, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_average_f32(float *x, bf16_t *shadow, int groups, long long Ppad, hipStream_t s) {
+// Blocks of at least this many elements over all replicas take the two-pass form when the caller brings a buffer.
+static constexpr long long AVERAGE_TWO_PASS_MIN = 32LL << 20;
+
+hipError_t launch_average_f32(float *x, bf16_t *shadow, float *mean, int groups, long long Ppad, hipStream_t s) {
   const dim3 grid(grid_for(Ppad / 4, 256, 1 << 30)), blk(256);
+  if (mean && groups > 1 && (long long)groups * Ppad >= AVERAGE_TWO_PASS_MIN) {
+    hipLaunchKernelGGL(average_f32_reduce_kernel, grid, blk, 0, s, x, mean, groups, Ppad);
+    if (shadow) hipLaunchKernelGGL(average_f32_spread_kernel<true>, grid, blk, 0, s, mean, x, shadow, groups, Ppad);
+    else hipLaunchKernelGGL(average_f32_spread_kernel<false>, grid, blk, 0, s, mean, x, shadow, groups, Ppad);
+    return hipGetLastError();
+  }
   if (shadow) hipLaunchKernelGGL(average_f32_kernel<true>, grid, blk, 0, s, x, shadow, groups, Ppad);
   else hipLaunchKernelGGL(average_f32_kernel<false>, grid, blk, 0, s, x, shadow, groups, Ppad);
   return hipGetLastError();
 }
 
-hipError_t launch_average_bf16(bf16_t *x, int groups, long long n, hipStream_t s) {
-  hipLaunchKernelGGL(average_bf16_kernel, dim3(grid_for(n / 8, 256, 1 << 30)), dim3(256), 0, s, x, groups, n);
+hipError_t launch_average_bf16(bf16_t *x, bf16_t *mean, int groups, long long n, hipStream_t s) {
+  const dim3 grid(grid_for(n / 8, 256, 1 << 30)), blk(256);
+  if (mean && groups > 1 && (long long)groups * n >= AVERAGE_TWO_PASS_MIN) {
+    hipLaunchKernelGGL(average_bf16_reduce_kernel, grid, blk, 0, s, x, mean, groups, n);
+    hipLaunchKernelGGL(average_bf16_spread_kernel, grid, blk, 0, s, mean, x, groups, n);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(average_bf16_kernel, grid, blk, 0, s, x, groups, n);
   return hipGetLastError();
 }
 

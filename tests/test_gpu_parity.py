@@ -796,6 +796,25 @@ def test_statistics_alone_on_wide_layers_large_tiles():
         assert (got[m] != want).mean() < 2e-3 and np.abs(got[m] - want).max() <= 2 ** -7 * np.abs(want).max()
 
 
+def test_two_pass_average_is_bitwise_the_one_pass_average():
+    """A bf16 block large enough for the two-pass form (read all replicas into a mean buffer, then write
+    all replicas): same additions in the same order, so the result equals the one-pass kernel's bit for bit."""
+    import torch
+    A = _A()
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    M, n = 8, (4 << 20) + 8 * 37                      # beyond the switch-over, ragged against the block size
+    p1 = (torch.randn((M, n), generator=gen, device="cuda", dtype=torch.float32) / 8).to(torch.bfloat16)
+    p2 = p1.clone()
+    scratch = torch.full((n,), float("nan"), device="cuda", dtype=torch.bfloat16)
+    A.average_bf16(p1)
+    A.average_bf16(p2, scratch)
+    torch.cuda.synchronize()
+    assert torch.equal(p1.view(torch.int16), p2.view(torch.int16))
+    assert torch.equal(p2[0].view(torch.int16), scratch.view(torch.int16))
+    ref = p1[0].float().cpu().numpy()
+    assert np.isfinite(ref).all() and ref.std() > 0.01
+
+
 def test_statistics_stress_full_size_sampled_replicas():
     """The statistics-only workload at its full size (32 replicas x 4 stacked 4096x4096 layers, b = 8192):
     two replicas, drawn from the seeded host generator, are recomputed by the oracle's definitions in fp64;
@@ -839,7 +858,8 @@ def test_statistics_stress_full_size_sampled_replicas():
     params = (torch.randn((M, P), generator=gen, device=dev, dtype=torch.float32) / 64).to(torch.bfloat16)
     ranges = [(0, 1 << 20), (P // 2 + 12345 // 8 * 8, P // 2 + 12345 // 8 * 8 + (1 << 20)), (P - (1 << 20), P)]
     before = [params[:, s0:s1].float().cpu().numpy().astype(np.float64) for s0, s1 in ranges]
-    A.average_bf16(params)
+    scratch = torch.empty(P, device=dev, dtype=torch.bfloat16)
+    A.average_bf16(params, scratch)          # two passes, as bench.py runs it
     torch.cuda.synchronize()
     for (s0, s1), ref in zip(ranges, before):
         want = O.bf16_round(ref.sum(axis=0) / M)
