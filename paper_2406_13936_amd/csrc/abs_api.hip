@@ -143,7 +143,7 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   pl.o_rows = take((size_t)2 * pl.M * sizeof(int));          // per-group row counts, then the launch order
   pl.o_sqwave = take((size_t)pl.M * (pl.Ppad / 256) * sizeof(float));
   if (pl.bf16) {
-    // a split is only taken when the un-split launch has fewer than 192 tiles, and never makes more than
+    // a split is only taken when the un-split launch has at most 256 tiles, and never makes more than
     // 512 (tile, slice) pairs of at most 128 x 128 or 256 x 256 outputs each
     size_t mx = 0;
     for (int l = 1; l <= pl.L; ++l) mx = std::max(mx, (size_t)pl.dims[l] * pl.dims[l - 1]);
@@ -155,6 +155,31 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   pl.o_scal = take(256);
   pl.o_mean = take((size_t)pl.Ppad * sizeof(float));          // the mean between the two passes of a large average
   pl.total = off;
+}
+
+// Number of slices for the reduction of a weight-gradient launch with `tiles` output tiles of shape `shape`
+// and `KT` k-tiles of 64, from a small cost model in microseconds fitted to measured launches (256..1024-wide
+// layers, b = 256..4096): a 128-wide tile takes 0.9 us per k-tile alone on a CU and 1.1 us when two work-groups
+// share it (launches of more than 256 blocks), a 256 x 256 tile 2.0 us; the partial products are written and
+// read once (8 bytes per slice and output at about 4.5 TB/s) and the finishing launch costs 10 us inside a
+// step (a dependent launch more on the stream).  The split
+// pays for few tiles and long reductions only: at b <= 1024 the un-split launch wins for every layer measured.
+int choose_ksplit(int shape, long long tiles, int KT, double outputs, size_t kpart_floats) {
+  if (tiles < 1 || tiles > 256) return 1;
+  int best = 1;
+  double best_cost = 0.0;
+  for (int S = 1; S <= 8; ++S) {
+    if (S > 1 && ((double)S * outputs > (double)kpart_floats || (KT + S - 1) / S < 4)) break;
+    const long long blocks = tiles * S;
+    const int kt = (KT + S - 1) / S;
+    double cost;
+    if (shape == 2) cost = (double)((blocks + 255) / 256) * kt * 2.0;
+    else if (blocks <= 256) cost = kt * 0.9;
+    else cost = (double)((blocks + 511) / 512) * kt * 1.1;
+    if (S > 1) cost += 10.0 + (double)S * outputs * 8.0 / 4.5e6;
+    if (S == 1 || cost < best_cost) { best = S; best_cost = cost; }
+  }
+  return best;
 }
 
 }  // namespace
@@ -607,12 +632,11 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         const int sh = gemm_bf16_tile_shape(p.Md, p.Nd, M);
         const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
         const long long tiles = (long long)((p.Md + te - 1) / te) * ((p.Nd + tn_e - 1) / tn_e) * M;
-        const int KT = (b + 63) / 64;
-        long long S = std::min<long long>(std::min<long long>(8, 512 / std::max<long long>(tiles, 1)), KT / 4);
-        while (S > 1 && (size_t)S * M * p.Md * p.Nd > pl.kpart_floats) --S;
-        if (tiles < 192 && S > 1) {
-          p.ksplit = (int)S;
-          p.kchunk = (int)(((KT + S - 1) / S) * 64);
+        const int S = choose_ksplit(sh, tiles, (b + 63) / 64, (double)M * p.Md * p.Nd, pl.kpart_floats);
+        if (S > 1) {
+          const int KT = (b + 63) / 64;
+          p.ksplit = S;
+          p.kchunk = ((KT + S - 1) / S) * 64;
           p.kpart = c->at<float>(pl.o_kpart);
         }
       }

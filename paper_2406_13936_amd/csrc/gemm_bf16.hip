@@ -650,11 +650,16 @@ hipError_t launch_shape(const GemmP &p, hipStream_t s) {
   switch (gemm_bf16_tile_shape(p.Md, p.Nd, p.groups)) {
     case 0: return launch_cfg<128, 64, 64, 4, 1, 3, AT, BT, EPI, ACT>(p, s);
     case 2: return launch_cfg<256, 256, 64, 2, 4, 2, AT, BT, EPI, ACT>(p, s);
-    default:
-      // short reductions: two stages (64 KB) so that two work-groups share a CU; long ones (few tiles,
-      // one work-group per CU anyway): three stages
-      if (p.Kd <= 1024) return launch_cfg<128, 128, 64, 2, 2, 2, AT, BT, EPI, ACT>(p, s);
+    default: {
+      // Two stages (64 KB) let two work-groups share a CU, three keep one work-group fed through a long
+      // reduction.  Two when the reduction is short, and for a weight gradient whose launch has more blocks
+      // than CUs (a split reduction, usually); three otherwise.
+      long long nblk = 0;
+      if (EPI == EPI_WGRAD)
+        nblk = (long long)((p.Md + 127) / 128) * ((p.Nd + 127) / 128) * p.groups * (p.ksplit > 1 ? p.ksplit : 1);
+      if (p.Kd <= 1024 || nblk > 256) return launch_cfg<128, 128, 64, 2, 2, 2, AT, BT, EPI, ACT>(p, s);
       return launch_cfg<128, 128, 64, 2, 2, 3, AT, BT, EPI, ACT>(p, s);
+    }
   }
 }
 

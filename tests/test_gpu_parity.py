@@ -370,6 +370,9 @@ def _ragged_rows(w, bs):
     # nine workers: the launch walks them in an order that balances the rows over the XCDs
     (W.PREC_BF16, (136, 264, 100), W.ACT_GELU, [40, 300, 7, 129, 2, 517, 64, 260, 33], W.OPT_SGD, True),
     (W.PREC_BF16, (1024, 1024, 100), W.ACT_RELU, [1100, 300, 1024, 129, 2, 517, 64, 260, 33, 900], W.OPT_SHB, True),
+    # batches long enough for the weight gradients to split their reduction into slices: workers whose rows end
+    # inside the first slice, on a slice boundary (a multiple of 64) and inside later slices
+    (W.PREC_BF16, (136, 264, 100), W.ACT_GELU, [2300, 300, 1152, 2, 1153, 2049], W.OPT_SHB, True),
 ])
 def test_ragged_step_matches_oracle(prec, dims, act, bs, opt, hb):
     A = _A()
@@ -490,6 +493,8 @@ def test_per_worker_schedule_lockstep_fp32():
     (W.PREC_BF16, (384, 256, 256, 100), W.ACT_GELU, 700, 256, 256, W.OPT_ADAMW, W.TEST_AUG_IP),
     (W.PREC_BF16, (784, 512, 512, 10), W.ACT_RELU, 300, 128, 300, W.OPT_SGD, W.TEST_NORM),
     (W.PREC_BF16, (1024, 1024, 1024, 100), W.ACT_RELU, 2124, 1024, 1024, W.OPT_SHB, W.TEST_IP),   # 256x256 tiles
+    # micro-batches long enough for sliced weight-gradient reductions that accumulate
+    (W.PREC_BF16, (136, 264, 72, 100), W.ACT_GELU, 4300, 2048, 2048, W.OPT_SGD, W.TEST_IP),
 ])
 def test_accumulated_step_matches_full_batch_oracle(prec, dims, act, b, micro, cap, opt, test):
     A = _A()
