@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <vector>
@@ -229,6 +230,15 @@ struct abs_ctx {
   std::string err;
 
   template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
+
+  abs_ctx() = default;
+  abs_ctx(const abs_ctx &) = delete;
+  abs_ctx &operator=(const abs_ctx &) = delete;
+  ~abs_ctx() {                      // the library owns the pinned mirror, the event pool and the graphs
+    if (host_stats) (void)hipHostFree(host_stats);
+    for (ProfRec &r : prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+    for (auto &g : graphs) (void)hipGraphExecDestroy(g.exec);
+  }
 };
 
 namespace {
@@ -312,21 +322,34 @@ abs_status read_stats(abs_ctx *c) {
   return ABS_OK;
 }
 
+// No exception leaves the library: host allocations (vectors, strings) are the only throwing operations.
+abs_status on_exception() noexcept {
+  try { throw; }
+  catch (const std::bad_alloc &) {
+    try { g_err = "out of host memory"; } catch (...) {}
+    return ABS_ENOMEM;
+  }
+  catch (...) {
+    try { g_err = "internal error"; } catch (...) {}
+    return ABS_EHIP;
+  }
+}
+
 }  // namespace
 
 extern "C" {
 
 const char *abs_last_error(const abs_ctx *ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
 
-abs_status abs_lr_linear_scaling(double lr_ref, int64_t b, int64_t b_ref, double *lr) {
+abs_status abs_lr_linear_scaling(double lr_ref, int64_t b, int64_t b_ref, double *lr) try {
   if (!lr) return fail(ABS_EINVAL, "lr is NULL");
   if (b < 1 || b_ref < 1) return fail(ABS_EINVAL, "batch sizes must be positive");
   *lr = lr_ref * (double)b / (double)b_ref;
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
 abs_status abs_lr_schedule(long long step, long long total_steps, long long warmup_steps, double peak, double floor,
-                           double *lr) {
+                           double *lr) try {
   if (!lr) return fail(ABS_EINVAL, "lr is NULL");
   if (step < 0 || total_steps < 1 || warmup_steps < 0 || warmup_steps > total_steps)
     return fail(ABS_EINVAL, "need 0 <= step, 0 <= warmup_steps <= total_steps, total_steps >= 1");
@@ -338,9 +361,9 @@ abs_status abs_lr_schedule(long long step, long long total_steps, long long warm
     *lr = floor + 0.5 * (peak - floor) * (1.0 + std::cos(kPi * (double)(step - warmup_steps) / (double)span));
   }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_n_params(const abs_config *cfg, int64_t *n) {
+abs_status abs_n_params(const abs_config *cfg, int64_t *n) try {
   if (!n) return fail(ABS_EINVAL, "n is NULL");
   abs_status st = check_cfg(cfg);
   if (st != ABS_OK) return st;
@@ -348,9 +371,9 @@ abs_status abs_n_params(const abs_config *cfg, int64_t *n) {
   make_plan(cfg, 0, pl);
   *n = pl.P;
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_workspace_bytes(const abs_config *cfg, int64_t N, size_t *bytes) {
+abs_status abs_workspace_bytes(const abs_config *cfg, int64_t N, size_t *bytes) try {
   if (!bytes) return fail(ABS_EINVAL, "bytes is NULL");
   if (N < 1) return fail(ABS_EINVAL, "N < 1");
   abs_status st = check_cfg(cfg);
@@ -359,10 +382,10 @@ abs_status abs_workspace_bytes(const abs_config *cfg, int64_t N, size_t *bytes) 
   make_plan(cfg, N, pl);
   *bytes = pl.total;
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
 abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const float *X_dev,
-                             const int32_t *y_dev, int64_t N, abs_ctx **out) {
+                             const int32_t *y_dev, int64_t N, abs_ctx **out) try {
   if (!out || !x0_host || !X_dev || !y_dev) return fail(ABS_EINVAL, "NULL argument");
   if (N < 1 || N > 0x7fffffffLL) return fail(ABS_EINVAL, "N out of range");
   abs_status st = check_cfg(cfg);
@@ -370,20 +393,18 @@ abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const 
   if (!cfg->workspace || (reinterpret_cast<uintptr_t>(cfg->workspace) & 255))
     return fail(ABS_EINVAL, "workspace must be a 256-byte aligned device pointer");
   if ((reinterpret_cast<uintptr_t>(X_dev) & 15)) return fail(ABS_EINVAL, "X_dev must be 16-byte aligned");
-  abs_ctx *c = new (std::nothrow) abs_ctx();
+  std::unique_ptr<abs_ctx> owner(new (std::nothrow) abs_ctx());
+  abs_ctx *c = owner.get();
   if (!c) return fail(ABS_ENOMEM, "host allocation failed");
   make_plan(cfg, N, c->pl);
-  if (cfg->workspace_bytes < c->pl.total) {
-    delete c;
-    return fail(ABS_ENOMEM, "workspace too small (see abs_workspace_bytes)");
-  }
+  if (cfg->workspace_bytes < c->pl.total) return fail(ABS_ENOMEM, "workspace too small (see abs_workspace_bytes)");
   c->cfg = *cfg;
   c->cfg.dims = c->pl.dims.data();
   c->stream = static_cast<hipStream_t>(cfg->hip_stream);
   c->ws = static_cast<unsigned char *>(cfg->workspace);
   c->X = X_dev; c->y = y_dev; c->N = N;
   const Plan &pl = c->pl;
-  auto bail = [&](const std::string &m) { g_err = m; if (c->host_stats) (void)hipHostFree(c->host_stats); delete c; return ABS_EHIP; };
+  auto bail = [&](const std::string &m) { g_err = m; return ABS_EHIP; };      // `owner` frees what was acquired
   hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&c->host_stats), ((size_t)pl.M * 8 + 8) * sizeof(double), hipHostMallocMapped);
   if (e != hipSuccess) { c->host_stats = nullptr; return bail(std::string("hipHostMalloc: ") + hipGetErrorString(e)); }
   std::memset(c->host_stats, 0, ((size_t)pl.M * 8 + 8) * sizeof(double));
@@ -411,36 +432,33 @@ abs_status abs_init_replicas(const abs_config *cfg, const float *x0_host, const 
     if ((e = launch_convert_f32_to_bf16(X_dev, c->at<bf16_t>(pl.o_Xbf), (long long)N * pl.dims[0], c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
   }
   if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return bail(hipGetErrorString(e));
-  *out = c;
+  *out = owner.release();
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_destroy(abs_ctx *c) {
+abs_status abs_destroy(abs_ctx *c) try {
   if (!c) return ABS_OK;
   (void)hipStreamSynchronize(c->stream);
-  if (c->host_stats) (void)hipHostFree(c->host_stats);
-  for (ProfRec &r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
-  for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.exec);
   delete c;
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_profile_enable(abs_ctx *c, int on) {
+abs_status abs_profile_enable(abs_ctx *c, int on) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   HIPCHK(c, hipStreamSynchronize(c->stream));
   c->prof_on = on != 0;
   c->prof_used = 0;
   for (int t = 0; t < T_COUNT; ++t) { c->prof_ms[t] = c->prof_flops[t] = c->prof_bytes[t] = 0.0; c->prof_calls[t] = 0; }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_profile_pause(abs_ctx *c, int paused) {
+abs_status abs_profile_pause(abs_ctx *c, int paused) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   c->prof_on = paused == 0;       // no synchronisation, totals and pending records are kept
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out, int *n_entries) {
+abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out, int *n_entries) try {
   if (!c || !out || !n_entries) return fail(ABS_EINVAL, "NULL argument");
   HIPCHK(c, hipStreamSynchronize(c->stream));
   for (size_t i = 0; i < c->prof_used; ++i) {
@@ -463,7 +481,7 @@ abs_status abs_profile_read(abs_ctx *c, int max_entries, abs_profile_entry *out,
   }
   *n_entries = n;
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
 // One local step.  b is the largest local batch size; with b_host (M entries, each in [2, b]) the
 // workers' batches are ragged: worker m uses the first b_host[m] entries of row m of idx (row
@@ -734,6 +752,12 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   return ABS_OK;
 }
 
+// A step that failed before its update was enqueued has not advanced the optimizer.
+static abs_status settle_update(abs_ctx *c, abs_status st) {
+  if (st != ABS_OK) c->t -= 1;
+  return st;
+}
+
 // One more optimizer step is about to be taken: advance the counter and return Adam's bias corrections.
 static void next_update(abs_ctx *c, StepPhase &ph) {
   c->t += 1;
@@ -743,17 +767,17 @@ static void next_update(abs_ctx *c, StepPhase &ph) {
   }
 }
 
-abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
+abs_status abs_local_step(abs_ctx *c, const int32_t *idx_dev, int b, float lr) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
   if (b < 2 || b > c->pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
   StepPhase ph;
   next_update(c, ph);
-  return local_step_impl(c, idx_dev, b, b, nullptr, lr, ph);
-}
+  return settle_update(c, local_step_impl(c, idx_dev, b, b, nullptr, lr, ph));
+} catch (...) { return on_exception(); }
 
-abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, float lr) {
+abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, float lr) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
   if (b < 2 || b > c->pl.cap) return cfail(c, ABS_EINVAL, "b must be in [2, b_cap]");
@@ -802,15 +826,15 @@ abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, flo
   HIPCHK(c, hipGraphLaunch(slot->exec, c->stream));
   note_step(c, b, nullptr);
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_graph_count(const abs_ctx *c, int *n) {
+abs_status abs_graph_count(const abs_ctx *c, int *n) try {
   if (!c || !n) return fail(ABS_EINVAL, "NULL argument");
   *n = (int)c->graphs.size();
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b, int micro_b, float lr) {
+abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b, int micro_b, float lr) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
@@ -848,7 +872,7 @@ abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b,
   up.passes = up.wgrad = up.nstats = up.s2 = up.ip = false;
   up.b_total = b;
   next_update(c, up);
-  abs_status st = local_step_impl(c, idx_dev, b, micro_b, nullptr, lr, up);
+  abs_status st = settle_update(c, local_step_impl(c, idx_dev, b, micro_b, nullptr, lr, up));
   if (st != ABS_OK) return st;
   c->last_ps = 0;
   for (int j = 0; j < nmb; ++j) {
@@ -856,9 +880,9 @@ abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b,
     if (off + mb <= cap) c->last_ps = off + mb;
   }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_local_step_ragged(abs_ctx *c, const int32_t *idx_dev, int ldi, const int *b_host, float lr) {
+abs_status abs_local_step_ragged(abs_ctx *c, const int32_t *idx_dev, int ldi, const int *b_host, float lr) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (!idx_dev || !b_host) return cfail(c, ABS_EINVAL, "idx_dev or b_host is NULL");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
@@ -870,8 +894,8 @@ abs_status abs_local_step_ragged(abs_ctx *c, const int32_t *idx_dev, int ldi, co
   if (ldi < bmax) return cfail(c, ABS_EINVAL, "ldi must be >= max_m b[m]");
   StepPhase ph;
   next_update(c, ph);
-  return local_step_impl(c, idx_dev, ldi, bmax, b_host, lr, ph);
-}
+  return settle_update(c, local_step_impl(c, idx_dev, ldi, bmax, b_host, lr, ph));
+} catch (...) { return on_exception(); }
 
 static abs_status norm_test_impl(abs_ctx *c, const double *eta_m, double eta_all, int64_t n_total,
                                  abs_test_result *out) {
@@ -900,21 +924,21 @@ static abs_status norm_test_impl(abs_ctx *c, const double *eta_m, double eta_all
   return ABS_OK;
 }
 
-abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) {
+abs_status abs_norm_test(abs_ctx *c, double eta, abs_test_result *out) try {
   return norm_test_impl(c, nullptr, eta, 0, out);
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_norm_test_per_worker(abs_ctx *c, const double *eta, abs_test_result *out) {
+abs_status abs_norm_test_per_worker(abs_ctx *c, const double *eta, abs_test_result *out) try {
   if (!eta) return c ? cfail(c, ABS_EINVAL, "eta is NULL") : fail(ABS_EINVAL, "NULL argument");
   return norm_test_impl(c, eta, 0.0, 0, out);
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_norm_test_fpc(abs_ctx *c, double eta, int64_t n_total, abs_test_result *out) {
+abs_status abs_norm_test_fpc(abs_ctx *c, double eta, int64_t n_total, abs_test_result *out) try {
   if (n_total < 2) return c ? cfail(c, ABS_EINVAL, "n_total must be >= max(2, b)") : fail(ABS_EINVAL, "NULL argument");
   return norm_test_impl(c, nullptr, eta, n_total, out);
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_inner_product_test(abs_ctx *c, double theta, double nu, abs_test_result *out) {
+abs_status abs_inner_product_test(abs_ctx *c, double theta, double nu, abs_test_result *out) try {
   if (!c || !out) return fail(ABS_EINVAL, "NULL argument");
   if (!(theta > 0.0)) return cfail(c, ABS_EINVAL, "theta must be positive");
   if (!c->pl.want_ip) return cfail(c, ABS_ESTATE, "stats_mask lacks ABS_STATS_IP");
@@ -941,9 +965,9 @@ abs_status abs_inner_product_test(abs_ctx *c, double theta, double nu, abs_test_
     out[m] = r;
   }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_cross_worker_test(abs_ctx *c, double eta, abs_test_result *out) {
+abs_status abs_cross_worker_test(abs_ctx *c, double eta, abs_test_result *out) try {
   if (!c || !out) return fail(ABS_EINVAL, "NULL argument");
   if (!(eta > 0.0 && eta < 1.0)) return cfail(c, ABS_EINVAL, "eta must be in (0,1)");
   if (c->pl.M < 2) return cfail(c, ABS_EINVAL, "the cross-worker estimator needs M >= 2");
@@ -966,10 +990,10 @@ abs_status abs_cross_worker_test(abs_ctx *c, double eta, abs_test_result *out) {
   r.pass = (r.lhs <= r.rhs) ? 1 : 0;
   *out = r;
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
 abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_cur, int b_cap, int sync_max,
-                               int *b_next) {
+                               int *b_next) try {
   if (!res || !b_cur || !b_next) return fail(ABS_EINVAL, "NULL argument");
   if (M < 1 || b_cap < 1) return fail(ABS_EINVAL, "M or b_cap out of range");
   long long mx = 0;
@@ -983,9 +1007,9 @@ abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_c
     b_next[m] = (int)(v > b_cap ? b_cap : v);
   }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_average_replicas(abs_ctx *c) {
+abs_status abs_average_replicas(abs_ctx *c) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   const Plan &pl = c->pl;
   {
@@ -994,9 +1018,9 @@ abs_status abs_average_replicas(abs_ctx *c) {
                                  c->stream));
   }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_get_params(abs_ctx *c, int m, float *out_host) {
+abs_status abs_get_params(abs_ctx *c, int m, float *out_host) try {
   if (!c || !out_host) return fail(ABS_EINVAL, "NULL argument");
   if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
   std::vector<float> in(c->pl.Ppad);
@@ -1004,9 +1028,9 @@ abs_status abs_get_params(abs_ctx *c, int m, float *out_host) {
   HIPCHK(c, hipMemcpy(in.data(), c->at<float>(c->pl.o_xm) + (size_t)m * c->pl.Ppad, c->pl.Ppad * sizeof(float), hipMemcpyDeviceToHost));
   to_external(c->pl, c->cfg.has_bias != 0, in.data(), out_host);
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_get_grad(abs_ctx *c, int m, float *out_host) {
+abs_status abs_get_grad(abs_ctx *c, int m, float *out_host) try {
   if (!c || !out_host) return fail(ABS_EINVAL, "NULL argument");
   if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
@@ -1015,9 +1039,9 @@ abs_status abs_get_grad(abs_ctx *c, int m, float *out_host) {
   HIPCHK(c, hipMemcpy(in.data(), c->at<float>(c->pl.o_grad) + (size_t)m * c->pl.Ppad, c->pl.Ppad * sizeof(float), hipMemcpyDeviceToHost));
   to_external(c->pl, c->cfg.has_bias != 0, in.data(), out_host);
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_set_params(abs_ctx *c, int m, const float *in_host) {
+abs_status abs_set_params(abs_ctx *c, int m, const float *in_host) try {
   if (!c || !in_host) return fail(ABS_EINVAL, "NULL argument");
   if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
   const Plan &pl = c->pl;
@@ -1030,9 +1054,9 @@ abs_status abs_set_params(abs_ctx *c, int m, const float *in_host) {
     HIPCHK(c, hipStreamSynchronize(c->stream));
   }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_get_per_sample(abs_ctx *c, int m, float *n_host, float *q_host) {
+abs_status abs_get_per_sample(abs_ctx *c, int m, float *n_host, float *q_host) try {
   if (!c || !n_host) return fail(ABS_EINVAL, "NULL argument");
   if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
@@ -1042,7 +1066,7 @@ abs_status abs_get_per_sample(abs_ctx *c, int m, float *n_host, float *q_host) {
   if (q_host)
     HIPCHK(c, hipMemcpy(q_host, c->at<float>(c->pl.o_qout) + (size_t)m * c->pl.cap, (size_t)(c->last_ps >= 0 ? c->last_ps : c->last_bm[m]) * sizeof(float), hipMemcpyDeviceToHost));
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
 // ---- statistics and averaging alone ---------------------------------------------------------
 
@@ -1077,18 +1101,18 @@ static abs_status ls_plan(int L, const int *in_dims, const int *out_dims, int M,
 }
 
 abs_status abs_layer_stats_workspace_bytes(int L, const int *in_dims, const int *out_dims, int M, int b,
-                                           size_t *bytes) {
+                                           size_t *bytes) try {
   if (!bytes) return fail(ABS_EINVAL, "bytes is NULL");
   std::vector<size_t> off; std::vector<long long> woff; long long Wtot; size_t total;
   abs_status st = ls_plan(L, in_dims, out_dims, M, b, off, woff, Wtot, total);
   if (st != ABS_OK) return st;
   *bytes = total;
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
 abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M, int b, const void *const *a_dev,
                            const void *const *delta_dev, void *workspace, size_t workspace_bytes, void *hip_stream,
-                           abs_test_result *out, float *n_out_dev, float *q_out_dev, float *gbar_out_dev) {
+                           abs_test_result *out, float *n_out_dev, float *q_out_dev, float *gbar_out_dev) try {
   if (!a_dev || !delta_dev || !workspace || !out) return fail(ABS_EINVAL, "NULL argument");
   std::vector<size_t> off; std::vector<long long> woff; long long Wtot; size_t total;
   abs_status st = ls_plan(L, in_dims, out_dims, M, b, off, woff, Wtot, total);
@@ -1165,18 +1189,18 @@ abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M
     out[m] = r;
   }
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_copy_probe(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream) {
+abs_status abs_copy_probe(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream) try {
   if (!src_dev || !dst_dev) return fail(ABS_EINVAL, "NULL argument");
   if (bytes < 16 || (bytes % 16) || ((reinterpret_cast<uintptr_t>(src_dev) | reinterpret_cast<uintptr_t>(dst_dev)) & 15))
     return fail(ABS_EINVAL, "bytes must be a positive multiple of 16 and the pointers 16-byte aligned");
   abs_ctx *nc = nullptr;
   HIPCHK(nc, launch_copy_probe(src_dev, dst_dev, bytes, static_cast<hipStream_t>(hip_stream)));
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
-abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *scratch_dev, void *hip_stream) {
+abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *scratch_dev, void *hip_stream) try {
   if (!params_dev) return fail(ABS_EINVAL, "params_dev is NULL");
   if (M < 1 || n < 8 || (n % 8)) return fail(ABS_EINVAL, "M < 1 or n not a positive multiple of 8");
   if ((reinterpret_cast<uintptr_t>(params_dev) | reinterpret_cast<uintptr_t>(scratch_dev)) & 15)
@@ -1185,6 +1209,6 @@ abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *scratch_de
   HIPCHK(nc, launch_average_bf16(static_cast<bf16_t *>(params_dev), static_cast<bf16_t *>(scratch_dev), M, n,
                                  static_cast<hipStream_t>(hip_stream)));
   return ABS_OK;
-}
+} catch (...) { return on_exception(); }
 
 }  // extern "C"
