@@ -197,22 +197,32 @@ __global__ void __launch_bounds__(256) col_sum_stage1(const T *__restrict__ X, l
   if (rl == 0 && c < cols)
     part[((long long)g * nsplit + rs) * cols + c] = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
 }
+// Stage 2: a block owns 64 columns; its four row-lanes add the partials r = lane, lane + 4, ... in that
+// order and the four sums are combined in lane order.
 __global__ void __launch_bounds__(256) col_sum_stage2(const float *__restrict__ part, int cols, int nsplit,
                                                       float alpha, float *__restrict__ out, long long sOg,
                                                       const int *__restrict__ rows, int tile_m, int parts_per_tile,
                                                       int accumulate) {
-  const int g = blockIdx.y, c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= cols) return;
-  const float *p = part + (long long)g * nsplit * cols + c;
+  __shared__ float red[4][64];
+  const int g = blockIdx.y, cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
   int ns = nsplit;
   if (rows) {
     alpha = 1.0f / (float)rows[g];
     if (tile_m > 0) ns = (rows[g] + tile_m - 1) / tile_m * parts_per_tile;   // only these were written
   }
   float s = 0.0f;
-  for (int r = 0; r < ns; ++r) s += p[(long long)r * cols];
-  float *o = out + (long long)g * sOg + c;
-  *o = accumulate ? fmaf(alpha, s, *o) : alpha * s;
+  if (c < cols) {
+    const float *p = part + (long long)g * nsplit * cols + c;
+    for (int r = rl; r < ns; r += 4) s += p[(long long)r * cols];
+  }
+  red[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && c < cols) {
+    const float t = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
+    float *o = out + (long long)g * sOg + c;
+    *o = accumulate ? fmaf(alpha, t, *o) : alpha * t;
+  }
 }
 
 __global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, int ldd,
@@ -238,13 +248,13 @@ __global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, in
 // Stage 1a (grid: PBLK x groups): per-sample squared gradient norms
 //   n_i = sum_l ||delta_i^l||^2 (||a_i^{l-1}||^2 + [bias])   and   q_i = sum_l sum_parts ...
 // with block partial sums of n_i, q_i, q_i^2 and the loss, in double.
-__global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p) {
-  __shared__ double red[4];
-  const int g = blockIdx.y;
+// Blocks 0 .. nb-1 of a group share its samples (block j owns samples 256 j + t, then strides of 256 nb);
+// the launch uses nb = min(PBLK, ceil(b / 256)) blocks and stage 2 takes the other partials as zero.
+__device__ __forceinline__ void stats_samples_block(const StatsP &p, int g, int blk, int nb, double *red) {
   double s1 = 0.0, s3 = 0.0, s4 = 0.0, sl = 0.0;
   const float hb = p.has_bias ? 1.0f : 0.0f;
   const int bg = p.rows ? p.rows[g] : p.b;
-  for (int i = blockIdx.x * 256 + threadIdx.x; i < bg; i += 256 * STATS_PBLK) {
+  for (int i = blk * 256 + threadIdx.x; i < bg; i += 256 * nb) {
     const long long o = (long long)g * p.sNg + i;
     if (p.do_n) {
       float n = 0.0f;
@@ -269,12 +279,28 @@ __global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p) {
       s3 += (double)q * (double)q;
     }
   }
-  double *out = p.partials + ((long long)g * 5) * STATS_PBLK + blockIdx.x;
+  double *out = p.partials + ((long long)g * 5) * STATS_PBLK + blk;
   double r;
   r = block_sum<4>(s1, red); if (threadIdx.x == 0) out[0 * STATS_PBLK] = r;
   r = block_sum<4>(s3, red); if (threadIdx.x == 0) out[2 * STATS_PBLK] = r;
   r = block_sum<4>(s4, red); if (threadIdx.x == 0) out[3 * STATS_PBLK] = r;
   r = block_sum<4>(sl, red); if (threadIdx.x == 0) out[4 * STATS_PBLK] = r;
+}
+__device__ __forceinline__ void stats_gradsq_parts_block(const float *__restrict__ sq_wave, long long per_group,
+                                                         double *__restrict__ partials, int g, int blk, double *red) {
+  const float *p = sq_wave + (long long)g * per_group;
+  double s = 0.0;
+  for (long long i = blk * 256LL + threadIdx.x; i < per_group; i += 256LL * STATS_PBLK) s += (double)p[i];
+  const double r = block_sum<4>(s, red);
+  if (threadIdx.x == 0) partials[((long long)g * 5 + 1) * STATS_PBLK + blk] = r;
+}
+// grid (nb_samples + nb_parts) x groups: the first nb_samples blocks of a group take the per-sample sums,
+// the other PBLK blocks (present when the update kernel left per-wavefront partials) the ||gbar||^2 partials.
+__global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p, int nb_samples) {
+  __shared__ double red[4];
+  const int g = blockIdx.y, blk = blockIdx.x;
+  if (blk < nb_samples) stats_samples_block(p, g, blk, nb_samples, red);
+  else stats_gradsq_parts_block(p.sq_wave, p.n_sq_wave, p.partials, g, blk - nb_samples, red);
 }
 
 // Stage 1b (grid: PBLK x groups): ||gbar||^2 over the padded gradient vector.
@@ -294,29 +320,19 @@ __global__ void __launch_bounds__(256) stats_gradsq_kernel(const float *__restri
   if (threadIdx.x == 0) partials[((long long)g * 5 + 1) * STATS_PBLK + blockIdx.x] = r;
 }
 
-// Stage 1b': the same sum from the per-wavefront partials left by the update kernel.
-__global__ void __launch_bounds__(256) stats_gradsq_parts_kernel(const float *__restrict__ sq_wave, long long per_group,
-                                                                 double *__restrict__ partials) {
-  __shared__ double red[4];
-  const int g = blockIdx.y;
-  const float *p = sq_wave + (long long)g * per_group;
-  double s = 0.0;
-  for (long long i = blockIdx.x * 256LL + threadIdx.x; i < per_group; i += 256LL * STATS_PBLK) s += (double)p[i];
-  const double r = block_sum<4>(s, red);
-  if (threadIdx.x == 0) partials[((long long)g * 5 + 1) * STATS_PBLK + blockIdx.x] = r;
-}
-
 // Stage 2 (grid: groups): add the PBLK partials of each of the five sums in index order.
 // sel / acc: bit k set = sum k is produced by this launch / is added to the stored value.
+// nb_samples: how many partials of the per-sample sums (all but k = 1) this step wrote; the rest count as zero.
 __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restrict__ partials,
                                                           double *__restrict__ stats, double *__restrict__ stats_host,
-                                                          int sel, int acc) {
+                                                          int sel, int acc, int nb_samples) {
   __shared__ double red[4];
   const int g = blockIdx.x;
   static_assert(STATS_PBLK == 256, "one partial per thread");
   for (int k = 0; k < 5; ++k) {
     if (!((sel >> k) & 1)) continue;
-    const double v = partials[((long long)g * 5 + k) * STATS_PBLK + threadIdx.x];
+    const bool live = k == 1 || (int)threadIdx.x < nb_samples;
+    const double v = live ? partials[((long long)g * 5 + k) * STATS_PBLK + threadIdx.x] : 0.0;
     const double r = block_sum<4>(v, red);
     if (threadIdx.x == 0) {
       const double v = ((acc >> k) & 1) ? stats[g * 8 + k] + r : r;
@@ -651,7 +667,7 @@ hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int
     hipLaunchKernelGGL(col_sum_stage1<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
                        scratch, nsplit, rows);
   // stage 1 writes every partial (zeros past a group's rows), so stage 2 adds all of them
-  hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, scratch, cols, nsplit,
+  hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 63) / 64, groups), dim3(256), 0, s, scratch, cols, nsplit,
                      alpha, out, sOg, rows, 0, 0, accumulate);
   return hipGetLastError();
 }
@@ -659,7 +675,7 @@ hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int
 hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha, float *out,
                                  long long sOg, const int *rows, int tile_m, int parts_per_tile, int accumulate,
                                  hipStream_t s) {
-  hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 255) / 256, groups), dim3(256), 0, s, part, cols, nsplit,
+  hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 63) / 64, groups), dim3(256), 0, s, part, cols, nsplit,
                      alpha, out, sOg, rows, tile_m, parts_per_tile, accumulate);
   return hipGetLastError();
 }
@@ -680,14 +696,19 @@ hipError_t launch_stats(const StatsP &p, hipStream_t s) {
   if (p.grad && p.sq_wave) return hipErrorInvalidValue;
   if (p.grad || p.sq_wave) sel |= 2;
   if (!sel) return hipSuccess;
-  if (p.do_n || p.do_q) hipLaunchKernelGGL(stats_samples_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p);
+  int nb_samples = 0;
+  if (p.do_n || p.do_q) {
+    nb_samples = (p.b + 255) / 256;
+    nb_samples = nb_samples < 1 ? 1 : (nb_samples > STATS_PBLK ? STATS_PBLK : nb_samples);
+  }
+  const int nb_parts = p.sq_wave ? STATS_PBLK : 0;
+  if (nb_samples + nb_parts > 0)
+    hipLaunchKernelGGL(stats_samples_kernel, dim3(nb_samples + nb_parts, p.groups), dim3(256), 0, s, p, nb_samples);
   if (p.grad)
     hipLaunchKernelGGL(stats_gradsq_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.grad, p.Ppad,
                        p.partials);
-  if (p.sq_wave)
-    hipLaunchKernelGGL(stats_gradsq_parts_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.sq_wave, p.n_sq_wave,
-                       p.partials);
-  hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats, p.stats_host, sel, acc);
+  hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats, p.stats_host, sel, acc,
+                     nb_samples);
   return hipGetLastError();
 }
 
