@@ -113,37 +113,40 @@ __global__ void gather_kernel(const T *__restrict__ X, int d, int N, const int32
   if (lane == 0) an0[(long long)g * sNg + i] = s;
 }
 
-// One wavefront per row of logits.
-template <class T>
+// LPR lanes per row of logits: a whole wavefront, or 16 lanes (four rows per wavefront) for at most 16
+// classes.  The butterflies stay inside a row's lanes (xor distances below LPR).
+template <class T, int LPR>
 __global__ void softmax_ce_kernel(const float *__restrict__ Z, long long sZg, int ldz, int K,
                                   const int32_t *__restrict__ y, int N, const int32_t *__restrict__ idx, int ldi,
                                   int b, T *__restrict__ D, long long sDg, int ldd,
                                   float *__restrict__ dn, float *__restrict__ loss, long long sNg,
                                   const int *__restrict__ rows) {
   const int g = blockIdx.y;
-  const int i = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (i >= (rows ? rows[g] : b)) return;
-  const int lane = threadIdx.x & 63;
+  const int i = (blockIdx.x * blockDim.x + threadIdx.x) / LPR;
+  if (i >= (rows ? rows[g] : b)) return;          // uniform over a row's lanes
+  const int lane = threadIdx.x & (LPR - 1);
   const float *z = Z + (long long)g * sZg + (long long)i * ldz;
   const int label = min(max(y[min(max(idx[(long long)g * ldi + i], 0), N - 1)], 0), K - 1);
   float mx = -INFINITY;
-  for (int c = lane; c < K; c += 64) mx = fmaxf(mx, z[c]);
+  for (int c = lane; c < K; c += LPR) mx = fmaxf(mx, z[c]);
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  for (int o = LPR / 2; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
   float se = 0.0f;
-  for (int c = lane; c < K; c += 64) se += expf(z[c] - mx);
-  se = wave_sum(se);
+  for (int c = lane; c < K; c += LPR) se += expf(z[c] - mx);
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
   const float inv = 1.0f / se;
   T *drow = D + (long long)g * sDg + (long long)i * ldd;
   float sq = 0.0f;
-  for (int c = lane; c < ldd; c += 64) {
+  for (int c = lane; c < ldd; c += LPR) {
     float dv = 0.0f;
     if (c < K) dv = expf(z[c] - mx) * inv - (c == label ? 1.0f : 0.0f);
     const float st = Elem<T>::rnd(dv);
     Elem<T>::st(drow + c, dv);
     sq = fmaf(st, st, sq);
   }
-  sq = wave_sum(sq);
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
   if (lane == 0) {
     dn[(long long)g * sNg + i] = sq;
     loss[(long long)g * sNg + i] = -(z[label] - mx - logf(se));
@@ -633,12 +636,23 @@ hipError_t launch_gather_rows(int is_bf16, const void *X, int d, int N, const in
 hipError_t launch_softmax_ce(int is_bf16, const float *Z, long long sZg, int ldz, int K, const int32_t *y,
                              int N, const int32_t *idx, int ldi, int groups, int b, void *D, long long sDg, int ldd,
                              float *dn, float *loss, long long sNg, const int *rows, hipStream_t s) {
-  const dim3 grid((b + 3) / 4, groups), blk(256);
+  const dim3 blk(256);
+  if (ldd <= 16) {
+    const dim3 grid((b + 15) / 16, groups);
+    if (is_bf16)
+      hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, 16>), grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+                         static_cast<bf16_t *>(D), sDg, ldd, dn, loss, sNg, rows);
+    else
+      hipLaunchKernelGGL((softmax_ce_kernel<float, 16>), grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+                         static_cast<float *>(D), sDg, ldd, dn, loss, sNg, rows);
+    return hipGetLastError();
+  }
+  const dim3 grid((b + 3) / 4, groups);
   if (is_bf16)
-    hipLaunchKernelGGL(softmax_ce_kernel<bf16_t>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+    hipLaunchKernelGGL((softmax_ce_kernel<bf16_t, 64>), grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
                        static_cast<bf16_t *>(D), sDg, ldd, dn, loss, sNg, rows);
   else
-    hipLaunchKernelGGL(softmax_ce_kernel<float>, grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+    hipLaunchKernelGGL((softmax_ce_kernel<float, 64>), grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
                        static_cast<float *>(D), sDg, ldd, dn, loss, sNg, rows);
   return hipGetLastError();
 }
