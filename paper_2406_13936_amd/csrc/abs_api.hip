@@ -143,12 +143,14 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   pl.o_stats = take((size_t)pl.M * 8 * 8);
   pl.o_rows = take((size_t)2 * pl.M * sizeof(int));          // per-group row counts, then the launch order
   pl.o_sqwave = take((size_t)pl.M * (pl.Ppad / 256) * sizeof(float));
-  if (pl.bf16) {
-    // a split is only taken when the un-split launch has at most 256 tiles, and never makes more than
-    // 512 (tile, slice) pairs of at most 128 x 128 or 256 x 256 outputs each
+  {
+    // bf16: a split is only taken when the un-split launch has at most 256 tiles, and never makes more than
+    // 512 (tile, slice) pairs of at most 128 x 128 or 256 x 256 outputs each; fp32: at most 8 slices of launches
+    // of fewer than 256 tiles of 64 x 64
     size_t mx = 0;
     for (int l = 1; l <= pl.L; ++l) mx = std::max(mx, (size_t)pl.dims[l] * pl.dims[l - 1]);
-    pl.kpart_floats = std::min((size_t)8 * pl.M * mx, (size_t)512 * 65536);
+    pl.kpart_floats = pl.bf16 ? std::min((size_t)8 * pl.M * mx, (size_t)512 * 65536)
+                              : std::min((size_t)8 * pl.M * mx, (size_t)8 * 256 * 4096);
     pl.o_kpart = take(pl.kpart_floats * sizeof(float));
   }
   pl.o_cw = take((2 * (size_t)cross_worker_blocks(pl.Ppad) + 8) * 8);
@@ -644,6 +646,24 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
       p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
       if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
+      if (!pl.bf16 && p.ldc == p.Nd && (((long long)p.Md * p.Nd) & 3) == 0) {
+        // fp32 mode (small problems): a block walks its reduction 16 samples at a time, about 2.7 us a step, so
+        // a long batch over few 64 x 64 output tiles is cut into up to 8 slices (finish launch: about 8 us)
+        const long long blocks = (long long)((p.Md + 63) / 64) * ((p.Nd + 63) / 64) * M;
+        const int KT = (b + 15) / 16;
+        int best = 1;
+        double best_cost = KT * 2.7;
+        for (int S = 2; S <= 8 && blocks < 256; ++S) {
+          if (blocks * S > 1024 || (size_t)S * M * p.Md * p.Nd > pl.kpart_floats) break;
+          const double cost = ((KT + S - 1) / S) * 2.7 + 8.0;
+          if (cost < best_cost) { best = S; best_cost = cost; }
+        }
+        if (best > 1) {
+          p.ksplit = best;
+          p.kchunk = ((KT + best - 1) / best) * 16;
+          p.kpart = c->at<float>(pl.o_kpart);
+        }
+      }
       if (pl.bf16 && p.ldc == p.Nd && (p.Nd & 3) == 0) {
         // few output tiles and a long reduction (small layers, or any layer while b is the long side): cut
         // the reduction into slices so that the launch fills the chip, and add the slices in order afterwards

@@ -14,12 +14,22 @@ template <int EPI, int ACT>
 __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
   __shared__ float As[16][68];
   __shared__ float Bs[16][68];
-  const int g = blockIdx.z, m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  // blockIdx.z = group, or (group, k-slice) of a weight gradient whose reduction is split
+  const int ksplit = (EPI == EPI_WGRAD && pin.ksplit > 1) ? pin.ksplit : 1;
+  const int g = blockIdx.z / ksplit, ksl = blockIdx.z - g * ksplit;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
   GemmP p = pin;
   if (p.rows) {                                   // ragged groups: this group's own extent
     const int r = p.rows[g];
     if (p.rows_is_k) { p.Kd = r; p.alpha = 1.0f / (float)r; } else p.Md = r;
     if (m0 >= p.Md) return;                       // uniform over the block, before any barrier
+  }
+  int kbeg = 0;
+  if (ksplit > 1) {                               // this block's slice; an empty one writes zeros
+    kbeg = ksl * p.kchunk;
+    const int kend = kbeg + p.kchunk;
+    if (kend < p.Kd) p.Kd = kend;
+    if (kbeg > p.Kd) kbeg = p.Kd;
   }
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const float *A = static_cast<const float *>(p.A) + (long long)g * p.sAg;
@@ -30,7 +40,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
 
-  for (int k0 = 0; k0 < p.Kd; k0 += 16) {
+  for (int k0 = kbeg; k0 < p.Kd; k0 += 16) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int id = tid + e * 256;
@@ -94,7 +104,9 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
           static_cast<float *>(p.C)[(long long)g * p.sCg + (long long)m * p.ldc + n] = o;
         }
       } else if (EPI == EPI_WGRAD) {
-        if (nin) {
+        if (nin && ksplit > 1) {                  // raw partial product of this k-slice, packed Md x Nd
+          p.kpart[((long long)g * ksplit + ksl) * p.Md * p.Nd + (long long)m * p.Nd + n] = v;
+        } else if (nin) {
           float *o = static_cast<float *>(p.C) + (long long)g * p.sCg + (long long)m * p.ldc + n;
           *o = p.accumulate ? fmaf(v, p.alpha, *o) : v * p.alpha;
         }
@@ -105,7 +117,9 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
 
 template <int EPI, int ACT>
 hipError_t launch1(const GemmP &p, hipStream_t s) {
-  const dim3 grid((p.Nd + 63) / 64, (p.Md + 63) / 64, p.groups);
+  const int ks = (EPI == EPI_WGRAD && p.ksplit > 1) ? p.ksplit : 1;
+  if (ks > 1 && (!p.kpart || p.kchunk <= 0 || (p.kchunk & 15) || (long long)p.kchunk * ks < p.Kd)) return hipErrorInvalidValue;
+  const dim3 grid((p.Nd + 63) / 64, (p.Md + 63) / 64, p.groups * ks);
   if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
   hipLaunchKernelGGL((gemm_f32_kernel<EPI, ACT>), grid, dim3(256), 0, s, p);
   return hipGetLastError();

@@ -490,6 +490,7 @@ def test_per_worker_schedule_lockstep_fp32():
 @pytest.mark.parametrize("prec,dims,act,b,micro,cap,opt,test", [
     (W.PREC_F32, (72, 130, 66, 5), W.ACT_GELU, 150, 64, 150, W.OPT_SHB, W.TEST_AUG_IP),
     (W.PREC_F32, (256, 10), W.ACT_NONE, 96, 32, 32, W.OPT_SGD, W.TEST_NORM),
+    (W.PREC_F32, (72, 30, 5), W.ACT_GELU, 600, 256, 256, W.OPT_SHB, W.TEST_AUG_IP),   # sliced fp32 reductions that accumulate
     (W.PREC_BF16, (384, 256, 256, 100), W.ACT_GELU, 700, 256, 256, W.OPT_ADAMW, W.TEST_AUG_IP),
     (W.PREC_BF16, (784, 512, 512, 10), W.ACT_RELU, 300, 128, 300, W.OPT_SGD, W.TEST_NORM),
     (W.PREC_BF16, (1024, 1024, 1024, 100), W.ACT_RELU, 2124, 1024, 1024, W.OPT_SHB, W.TEST_IP),   # 256x256 tiles
