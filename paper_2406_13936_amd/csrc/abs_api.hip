@@ -647,10 +647,10 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
       if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
       if (!pl.bf16 && p.ldc == p.Nd && (((long long)p.Md * p.Nd) & 3) == 0) {
-        // fp32 mode (small problems): a block walks its reduction 16 samples at a time, about 2.7 us a step, so
+        // fp32 mode (small problems): a block walks its reduction 32 samples at a time, about 2.7 us a step, so
         // a long batch over few 64 x 64 output tiles is cut into up to 8 slices (finish launch: about 8 us)
         const long long blocks = (long long)((p.Md + 63) / 64) * ((p.Nd + 63) / 64) * M;
-        const int KT = (b + 15) / 16;
+        const int KT = (b + 31) / 32;
         int best = 1;
         double best_cost = KT * 2.7;
         for (int S = 2; S <= 8 && blocks < 256; ++S) {
@@ -660,7 +660,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         }
         if (best > 1) {
           p.ksplit = best;
-          p.kchunk = ((KT + best - 1) / best) * 16;
+          p.kchunk = ((KT + best - 1) / best) * 32;
           p.kpart = c->at<float>(pl.o_kpart);
         }
       }

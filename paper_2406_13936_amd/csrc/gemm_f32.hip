@@ -2,8 +2,9 @@
 //   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k]
 // with the same operand-layout flags and epilogues as the bf16 matrix-core family.  The fp32
 // mode serves small, latency-bound problems (logistic regression), so this kernel favours
-// generality (arbitrary strides and extents) over peak rate: 64x64 block tile, k-step 16,
-// 256 threads, 4x4 outputs per thread.
+// generality (arbitrary strides and extents) over peak rate: 64x64 block tile, k-step 32,
+// 256 threads, 4x4 outputs per thread; the next k-step's operands are fetched into registers
+// while the current one is multiplied (the loop is bound by load latency, not by arithmetic).
 #include "abs_internal.h"
 #include "device_utils.h"
 
@@ -12,8 +13,9 @@ namespace {
 
 template <int EPI, int ACT>
 __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
-  __shared__ float As[16][68];
-  __shared__ float Bs[16][68];
+  constexpr int BK = 32, PT = 64 * BK / 256;     // k-step, elements per thread and operand
+  __shared__ float As[BK][68];
+  __shared__ float Bs[BK][68];
   // blockIdx.z = group, or (group, k-slice) of a weight gradient whose reduction is split
   const int ksplit = (EPI == EPI_WGRAD && pin.ksplit > 1) ? pin.ksplit : 1;
   const int g = blockIdx.z / ksplit, ksl = blockIdx.z - g * ksplit;
@@ -40,25 +42,37 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
 
-  for (int k0 = kbeg; k0 < p.Kd; k0 += 16) {
+  float ra[PT], rb[PT];
+  auto fetch = [&](int k0) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+    for (int e = 0; e < PT; ++e) {
       const int id = tid + e * 256;
       int kk, rr;
-      if (!p.a_trans) { kk = id & 15; rr = id >> 4; } else { rr = id & 63; kk = id >> 6; }
+      if (!p.a_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
       const int m = m0 + rr, k = k0 + kk;
-      float v = 0.0f;
-      if (m < p.Md && k < p.Kd) v = p.a_trans ? A[(long long)k * p.lda + m] : A[(long long)m * p.lda + k];
-      As[kk][rr] = v;
-      if (!p.b_trans) { kk = id & 15; rr = id >> 4; } else { rr = id & 63; kk = id >> 6; }
+      ra[e] = 0.0f;
+      if (m < p.Md && k < p.Kd) ra[e] = p.a_trans ? A[(long long)k * p.lda + m] : A[(long long)m * p.lda + k];
+      if (!p.b_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
       const int n = n0 + rr, kb = k0 + kk;
-      v = 0.0f;
-      if (n < p.Nd && kb < p.Kd) v = p.b_trans ? B[(long long)kb * p.ldb + n] : B[(long long)n * p.ldb + kb];
-      Bs[kk][rr] = v;
+      rb[e] = 0.0f;
+      if (n < p.Nd && kb < p.Kd) rb[e] = p.b_trans ? B[(long long)kb * p.ldb + n] : B[(long long)n * p.ldb + kb];
+    }
+  };
+  if (kbeg < p.Kd) fetch(kbeg);
+  for (int k0 = kbeg; k0 < p.Kd; k0 += BK) {
+#pragma unroll
+    for (int e = 0; e < PT; ++e) {
+      const int id = tid + e * 256;
+      int kk, rr;
+      if (!p.a_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
+      As[kk][rr] = ra[e];
+      if (!p.b_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
+      Bs[kk][rr] = rb[e];
     }
     __syncthreads();
+    if (k0 + BK < p.Kd) fetch(k0 + BK);
 #pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
+    for (int kk = 0; kk < BK; ++kk) {
       float a[4], b[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
@@ -118,7 +132,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
 template <int EPI, int ACT>
 hipError_t launch1(const GemmP &p, hipStream_t s) {
   const int ks = (EPI == EPI_WGRAD && p.ksplit > 1) ? p.ksplit : 1;
-  if (ks > 1 && (!p.kpart || p.kchunk <= 0 || (p.kchunk & 15) || (long long)p.kchunk * ks < p.Kd)) return hipErrorInvalidValue;
+  if (ks > 1 && (!p.kpart || p.kchunk <= 0 || (p.kchunk & 31) || (long long)p.kchunk * ks < p.Kd)) return hipErrorInvalidValue;
   const dim3 grid((p.Nd + 63) / 64, (p.Md + 63) / 64, p.groups * ks);
   if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
   hipLaunchKernelGGL((gemm_f32_kernel<EPI, ACT>), grid, dim3(256), 0, s, p);
