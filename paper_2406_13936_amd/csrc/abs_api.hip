@@ -1151,7 +1151,13 @@ abs_status abs_layer_stats(int L, const int *in_dims, const int *out_dims, int M
   float *loss = reinterpret_cast<float *>(ws + off[4]);
   abs_ctx *nc = nullptr;
   HIPCHK(nc, launch_fill_zero(loss, (long long)M * b * 4, s));
-  HIPCHK(nc, launch_fill_zero(grad, (long long)M * Wtot * 4, s));
+  {
+    // the weight gradients overwrite every entry of their layers; only the padding behind the last layer,
+    // which the ||gbar||^2 pass reads too, has to be cleared
+    long long Wsum = 0;
+    for (int l = 0; l < L; ++l) Wsum += (long long)in_dims[l] * out_dims[l];
+    HIPCHK(nc, launch_zero_range(grad, Wtot, Wsum, Wtot, M, s));
+  }
   StatsP sp;
   std::memset(&sp, 0, sizeof(sp));
   const float inv_b = 1.0f / (float)b;

@@ -148,6 +148,7 @@ int cross_worker_blocks(long long Ppad);
 hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, double *partials,
                                double *out, hipStream_t s);
 hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);
+hipError_t launch_zero_range(float *x, long long stride, long long from, long long to, int groups, hipStream_t s);
 // C[g][e] = alpha * sum_sp kpart[(g * ksplit + sp) * mn + e]  (+ C[g][e] if accumulate), slices added in order;
 // C2 (bf16, may be null) gets the rounded result; rows (may be null): alpha = 1 / rows[g].  mn multiple of 4.
 hipError_t launch_splitk_finish(const float *kpart, int ksplit, int groups, long long mn, float alpha, const int *rows,

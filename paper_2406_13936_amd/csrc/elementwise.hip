@@ -816,6 +816,18 @@ hipError_t launch_set_ints(const int *v_host, int n, int *dst, hipStream_t s) {
   return hipGetLastError();
 }
 
+// x[g * stride + i] = 0 for i in [from, to) and every group g (a short range: padding behind the data)
+__global__ void __launch_bounds__(256) zero_range_kernel(float *__restrict__ x, long long stride, long long from, long long to) {
+  float *p = x + (long long)blockIdx.x * stride;
+  for (long long i = from + threadIdx.x; i < to; i += 256) p[i] = 0.0f;
+}
+
+hipError_t launch_zero_range(float *x, long long stride, long long from, long long to, int groups, hipStream_t s) {
+  if (to <= from || groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(zero_range_kernel, dim3(groups), dim3(256), 0, s, x, stride, from, to);
+  return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s) {
   if (bytes <= 0) return hipSuccess;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(grid_for(bytes / 16, 256, 4096)), dim3(256), 0, s,
