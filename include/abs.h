@@ -43,9 +43,9 @@ typedef struct abs_ctx abs_ctx;
 typedef enum {
   ABS_OK = 0,
   ABS_EINVAL = 1,       /* bad argument (range, NULL, alignment) */
-  ABS_ENOMEM = 2,       /* workspace too small */
+  ABS_ENOMEM = 2,       /* workspace (or one of its pieces) too small; host allocation failed */
   ABS_ESTATE = 3,       /* call out of order (e.g. a test before any local step) */
-  ABS_EHIP = 4,         /* a HIP runtime call failed */
+  ABS_EHIP = 4,         /* a HIP runtime call failed (or an unexpected internal error) */
   ABS_EUNSUPPORTED = 5  /* shape the kernels do not cover */
 } abs_status;
 
