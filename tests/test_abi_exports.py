@@ -32,6 +32,18 @@ def test_every_declared_entry_point_is_exported():
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 with no C++ in it."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "abs.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_binding_lists_the_same_entry_points():
     from paper_2406_13936_amd import binding
     assert sorted(binding.EXPORTS) == _declared()
