@@ -622,6 +622,62 @@ def test_identical_samples_give_zero_variance_and_smallest_batch():
 
 
 @pytest.mark.parametrize("prec", [W.PREC_F32, W.PREC_BF16])
+def test_zero_batch_gradient_keeps_the_batch_size(prec):
+    """All-zero inputs and no biases: every per-sample gradient is zero, so S1 = S2 = 0; the rule then leaves the
+    batch size alone (T = b, test passes) for the norm test and for the inner-product tests, as in the oracle."""
+    A = _A()
+    w = W.Workload("zero", (64, 32, 8), W.ACT_NONE, False, prec, N=64, M=2, H=1, rounds=1, b0=12, b_cap=16,
+                   opt=W.OPT_SGD, lr=0.1, test=W.TEST_AUG_IP, eta=0.5, theta=0.9, nu=0.5, data="teacher_mlp", seed=4)
+    X, y = W.make_dataset(w)
+    X = np.zeros_like(X)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    orc = _oracle_for(w, X, y, x0, mixed=prec == W.PREC_BF16)
+    try:
+        idx = W.step_indices(w, 0, 0, 12)
+        rep.local_step(idx, w.lr)
+        orc.local_step(idx, w.lr)
+        for res, ores in ((rep.norm_test(0.5), orc.test(W.TEST_NORM, eta=0.5)),
+                          (rep.inner_product_test(0.9, 0.5), orc.test(W.TEST_AUG_IP, theta=0.9, nu=0.5))):
+            for m in range(w.M):
+                assert res[m].sum_sq == 0.0 and res[m].gbar_sq == 0.0
+                assert res[m].T == 12 == ores[m]["T"] and res[m].pass_ == 1
+        assert A.next_batch_size(rep.norm_test(0.5), [12, 12], w.b_cap, True) == [12, 12]
+        for m in range(w.M):
+            assert np.array_equal(rep.get_params(m), x0.astype(np.float32))     # a zero gradient moves nothing
+    finally:
+        rep.close()
+
+
+def test_one_local_step_per_round_is_synchronous_sgd_on_the_concatenated_batch():
+    """H = 1 with plain SGD (Sec. 3: Local SGD with one local step is mini-batch SGD): M workers with b samples
+    each, averaged after every step, follow the single model trained on the M b samples together."""
+    A = _A()
+    M, b, steps = 4, 24, 5
+    wl = W.Workload("local", (40, 24, 6), W.ACT_GELU, True, W.PREC_F32, N=512, M=M, H=1, rounds=steps, b0=b, b_cap=b,
+                    opt=W.OPT_SGD, lr=0.2, test=W.TEST_NORM, eta=0.5, data="teacher_mlp", seed=31)
+    ws = W.Workload("sync", wl.dims, wl.act, True, W.PREC_F32, N=512, M=1, H=1, rounds=steps, b0=M * b, b_cap=M * b,
+                    opt=W.OPT_SGD, lr=0.2, test=W.TEST_NORM, eta=0.5, data="teacher_mlp", seed=31)
+    X, y = W.make_dataset(wl)
+    x0 = W.make_x0(wl)
+    loc = A.Replicas.from_workload(wl, X, y, x0)
+    syn = A.Replicas.from_workload(ws, X, y, x0)
+    try:
+        for k in range(steps):
+            idx = W.step_indices(wl, k, 0, b)                     # [M, b]
+            loc.local_step(idx, wl.lr)
+            loc.average_replicas()
+            syn.local_step(idx.reshape(1, M * b), ws.lr)
+            want = syn.get_params(0).astype(np.float64)
+            for m in range(M):
+                got = loc.get_params(m).astype(np.float64)
+                assert np.abs(got - want).max() <= 2e-6 * np.abs(want).max(), (k, m)
+    finally:
+        loc.close()
+        syn.close()
+
+
+@pytest.mark.parametrize("prec", [W.PREC_F32, W.PREC_BF16])
 def test_single_worker_is_plain_minibatch_sgd(prec):
     """M = 1 (the adaptive-sampling method for one worker, Sec. 4.1): the average is the identity,
     the cross-worker estimator is undefined, the step equals the oracle's."""
