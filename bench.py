@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--graphs", action="store_true",
                     help="replay captured HIP graphs on the steps that are not bracketed by events (fixed batch size)")
     ap.add_argument("--no-also", action="store_true", help="skip the reference measurement of config 2 (profiling runs)")
+    ap.add_argument("--beyond", action="store_true",
+                    help="time the entry points beyond the base path on config-3 / config-2 shapes instead: the "
+                         "cross-worker estimator, ragged per-worker batch sizes, accumulated steps")
     return ap.parse_args()
 
 
@@ -295,6 +298,53 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     return out
 
 
+def beyond_base_path(np, torch, A, W):
+    """Step times of the entry points beyond the base path (cross-worker estimator, ragged sizes, accumulation)
+    on config-3 shapes at the cap and one accumulated case on config 2; inputs resident in HBM, test included."""
+    def timeit(f, n):
+        f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    cases = []
+    w = W.config3()
+    X, y = W.make_dataset(w)
+    rep = A.Replicas.from_workload(w, X, y, W.make_x0(w))
+    b = w.b_cap
+    t_idx, _ = rep.upload_indices(W.step_indices(w, 0, 0, b))
+    dt = timeit(lambda: (rep.local_step_dev(t_idx, b, w.lr), rep.inner_product_test(w.theta)), 6)
+    cases.append({"case": "config 3 uniform step, b = %d" % b, "ms": dt * 1e3, "samples_per_s": w.M * b / dt})
+    dt = timeit(lambda: rep.cross_worker_test(0.5), 10)
+    cases.append({"case": "cross-worker estimator on the gradients of the last step", "ms": dt * 1e3,
+                  "gbs": w.M * rep.n_params * 4 / dt / 1e9})
+    for name, bs in (("ragged: 8 workers at 8192, 8 at 4096", [8192] * 8 + [4096] * 8),
+                     ("ragged: sizes spread from 1024 to 8192", [1024 + (8192 - 1024) * m // 15 for m in range(16)])):
+        rows = [W.batch_indices(w.seed, 0, 0, m, bs[m], w.N) for m in range(w.M)]
+        dt = timeit(lambda: (rep.local_step_ragged(rows, w.lr), rep.inner_product_test(w.theta)), 4)
+        cases.append({"case": name, "ms": dt * 1e3, "samples_per_s": sum(bs) / dt,
+                      "note": "indices uploaded from the host in every call"})
+    idx2 = W.step_indices(w, 0, 1, 2 * b)
+    dt = timeit(lambda: (rep.local_step_accumulated(idx2, b, w.lr), rep.inner_product_test(w.theta)), 3)
+    cases.append({"case": "accumulated: b = %d in two micro-batches, inner-product statistics" % (2 * b), "ms": dt * 1e3,
+                  "samples_per_s": w.M * 2 * b / dt, "note": "indices uploaded from the host in every call"})
+    rep.close()
+    w2 = W.config2()
+    X, y = W.make_dataset(w2)
+    rep = A.Replicas.from_workload(w2, X, y, W.make_x0(w2))
+    idx2 = W.step_indices(w2, 0, 1, 4 * w2.b_cap)
+    dt = timeit(lambda: (rep.local_step_accumulated(idx2, w2.b_cap, w2.lr), rep.norm_test(w2.eta)), 10)
+    cases.append({"case": "config 2 accumulated: b = %d in four micro-batches, norm statistics" % (4 * w2.b_cap),
+                  "ms": dt * 1e3, "samples_per_s": w2.M * 4 * w2.b_cap / dt,
+                  "note": "indices uploaded from the host in every call"})
+    rep.close()
+    return {"metric": "step time of the entry points beyond the base path", "unit": "ms", "n_gpus": 1,
+            "dtype": "bf16", "data": "synthetic", "config": {"workload": "cfg3 / cfg2 shapes at the cap"}, "cases": cases}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -309,6 +359,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(3)
+    if a.beyond:
+        print(json.dumps(beyond_base_path(np, torch, A, W)))
+        return
     if a.workload == "config5":
         print(json.dumps(stats_stress(a, np, torch, A, W)))
         return
