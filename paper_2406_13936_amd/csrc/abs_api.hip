@@ -32,7 +32,9 @@ struct Plan {
   long long P = 0, Ppad = 0;
   int M = 0, cap = 0;
   int qparts[MAXL] = {0};
-  size_t colpart_per = 0;              // floats of column-partial scratch per replica
+  size_t colpart_per = 0;              // floats of column-partial scratch per replica (fp32 mode: one piece for all layers)
+  size_t o_colpart_l[MAXL + 1] = {0};  // bf16 mode: one piece per layer, so that one launch can finish all bias gradients
+  size_t colpart_l_per[MAXL + 1] = {0};
   int rparts[MAXL + 1] = {0};          // partial vectors kept for the row norms of width dims[l]
   // byte offsets into the workspace
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
@@ -126,18 +128,20 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
       if (pl.qparts[l - 1]) pl.o_qpart[l - 1] = take(MB * 4 * pl.qparts[l - 1]);
     }
   }
-  if (c->has_bias) {
+  if (c->has_bias && !pl.bf16) {
     int mx = 0;
     for (int l = 1; l <= pl.L; ++l) mx = pl.dims[l] > mx ? pl.dims[l] : mx;
-    size_t per = (size_t)((pl.cap + COLSUM_ROWS - 1) / COLSUM_ROWS) * mx;      // standalone column sums
-    for (int l = 1; l < pl.L; ++l) {                                           // backward-epilogue partials
-      // rows of partials per replica: at most ceil(b / 128) * 4 for any tile shape the GEMM may pick
-      // (128-row tiles of 4 wave rows; the other shapes write fewer)
-      const size_t rows = (size_t)((pl.cap + 127) / 128 * 4);
-      per = std::max(per, rows * pl.dims[l]);
+    pl.colpart_per = (size_t)((pl.cap + COLSUM_ROWS - 1) / COLSUM_ROWS) * mx;      // standalone column sums
+    pl.o_colpart = take((size_t)pl.M * pl.colpart_per * 4);
+  }
+  if (c->has_bias && pl.bf16) {
+    for (int l = 1; l <= pl.L; ++l) {
+      // layers below L: partials from the backward epilogue, at most ceil(b / 128) * 4 rows for any tile shape the
+      // GEMM may pick (128-row tiles of 4 wave rows; the other shapes write fewer); layer L: the standalone sums
+      const size_t rows = l < pl.L ? (size_t)((pl.cap + 127) / 128 * 4) : (size_t)((pl.cap + COLSUM_ROWS - 1) / COLSUM_ROWS);
+      pl.colpart_l_per[l] = rows * pl.dims[l];
+      pl.o_colpart_l[l] = take((size_t)pl.M * pl.colpart_l_per[l] * 4);
     }
-    pl.colpart_per = per;
-    pl.o_colpart = take((size_t)pl.M * per * 4);
   }
   pl.o_partials = take((size_t)pl.M * 5 * STATS_PBLK * 8);
   pl.o_stats = take((size_t)pl.M * 8 * 8);
@@ -556,6 +560,9 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   auto act_ptr = [&](size_t off) -> void * { return c->ws + off; };
 
   const bool want_parts = ph.nstats;      // row-norm partials feed S1 only
+  ColFinishMany cf;                       // bias-gradient partials of the layers, finished together (bf16 mode)
+  std::memset(&cf, 0, sizeof(cf));
+  double cf_bytes = 0.0;
   const float inv_b = 1.0f / (float)(ph.b_total > 0 ? ph.b_total : b);
   if (ph.passes) {
     // batch gather (Alg. 1: "sample the local batch")
@@ -615,18 +622,17 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         if (dn_parts[l - 1] > pl.rparts[l - 1]) return cfail(c, ABS_ENOMEM, "row-partial scratch too small for this tile shape");
         if (want_parts) { p.part = c->at<float>(pl.o_dn[l - 1]); p.sPartg = cap * pl.rparts[l - 1]; p.sPartTile = cap; }
         if (hb && ph.wgrad) {
-          p.cpart = c->at<float>(pl.o_colpart);
+          p.cpart = c->at<float>(pl.o_colpart_l[l - 1]);
           p.sCpartg = (long long)gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1];
-          if ((size_t)p.sCpartg > pl.colpart_per) return cfail(c, ABS_ENOMEM, "column-partial scratch too small for this tile shape");
+          if ((size_t)p.sCpartg > pl.colpart_l_per[l - 1]) return cfail(c, ABS_ENOMEM, "column-partial scratch too small for this tile shape");
+          // the partials are added up for all layers at once after the weight gradients
+          const int e = cf.n++;
+          cf.part[e] = p.cpart; cf.cols[e] = pl.dims[l - 1]; cf.nsplit[e] = gemm_bf16_col_parts(b, pl.dims[l - 1], M);
+          gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1], M), &cf.tile_m[e], &cf.parts_per_tile[e]);
+          cf.out_off[e] = pl.offB[l - 1];
+          cf_bytes += 4.0 * M * cf.nsplit[e] * cf.cols[e];
         }
         HIPCHK(c, gemm(c, p, EPI_BWD, l));
-        if (hb && ph.wgrad) {
-          ProfScope ps_(c, T_COLSUM, 0.0, 4.0 * M * gemm_bf16_col_parts(b, pl.dims[l - 1], M) * pl.dims[l - 1]);
-          int tile_m = 0, ppt = 0;
-          gemm_bf16_col_part_shape(gemm_bf16_tile_shape(b, pl.dims[l - 1], M), &tile_m, &ppt);
-          HIPCHK(c, launch_col_sum_finish(p.cpart, pl.dims[l - 1], gemm_bf16_col_parts(b, pl.dims[l - 1], M), M,
-                                          inv_b, grad + pl.offB[l - 1], pl.Ppad, rows, tile_m, ppt, ph.acc_grad ? 1 : 0, s));
-        }
       } else {
         HIPCHK(c, gemm(c, p, EPI_BWD, l));
         if (!want_parts) continue;
@@ -684,11 +690,26 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         HIPCHK(c, launch_splitk_finish(p.kpart, p.ksplit, M, (long long)p.Md * p.Nd, inv_b, rows, static_cast<float *>(p.C),
                                        p.sCg, static_cast<bf16_t *>(p.C2), p.sC2g, p.accumulate, s));
       }
-      if (hb && (!pl.bf16 || l == L)) {   // bf16 mode: layers below L got theirs from the backward epilogue
+      if (hb && !pl.bf16) {
         ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
         HIPCHK(c, launch_col_sum(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, inv_b, grad + pl.offB[l], pl.Ppad,
                                  c->at<float>(pl.o_colpart), rows, ph.acc_grad ? 1 : 0, s));
       }
+      if (hb && pl.bf16 && l == L) {      // bf16 mode: layers below L got their partials from the backward epilogue
+        ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
+        float *scr = c->at<float>(pl.o_colpart_l[L]);
+        const int e = cf.n++;
+        cf.part[e] = scr; cf.cols[e] = pl.dims[L]; cf.nsplit[e] = (b + COLSUM_ROWS - 1) / COLSUM_ROWS;
+        cf.tile_m[e] = 0; cf.parts_per_tile[e] = 0; cf.out_off[e] = pl.offB[L];
+        if ((size_t)cf.nsplit[e] * cf.cols[e] > pl.colpart_l_per[L]) return cfail(c, ABS_ENOMEM, "column-sum scratch too small");
+        cf_bytes += 4.0 * M * cf.nsplit[e] * cf.cols[e];
+        HIPCHK(c, launch_col_sum_partials(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, scr, rows, s));
+      }
+    }
+    if (cf.n > 0) {                        // all bias gradients of the step in one launch
+      ProfScope ps_(c, T_COLSUM, 0.0, cf_bytes);
+      cf.alpha = inv_b; cf.out = grad; cf.sOg = pl.Ppad; cf.rows = rows; cf.accumulate = ph.acc_grad ? 1 : 0;
+      HIPCHK(c, launch_col_sum_finish_many(cf, M, s));
     }
   }
   // inner products <g_i, gbar>

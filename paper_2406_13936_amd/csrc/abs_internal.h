@@ -92,12 +92,25 @@ enum { COLSUM_ROWS = 128 };
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups,
                           int b, float alpha, float *out, long long sOg, float *scratch, const int *rows,
                           int accumulate, hipStream_t s);
-// second stage alone: out[g][j] = alpha * sum_r part[g][r][j], r < nsplit (partials from a GEMM epilogue).
-// With rows: alpha = 1 / rows[g] and only the first ceil(rows[g] / tile_m) * parts_per_tile partials
-// of group g exist.
-hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha,
-                                 float *out, long long sOg, const int *rows, int tile_m, int parts_per_tile,
-                                 int accumulate, hipStream_t s);
+// First stage of launch_col_sum alone (partials into scratch, nsplit = ceil(b / COLSUM_ROWS) rows per group).
+hipError_t launch_col_sum_partials(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
+                                   float *scratch, const int *rows, hipStream_t s);
+// Second stage alone, for several layers in one launch (the bias gradients of a whole step):
+// out[g][out_off_l + j] = alpha * sum_r part_l[g][r][j], r < nsplit_l (partials from a GEMM epilogue or from
+// launch_col_sum_partials).  With rows: alpha = 1 / rows[g] and, where tile_m_l > 0, only the first
+// ceil(rows[g] / tile_m_l) * parts_per_tile_l partials of group g exist.
+struct ColFinishMany {
+  enum { MAXN = 16 };
+  int n;                         // layers
+  const float *part[MAXN];       // partials [groups][nsplit][cols]
+  int cols[MAXN], nsplit[MAXN], tile_m[MAXN], parts_per_tile[MAXN];
+  long long out_off[MAXN];       // offset of the layer's sums inside a group's output vector
+  float alpha;
+  float *out; long long sOg;
+  const int *rows;
+  int accumulate;
+};
+hipError_t launch_col_sum_finish_many(const ColFinishMany &p, int groups, hipStream_t s);
 // q[g][i] += sum_j D[g][i][j] * U[g][i][j]  (fp32 path of the inner products)
 hipError_t launch_rowdot_f32(const float *D, long long sDg, int ldd, const float *U,
                              long long sUg, int ldu, int cols, int groups, int b, float *q,

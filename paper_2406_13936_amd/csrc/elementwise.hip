@@ -228,6 +228,32 @@ __global__ void __launch_bounds__(256) col_sum_stage2(const float *__restrict__ 
   }
 }
 
+__global__ void __launch_bounds__(256) col_sum_stage2_many(const ColFinishMany p) {
+  __shared__ float red[4][64];
+  const int l = blockIdx.z, g = blockIdx.y, cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int cols = p.cols[l];
+  if (blockIdx.x * 64 >= cols) return;             // uniform over the block
+  const int c = blockIdx.x * 64 + cl;
+  int ns = p.nsplit[l];
+  float alpha = p.alpha;
+  if (p.rows) {
+    alpha = 1.0f / (float)p.rows[g];
+    if (p.tile_m[l] > 0) ns = (p.rows[g] + p.tile_m[l] - 1) / p.tile_m[l] * p.parts_per_tile[l];
+  }
+  float s = 0.0f;
+  if (c < cols) {
+    const float *q = p.part[l] + (long long)g * p.nsplit[l] * cols + c;
+    for (int r = rl; r < ns; r += 4) s += q[(long long)r * cols];
+  }
+  red[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && c < cols) {
+    const float t = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
+    float *o = p.out + (long long)g * p.sOg + p.out_off[l] + c;
+    *o = p.accumulate ? fmaf(alpha, t, *o) : alpha * t;
+  }
+}
+
 __global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, int ldd,
                                   const float *__restrict__ U, long long sUg, int ldu, int cols,
                                   int b, float *__restrict__ q, long long sQg, int accumulate,
@@ -686,11 +712,24 @@ hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int
   return hipGetLastError();
 }
 
-hipError_t launch_col_sum_finish(const float *part, int cols, int nsplit, int groups, float alpha, float *out,
-                                 long long sOg, const int *rows, int tile_m, int parts_per_tile, int accumulate,
-                                 hipStream_t s) {
-  hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 63) / 64, groups), dim3(256), 0, s, part, cols, nsplit,
-                     alpha, out, sOg, rows, tile_m, parts_per_tile, accumulate);
+hipError_t launch_col_sum_partials(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
+                                   float *scratch, const int *rows, hipStream_t s) {
+  const int nsplit = (b + COLSUM_ROWS - 1) / COLSUM_ROWS;
+  const dim3 grid((cols + 63) / 64, nsplit, groups), blk(256);
+  if (is_bf16)
+    hipLaunchKernelGGL(col_sum_stage1<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols, b,
+                       scratch, nsplit, rows);
+  else
+    hipLaunchKernelGGL(col_sum_stage1<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
+                       scratch, nsplit, rows);
+  return hipGetLastError();
+}
+
+hipError_t launch_col_sum_finish_many(const ColFinishMany &p, int groups, hipStream_t s) {
+  if (p.n < 1 || p.n > ColFinishMany::MAXN) return hipErrorInvalidValue;
+  int mx = 0;
+  for (int l = 0; l < p.n; ++l) mx = p.cols[l] > mx ? p.cols[l] : mx;
+  hipLaunchKernelGGL(col_sum_stage2_many, dim3((mx + 63) / 64, groups, p.n), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
