@@ -40,8 +40,9 @@ struct Plan {
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
   size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
-  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_kpart = 0, o_idx = 0, o_scal = 0, o_mean = 0;
-  size_t kpart_floats = 0;             // scratch for the partial products of a split weight-gradient reduction
+  size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_idx = 0, o_scal = 0, o_mean = 0;
+  size_t o_kpart_l[MAXL + 1] = {0};    // per layer: partial products of a split weight-gradient reduction
+  size_t kpart_floats_l[MAXL + 1] = {0};
   size_t total = 0;
 };
 
@@ -147,15 +148,14 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
   pl.o_stats = take((size_t)pl.M * 8 * 8);
   pl.o_rows = take((size_t)2 * pl.M * sizeof(int));          // per-group row counts, then the launch order
   pl.o_sqwave = take((size_t)pl.M * (pl.Ppad / 256) * sizeof(float));
-  {
-    // bf16: a split is only taken when the un-split launch has at most 256 tiles, and never makes more than
-    // 512 (tile, slice) pairs of at most 128 x 128 or 256 x 256 outputs each; fp32: at most 8 slices of launches
-    // of fewer than 256 tiles of 64 x 64
-    size_t mx = 0;
-    for (int l = 1; l <= pl.L; ++l) mx = std::max(mx, (size_t)pl.dims[l] * pl.dims[l - 1]);
-    pl.kpart_floats = pl.bf16 ? std::min((size_t)8 * pl.M * mx, (size_t)512 * 65536)
-                              : std::min((size_t)8 * pl.M * mx, (size_t)8 * 256 * 4096);
-    pl.o_kpart = take(pl.kpart_floats * sizeof(float));
+  for (int l = 1; l <= pl.L; ++l) {
+    // one piece per layer, so that one launch can finish the split reductions of all layers.  bf16: a split is
+    // only taken when the un-split launch has at most 256 tiles, and never makes more than 512 (tile, slice) pairs
+    // of at most 128 x 128 or 256 x 256 outputs each; fp32: at most 8 slices of launches of fewer than 256 tiles
+    // of 64 x 64
+    const size_t full = (size_t)8 * pl.M * pl.dims[l] * pl.dims[l - 1];
+    pl.kpart_floats_l[l] = std::min(full, pl.bf16 ? (size_t)512 * 65536 : (size_t)8 * 256 * 4096);
+    pl.o_kpart_l[l] = take(pl.kpart_floats_l[l] * sizeof(float));
   }
   pl.o_cw = take((2 * (size_t)cross_worker_blocks(pl.Ppad) + 8) * 8);
   pl.o_idx = take((size_t)pl.M * pl.cap * sizeof(int32_t));      // inputs of replayed (graph) steps
@@ -563,6 +563,9 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   ColFinishMany cf;                       // bias-gradient partials of the layers, finished together (bf16 mode)
   std::memset(&cf, 0, sizeof(cf));
   double cf_bytes = 0.0;
+  SplitKFinishMany kf;                    // split weight-gradient reductions, finished together
+  std::memset(&kf, 0, sizeof(kf));
+  double kf_bytes = 0.0;
   const float inv_b = 1.0f / (float)(ph.b_total > 0 ? ph.b_total : b);
   if (ph.passes) {
     // batch gather (Alg. 1: "sample the local batch")
@@ -660,14 +663,14 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         int best = 1;
         double best_cost = KT * 2.7;
         for (int S = 2; S <= 8 && blocks < 256; ++S) {
-          if (blocks * S > 1024 || (size_t)S * M * p.Md * p.Nd > pl.kpart_floats) break;
+          if (blocks * S > 1024 || (size_t)S * M * p.Md * p.Nd > pl.kpart_floats_l[l]) break;
           const double cost = ((KT + S - 1) / S) * 2.7 + 8.0;
           if (cost < best_cost) { best = S; best_cost = cost; }
         }
         if (best > 1) {
           p.ksplit = best;
           p.kchunk = ((KT + best - 1) / best) * 32;
-          p.kpart = c->at<float>(pl.o_kpart);
+          p.kpart = c->at<float>(pl.o_kpart_l[l]);
         }
       }
       if (pl.bf16 && p.ldc == p.Nd && (p.Nd & 3) == 0) {
@@ -676,19 +679,19 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         const int sh = gemm_bf16_tile_shape(p.Md, p.Nd, M);
         const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
         const long long tiles = (long long)((p.Md + te - 1) / te) * ((p.Nd + tn_e - 1) / tn_e) * M;
-        const int S = choose_ksplit(sh, tiles, (b + 63) / 64, (double)M * p.Md * p.Nd, pl.kpart_floats);
+        const int S = choose_ksplit(sh, tiles, (b + 63) / 64, (double)M * p.Md * p.Nd, pl.kpart_floats_l[l]);
         if (S > 1) {
           const int KT = (b + 63) / 64;
           p.ksplit = S;
           p.kchunk = ((KT + S - 1) / S) * 64;
-          p.kpart = c->at<float>(pl.o_kpart);
+          p.kpart = c->at<float>(pl.o_kpart_l[l]);
         }
       }
       HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
-      if (p.ksplit > 1) {
-        ProfScope ps_(c, T_COLSUM, 0.0, (4.0 * p.ksplit + 6.0) * M * p.Md * p.Nd);
-        HIPCHK(c, launch_splitk_finish(p.kpart, p.ksplit, M, (long long)p.Md * p.Nd, inv_b, rows, static_cast<float *>(p.C),
-                                       p.sCg, static_cast<bf16_t *>(p.C2), p.sC2g, p.accumulate, s));
+      if (p.ksplit > 1) {                    // its slices are added up after the loop, with those of the other layers
+        const int e = kf.n++;
+        kf.kpart[e] = p.kpart; kf.ksplit[e] = p.ksplit; kf.mn[e] = (long long)p.Md * p.Nd; kf.c_off[e] = pl.offW[l];
+        kf_bytes += (4.0 * p.ksplit + 6.0) * M * p.Md * p.Nd;
       }
       if (hb && !pl.bf16) {
         ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
@@ -705,6 +708,13 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         cf_bytes += 4.0 * M * cf.nsplit[e] * cf.cols[e];
         HIPCHK(c, launch_col_sum_partials(isb, p.A, p.sAg, pl.ld[l], pl.dims[l], M, b, scr, rows, s));
       }
+    }
+    if (kf.n > 0) {                        // all split reductions of the step in one launch
+      ProfScope ps_(c, T_COLSUM, 0.0, kf_bytes);
+      kf.alpha = inv_b; kf.rows = rows; kf.C = grad; kf.sCg = pl.Ppad;
+      kf.C2 = (pl.bf16 && pl.want_ip) ? c->at<bf16_t>(pl.o_gradbf) : nullptr; kf.sC2g = pl.Ppad;
+      kf.accumulate = ph.acc_grad ? 1 : 0;
+      HIPCHK(c, launch_splitk_finish(kf, M, s));
     }
     if (cf.n > 0) {                        // all bias gradients of the step in one launch
       ProfScope ps_(c, T_COLSUM, 0.0, cf_bytes);

@@ -162,10 +162,23 @@ hipError_t launch_cross_worker(const float *g, int groups, long long Ppad, doubl
                                double *out, hipStream_t s);
 hipError_t launch_fill_zero(void *p, long long bytes, hipStream_t s);
 hipError_t launch_zero_range(float *x, long long stride, long long from, long long to, int groups, hipStream_t s);
-// C[g][e] = alpha * sum_sp kpart[(g * ksplit + sp) * mn + e]  (+ C[g][e] if accumulate), slices added in order;
-// C2 (bf16, may be null) gets the rounded result; rows (may be null): alpha = 1 / rows[g].  mn multiple of 4.
-hipError_t launch_splitk_finish(const float *kpart, int ksplit, int groups, long long mn, float alpha, const int *rows,
-                                float *C, long long sCg, bf16_t *C2, long long sC2g, int accumulate, hipStream_t s);
+// Finish of split reductions, the layers of a step in one launch: for layer l and group g
+//   C[g][c_off_l + e] = alpha * sum_sp kpart_l[(g * ksplit_l + sp) * mn_l + e]  (+ the old value if accumulate),
+// slices added in order; C2 (bf16, may be null) gets the rounded result at the same offsets; rows (may be null):
+// alpha = 1 / rows[g].  mn_l and c_off_l are multiples of 4.
+struct SplitKFinishMany {
+  enum { MAXN = 16 };
+  int n;
+  const float *kpart[MAXN];
+  int ksplit[MAXN];
+  long long mn[MAXN], c_off[MAXN];
+  float alpha;
+  const int *rows;
+  float *C; long long sCg;
+  bf16_t *C2; long long sC2g;
+  int accumulate;
+};
+hipError_t launch_splitk_finish(const SplitKFinishMany &p, int groups, hipStream_t s);
 // Inputs of a replayed step: idx_dst[0..n) = idx_src[0..n), scal[0..3) = {lr, c1, c2}
 hipError_t launch_stage_step_inputs(const int32_t *idx_src, int32_t *idx_dst, long long n, float lr, float c1, float c2,
                                     float *scal, hipStream_t s);

@@ -587,28 +587,28 @@ __global__ void __launch_bounds__(256) copy_probe_kernel(const uint4 *__restrict
   if (i < n16) dst[i] = src[i];
 }
 
-__global__ void __launch_bounds__(256) splitk_finish_kernel(const float *__restrict__ kpart, int ksplit, long long mn,
-                                                            float alpha, const int *__restrict__ rows,
-                                                            float *__restrict__ C, long long sCg, bf16_t *__restrict__ C2,
-                                                            long long sC2g, int accumulate) {
-  const int g = blockIdx.y;
-  const long long i = blockIdx.x * 256LL + threadIdx.x;          // float4 index inside the group
+// blockIdx.z = layer; the layers of a step share one launch
+__global__ void __launch_bounds__(256) splitk_finish_kernel(const SplitKFinishMany p) {
+  const int l = blockIdx.z, g = blockIdx.y;
+  const long long mn = p.mn[l];
+  const long long i = blockIdx.x * 256LL + threadIdx.x;          // float4 index inside the group's layer
   if (i * 4 >= mn) return;
-  if (rows) alpha = 1.0f / (float)rows[g];
-  const float *p = kpart + (long long)g * ksplit * mn + i * 4;
-  float4 s = ld_stream(reinterpret_cast<const float4 *>(p));
+  const int ksplit = p.ksplit[l];
+  const float alpha = p.rows ? 1.0f / (float)p.rows[g] : p.alpha;
+  const float *q = p.kpart[l] + (long long)g * ksplit * mn + i * 4;
+  float4 s = ld_stream(reinterpret_cast<const float4 *>(q));
   for (int sp = 1; sp < ksplit; ++sp) {
-    const float4 v = ld_stream(reinterpret_cast<const float4 *>(p + (long long)sp * mn));
+    const float4 v = ld_stream(reinterpret_cast<const float4 *>(q + (long long)sp * mn));
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
-  float4 *c = reinterpret_cast<float4 *>(C + (long long)g * sCg) + i;
-  if (accumulate) { const float4 o = *c; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
+  float4 *c = reinterpret_cast<float4 *>(p.C + (long long)g * p.sCg + p.c_off[l]) + i;
+  if (p.accumulate) { const float4 o = *c; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
   *c = s;
-  if (C2) {
+  if (p.C2) {
     uint2 o;
     o.x = pack2bf(s.x, s.y); o.y = pack2bf(s.z, s.w);
-    reinterpret_cast<uint2 *>(C2 + (long long)g * sC2g)[i] = o;
+    reinterpret_cast<uint2 *>(p.C2 + (long long)g * p.sC2g + p.c_off[l])[i] = o;
   }
 }
 
@@ -830,11 +830,14 @@ hipError_t launch_copy_probe(const void *src, void *dst, long long bytes, hipStr
   return hipGetLastError();
 }
 
-hipError_t launch_splitk_finish(const float *kpart, int ksplit, int groups, long long mn, float alpha, const int *rows,
-                                float *C, long long sCg, bf16_t *C2, long long sC2g, int accumulate, hipStream_t s) {
-  if (mn & 3) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((mn / 4 + 255) / 256), groups), dim3(256), 0, s, kpart, ksplit,
-                     mn, alpha, rows, C, sCg, C2, sC2g, accumulate);
+hipError_t launch_splitk_finish(const SplitKFinishMany &p, int groups, hipStream_t s) {
+  if (p.n < 1 || p.n > SplitKFinishMany::MAXN) return hipErrorInvalidValue;
+  long long mx = 0;
+  for (int l = 0; l < p.n; ++l) {
+    if ((p.mn[l] & 3) || (p.c_off[l] & 3) || p.ksplit[l] < 1 || !p.kpart[l]) return hipErrorInvalidValue;
+    mx = p.mn[l] > mx ? p.mn[l] : mx;
+  }
+  hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((mx / 4 + 255) / 256), groups, p.n), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
