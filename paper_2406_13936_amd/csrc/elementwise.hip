@@ -178,27 +178,33 @@ __global__ void row_sqnorm_kernel(const T *__restrict__ X, long long sXg, int ld
   if (lane == 0) out[(long long)g * sOg + i] = s;
 }
 
-// Column sums in two fixed-order stages.  Stage 1: a block owns 64 columns x COLSUM_ROWS rows
-// (4 row-lanes striding over them, added in lane order) and writes one partial per column;
-// stage 2 adds the partials of all row-blocks in index order and scales.
-template <class T>
+// Column sums in two fixed-order stages.  Stage 1: a block owns CL columns x COLSUM_ROWS rows
+// (256 / CL row-lanes striding over them, added in lane order) and writes one partial per column;
+// stage 2 adds the partials of all row-blocks in index order and scales.  CL = 64, or 16 for narrow
+// matrices (the signals of a small last layer), where more row-lanes shorten each lane's serial walk.
+template <class T, int CL>
 __global__ void __launch_bounds__(256) col_sum_stage1(const T *__restrict__ X, long long sXg, int ld, int cols,
                                                       int b, float *__restrict__ part, int nsplit,
                                                       const int *__restrict__ rows) {
-  __shared__ float red[4][64];
+  constexpr int RL = 256 / CL;
+  __shared__ float red[RL][CL];
   const int g = blockIdx.z, rs = blockIdx.y;
-  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl;
+  const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
+  const int c = blockIdx.x * CL + cl;
   const int r0 = rs * COLSUM_ROWS, r1 = min(rows ? rows[g] : b, r0 + COLSUM_ROWS);
   float s = 0.0f;
   if (c < cols) {
     const T *p = X + (long long)g * sXg + c;
-    for (int i = r0 + rl; i < r1; i += 4) s += Elem<T>::ld(p + (long long)i * ld);
+    for (int i = r0 + rl; i < r1; i += RL) s += Elem<T>::ld(p + (long long)i * ld);
   }
   red[rl][cl] = s;
   __syncthreads();
-  if (rl == 0 && c < cols)
-    part[((long long)g * nsplit + rs) * cols + c] = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
+  if (rl == 0 && c < cols) {
+    float t = red[0][cl];
+#pragma unroll
+    for (int k = 1; k < RL; ++k) t += red[k][cl];
+    part[((long long)g * nsplit + rs) * cols + c] = t;
+  }
 }
 // Stage 2: a block owns 64 columns; its four row-lanes add the partials r = lane, lane + 4, ... in that
 // order and the four sums are combined in lane order.
@@ -695,17 +701,33 @@ hipError_t launch_row_sqnorm(int is_bf16, const void *X, long long sXg, int ld, 
   return hipGetLastError();
 }
 
+static void launch_col_sum_stage1(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
+                                  float *scratch, int nsplit, const int *rows, hipStream_t s) {
+  const dim3 blk(256);
+  if (cols <= 16) {
+    const dim3 grid((cols + 15) / 16, nsplit, groups);
+    if (is_bf16)
+      hipLaunchKernelGGL((col_sum_stage1<bf16_t, 16>), grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols, b,
+                         scratch, nsplit, rows);
+    else
+      hipLaunchKernelGGL((col_sum_stage1<float, 16>), grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
+                         scratch, nsplit, rows);
+    return;
+  }
+  const dim3 grid((cols + 63) / 64, nsplit, groups);
+  if (is_bf16)
+    hipLaunchKernelGGL((col_sum_stage1<bf16_t, 64>), grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols, b,
+                       scratch, nsplit, rows);
+  else
+    hipLaunchKernelGGL((col_sum_stage1<float, 64>), grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
+                       scratch, nsplit, rows);
+}
+
 hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
                           float alpha, float *out, long long sOg, float *scratch, const int *rows, int accumulate,
                           hipStream_t s) {
   const int nsplit = (b + COLSUM_ROWS - 1) / COLSUM_ROWS;
-  const dim3 grid((cols + 63) / 64, nsplit, groups), blk(256);
-  if (is_bf16)
-    hipLaunchKernelGGL(col_sum_stage1<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols, b,
-                       scratch, nsplit, rows);
-  else
-    hipLaunchKernelGGL(col_sum_stage1<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
-                       scratch, nsplit, rows);
+  launch_col_sum_stage1(is_bf16, X, sXg, ld, cols, groups, b, scratch, nsplit, rows, s);
   // stage 1 writes every partial (zeros past a group's rows), so stage 2 adds all of them
   hipLaunchKernelGGL(col_sum_stage2, dim3((cols + 63) / 64, groups), dim3(256), 0, s, scratch, cols, nsplit,
                      alpha, out, sOg, rows, 0, 0, accumulate);
@@ -715,13 +737,7 @@ hipError_t launch_col_sum(int is_bf16, const void *X, long long sXg, int ld, int
 hipError_t launch_col_sum_partials(int is_bf16, const void *X, long long sXg, int ld, int cols, int groups, int b,
                                    float *scratch, const int *rows, hipStream_t s) {
   const int nsplit = (b + COLSUM_ROWS - 1) / COLSUM_ROWS;
-  const dim3 grid((cols + 63) / 64, nsplit, groups), blk(256);
-  if (is_bf16)
-    hipLaunchKernelGGL(col_sum_stage1<bf16_t>, grid, blk, 0, s, static_cast<const bf16_t *>(X), sXg, ld, cols, b,
-                       scratch, nsplit, rows);
-  else
-    hipLaunchKernelGGL(col_sum_stage1<float>, grid, blk, 0, s, static_cast<const float *>(X), sXg, ld, cols, b,
-                       scratch, nsplit, rows);
+  launch_col_sum_stage1(is_bf16, X, sXg, ld, cols, groups, b, scratch, nsplit, rows, s);
   return hipGetLastError();
 }
 
