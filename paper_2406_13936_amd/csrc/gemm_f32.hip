@@ -2,24 +2,26 @@
 //   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k]
 // with the same operand-layout flags and epilogues as the bf16 matrix-core family.  The fp32
 // mode serves small, latency-bound problems (logistic regression), so this kernel favours
-// generality (arbitrary strides and extents) over peak rate: 64x64 block tile, k-step 32,
-// 256 threads, 4x4 outputs per thread; the next k-step's operands are fetched into registers
-// while the current one is multiplied (the loop is bound by load latency, not by arithmetic).
+// generality (arbitrary strides and extents) over peak rate: TS x TS block tile (64, or 32 when
+// the output has few tiles, so that more work-groups share the latency-bound walk over k),
+// k-step 32, 256 threads, (TS/16)^2 outputs per thread; the next k-step's operands are fetched
+// into registers while the current one is multiplied.
 #include "abs_internal.h"
 #include "device_utils.h"
 
 namespace absk {
 namespace {
 
-template <int EPI, int ACT>
+template <int EPI, int ACT, int TS>
 __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
-  constexpr int BK = 32, PT = 64 * BK / 256;     // k-step, elements per thread and operand
-  __shared__ float As[BK][68];
-  __shared__ float Bs[BK][68];
+  constexpr int BK = 32, PT = TS * BK / 256;     // k-step, elements per thread and operand
+  constexpr int R = TS / 16;                     // outputs per thread and dimension
+  __shared__ float As[BK][TS + 4];
+  __shared__ float Bs[BK][TS + 4];
   // blockIdx.z = group, or (group, k-slice) of a weight gradient whose reduction is split
   const int ksplit = (EPI == EPI_WGRAD && pin.ksplit > 1) ? pin.ksplit : 1;
   const int g = blockIdx.z / ksplit, ksl = blockIdx.z - g * ksplit;
-  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int m0 = blockIdx.y * TS, n0 = blockIdx.x * TS;
   GemmP p = pin;
   if (p.rows) {                                   // ragged groups: this group's own extent
     const int r = p.rows[g];
@@ -36,11 +38,11 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const float *A = static_cast<const float *>(p.A) + (long long)g * p.sAg;
   const float *B = static_cast<const float *>(p.B) + (long long)g * p.sBg;
-  float acc[4][4];
+  float acc[R][R];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < R; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
+    for (int j = 0; j < R; ++j) acc[i][j] = 0.0f;
 
   float ra[PT], rb[PT];
   auto fetch = [&](int k0) {
@@ -48,11 +50,11 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
     for (int e = 0; e < PT; ++e) {
       const int id = tid + e * 256;
       int kk, rr;
-      if (!p.a_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
+      if (!p.a_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id % TS; kk = id / TS; }
       const int m = m0 + rr, k = k0 + kk;
       ra[e] = 0.0f;
       if (m < p.Md && k < p.Kd) ra[e] = p.a_trans ? A[(long long)k * p.lda + m] : A[(long long)m * p.lda + k];
-      if (!p.b_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
+      if (!p.b_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id % TS; kk = id / TS; }
       const int n = n0 + rr, kb = k0 + kk;
       rb[e] = 0.0f;
       if (n < p.Nd && kb < p.Kd) rb[e] = p.b_trans ? B[(long long)kb * p.ldb + n] : B[(long long)n * p.ldb + kb];
@@ -64,36 +66,36 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmP pin) {
     for (int e = 0; e < PT; ++e) {
       const int id = tid + e * 256;
       int kk, rr;
-      if (!p.a_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
+      if (!p.a_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id % TS; kk = id / TS; }
       As[kk][rr] = ra[e];
-      if (!p.b_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id & 63; kk = id >> 6; }
+      if (!p.b_trans) { kk = id & (BK - 1); rr = id / BK; } else { rr = id % TS; kk = id / TS; }
       Bs[kk][rr] = rb[e];
     }
     __syncthreads();
     if (k0 + BK < p.Kd) fetch(k0 + BK);
 #pragma unroll
     for (int kk = 0; kk < BK; ++kk) {
-      float a[4], b[4];
+      float a[R], b[R];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+      for (int i = 0; i < R; ++i) a[i] = As[kk][ty * R + i];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+      for (int j = 0; j < R; ++j) b[j] = Bs[kk][tx * R + j];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < R; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        for (int j = 0; j < R; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
     }
     __syncthreads();
   }
 
   const float *bias = p.bias ? p.bias + (long long)g * p.sBiasg : nullptr;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + ty * 4 + i;
+  for (int i = 0; i < R; ++i) {
+    const int m = m0 + ty * R + i;
     if (m >= p.Md) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = n0 + tx * 4 + j;
+    for (int j = 0; j < R; ++j) {
+      const int n = n0 + tx * R + j;
       const bool nin = n < p.Nd;
       const float v = acc[i][j];
       const float bv = (bias && nin) ? bias[n] : 0.0f;
@@ -133,9 +135,13 @@ template <int EPI, int ACT>
 hipError_t launch1(const GemmP &p, hipStream_t s) {
   const int ks = (EPI == EPI_WGRAD && p.ksplit > 1) ? p.ksplit : 1;
   if (ks > 1 && (!p.kpart || p.kchunk <= 0 || (p.kchunk & 31) || (long long)p.kchunk * ks < p.Kd)) return hipErrorInvalidValue;
-  const dim3 grid((p.Nd + 63) / 64, (p.Md + 63) / 64, p.groups * ks);
+  // 32 x 32 tiles while 64 x 64 ones would leave most CUs without a work-group
+  const long long blocks64 = (long long)((p.Nd + 63) / 64) * ((p.Md + 63) / 64) * p.groups * ks;
+  const int ts = blocks64 < 128 ? 32 : 64;
+  const dim3 grid((p.Nd + ts - 1) / ts, (p.Md + ts - 1) / ts, p.groups * ks);
   if (grid.y > 65535 || grid.z > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((gemm_f32_kernel<EPI, ACT>), grid, dim3(256), 0, s, p);
+  if (ts == 32) hipLaunchKernelGGL((gemm_f32_kernel<EPI, ACT, 32>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((gemm_f32_kernel<EPI, ACT, 64>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
 template <int EPI>
