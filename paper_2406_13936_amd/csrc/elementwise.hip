@@ -283,6 +283,30 @@ __global__ void rowdot_f32_kernel(const float *__restrict__ D, long long sDg, in
 // Stage 1a (grid: PBLK x groups): per-sample squared gradient norms
 //   n_i = sum_l ||delta_i^l||^2 (||a_i^{l-1}||^2 + [bias])   and   q_i = sum_l sum_parts ...
 // with block partial sums of n_i, q_i, q_i^2 and the loss, in double.
+// s = (((s0 + base[0]) + base[stride]) + base[2 stride]) + ... over n entries: the additions keep their order, the
+// loads go out eight at a time (one at a time, n dependent round trips to memory dominate the kernel).
+__device__ __forceinline__ float sum_strided(float s0, const float *__restrict__ base, int n, long long stride) {
+  float s = s0;
+  int k = 0;
+  for (; k + 8 <= n; k += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = base[(long long)(k + u) * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  if (k + 4 <= n) {
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = base[(long long)(k + u) * stride];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s += v[u];
+    k += 4;
+  }
+  for (; k < n; ++k) s += base[(long long)k * stride];
+  return s;
+}
+
 // Blocks 0 .. nb-1 of a group share its samples (block j owns samples 256 j + t, then strides of 256 nb);
 // the launch uses nb = min(PBLK, ceil(b / 256)) blocks and stage 2 takes the other partials as zero.
 __device__ __forceinline__ void stats_samples_block(const StatsP &p, int g, int blk, int nb, double *red) {
@@ -294,9 +318,8 @@ __device__ __forceinline__ void stats_samples_block(const StatsP &p, int g, int 
     if (p.do_n) {
       float n = 0.0f;
       for (int l = 0; l < p.L; ++l) {
-        float a = 0.0f, d = 0.0f;
-        for (int k = 0; k < p.an_parts[l]; ++k) a += p.an[l][(long long)g * p.an_sg[l] + (long long)k * p.sNg + i];
-        for (int k = 0; k < p.dn_parts[l]; ++k) d += p.dn[l][(long long)g * p.dn_sg[l] + (long long)k * p.sNg + i];
+        const float a = sum_strided(0.0f, p.an[l] + (long long)g * p.an_sg[l] + i, p.an_parts[l], p.sNg);
+        const float d = sum_strided(0.0f, p.dn[l] + (long long)g * p.dn_sg[l] + i, p.dn_parts[l], p.sNg);
         n = fmaf(d, a + hb, n);
       }
       if (p.n_out) p.n_out[o] = n;
@@ -306,8 +329,7 @@ __device__ __forceinline__ void stats_samples_block(const StatsP &p, int g, int 
     if (p.do_q) {
       float q = 0.0f;
       for (int l = 0; l < p.L; ++l) {
-        const float *qp = p.qpart[l] + (long long)g * p.sQg[l] + i;
-        for (int k = 0; k < p.nparts[l]; ++k) q += qp[(long long)k * p.sQpart[l]];
+        q = sum_strided(q, p.qpart[l] + (long long)g * p.sQg[l] + i, p.nparts[l], p.sQpart[l]);
       }
       if (p.q_out) p.q_out[o] = q;
       s4 += (double)q;
