@@ -652,11 +652,11 @@ hipError_t launch_shape(const GemmP &p, hipStream_t s) {
     case 2: return launch_cfg<256, 256, 64, 2, 4, 2, AT, BT, EPI, ACT>(p, s);
     default: {
       // Two stages (64 KB) let two work-groups share a CU, three keep one work-group fed through a long
-      // reduction.  Two when the reduction is short, and for a weight gradient whose launch has more blocks
-      // than CUs (a split reduction, usually); three otherwise.
-      long long nblk = 0;
-      if (EPI == EPI_WGRAD)
-        nblk = (long long)((p.Md + 127) / 128) * ((p.Nd + 127) / 128) * p.groups * (p.ksplit > 1 ? p.ksplit : 1);
+      // reduction.  Two when the reduction is short or the launch has more blocks than CUs (measured: 2048-wide
+      // layers at b = 256, 512 blocks: 43 against 62 us; 1024 blocks of a 100-wide output: 145 against 163 us;
+      // 256 blocks: three stages win); three otherwise.
+      const long long nblk = (long long)((p.Md + 127) / 128) * ((p.Nd + 127) / 128) * p.groups *
+                             ((EPI == EPI_WGRAD && p.ksplit > 1) ? p.ksplit : 1);
       if (p.Kd <= 1024 || nblk > 256) return launch_cfg<128, 128, 64, 2, 2, 2, AT, BT, EPI, ACT>(p, s);
       return launch_cfg<128, 128, 64, 2, 2, 3, AT, BT, EPI, ACT>(p, s);
     }
@@ -680,10 +680,13 @@ hipError_t launch_act(const GemmP &p, hipStream_t s) {
 int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
   if (Nd <= 64) return 0;
   if (Md >= 1024 && Nd >= 1024) return 2;
-  // mid-sized outputs: the large tile only if it still gives every CU a work-group
-  if (Md >= 512 && Nd >= 512) {
-    const long long tiles = (long long)((Md + 255) / 256) * ((Nd + 255) / 256) * groups;
-    if (tiles >= 256) return 2;
+  // mid-sized outputs: the large tile only if it still gives every CU a work-group and its last row of tiles is
+  // not mostly padding (measured on 2048-wide layers, 16 groups: b = 384 and 512 faster with 256 x 256 tiles,
+  // b = 256 with two 128 x 128 work-groups per CU)
+  if (Md >= 256 && Nd >= 512) {
+    const long long tm = (Md + 255) / 256;
+    const long long tiles = tm * ((Nd + 255) / 256) * groups;
+    if (tiles >= 256 && 10LL * Md >= 7LL * tm * 256) return 2;
   }
   return 1;
 }
