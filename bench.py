@@ -147,11 +147,10 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     b_fixed = a.batch or w.b_cap
 
     def test_and_rule(b):
+        # abs_norm_test / abs_inner_product_test, then abs_next_batch_size (max over the workers)
         if w.test == W.TEST_NORM:
-            res = rep.norm_test(w.eta)
-        else:
-            res = rep.inner_product_test(w.theta, w.nu if w.test == W.TEST_AUG_IP else 0.0)
-        return A.next_batch_size(res, [b] * w.M, w.b_cap, True)[0]
+            return rep.test_and_next_batch_size(b, w.b_cap, eta=w.eta)[0]
+        return rep.test_and_next_batch_size(b, w.b_cap, theta=w.theta, nu=w.nu if w.test == W.TEST_AUG_IP else 0.0)[0]
 
     # pre-stage every index batch in HBM
     total = a.warmup + a.steps

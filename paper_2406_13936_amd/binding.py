@@ -247,6 +247,26 @@ class Replicas:
         _check(self._lib.abs_inner_product_test(self._ctx, float(theta), float(nu), out), self._ctx)
         return list(out)
 
+    def test_and_next_batch_size(self, b_cur: int, b_cap: int, eta: float = 0.0, theta: float = 0.0, nu: float = 0.0,
+                                 sync_max: bool = True) -> List[int]:
+        """The batch test of the last step followed by the batch-size rule, for tight loops: the same two library
+        calls as norm_test / inner_product_test + next_batch_size, on argument arrays that are kept between calls
+        (theta > 0 selects the inner-product test, augmented when nu > 0; otherwise the norm test with eta).  The
+        test results of the call stay readable in `self.last_results`."""
+        M = self.M
+        if getattr(self, "_loop_args", None) is None:
+            self._loop_args = ((TestResult * M)(), (C.c_int * M)(), (C.c_int * M)())
+        out, cur, nxt = self._loop_args
+        if theta > 0.0:
+            _check(self._lib.abs_inner_product_test(self._ctx, theta, nu, out), self._ctx)
+        else:
+            _check(self._lib.abs_norm_test(self._ctx, eta, out), self._ctx)
+        for m in range(M):
+            cur[m] = b_cur
+        _check(self._lib.abs_next_batch_size(out, M, cur, b_cap, 1 if sync_max else 0, nxt))
+        self.last_results = out
+        return nxt
+
     def cross_worker_test(self, eta: float) -> TestResult:
         out = TestResult()
         _check(self._lib.abs_cross_worker_test(self._ctx, float(eta), C.byref(out)), self._ctx)

@@ -621,6 +621,27 @@ def test_identical_samples_give_zero_variance_and_smallest_batch():
         rep.close()
 
 
+def test_loop_binding_makes_the_same_two_calls():
+    """`test_and_next_batch_size` (kept argument arrays, for tight loops) returns what the test call followed by
+    the rule call return, for the norm test and for the augmented inner-product test."""
+    A = _A()
+    w = _one_step_case((72, 40, 6), W.ACT_RELU, W.PREC_F32, 48, 3, test=W.TEST_AUG_IP)
+    X, y = W.make_dataset(w)
+    rep = A.Replicas.from_workload(w, X, y, W.make_x0(w))
+    try:
+        rep.local_step(W.step_indices(w, 0, 0, 48), w.lr)
+        for kw, res in (({"eta": 0.3}, rep.norm_test(0.3)),
+                        ({"theta": 0.9, "nu": 0.5}, rep.inner_product_test(0.9, 0.5)),
+                        ({"theta": 0.9}, rep.inner_product_test(0.9))):
+            want = A.next_batch_size(res, [48] * w.M, 4096, True)
+            got = list(rep.test_and_next_batch_size(48, 4096, **kw))
+            assert got == want
+            assert [r.T for r in rep.last_results] == [r.T for r in res]
+            assert [r.ratio for r in rep.last_results] == [r.ratio for r in res]
+    finally:
+        rep.close()
+
+
 @pytest.mark.parametrize("prec", [W.PREC_F32, W.PREC_BF16])
 def test_zero_batch_gradient_keeps_the_batch_size(prec):
     """All-zero inputs and no biases: every per-sample gradient is zero, so S1 = S2 = 0; the rule then leaves the
