@@ -299,14 +299,6 @@ def test_bf16_rounding_against_known_values_and_torch():
     np.testing.assert_array_equal(f(v.astype(np.float64)), want)
 
 
-def test_mixed_mode_stays_close_to_exact():
-    net, x, Xb, yb = _tiny((32, 24, 16, 5), O.ACT_GELU, True, b=40, seed=17)
-    ex = O.stats_factored(net, O.backprop(net, x, Xb, yb), True)
-    mx = O.stats_factored(net, O.backprop(net, x, Xb, yb, mixed=True), True, mixed=True)
-    for key in ("S1", "S2", "S3", "S4"):
-        assert mx[key] == pytest.approx(ex[key], rel=2e-2), key
-
-
 def test_adagrad_closed_forms():
     # first step: x - lr g / (|g| + eps); two steps by hand on a scalar
     rng = np.random.default_rng(18)
