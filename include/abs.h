@@ -206,10 +206,21 @@ abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_c
  * Only the parameters are averaged; optimizer state stays local. */
 abs_status abs_average_replicas(abs_ctx *ctx);
 
+/*
+ * Counters of Alg. 1: rounds = k, the communication rounds completed (one per abs_average_replicas,
+ * "k <- k + 1"); local_steps = optimizer steps taken by every worker; samples = B, the local batch
+ * sizes actually used, summed over workers and local steps ("B <- B + sum_m sum_h b^m").
+ * Host integers kept by the context; no GPU call, no synchronisation.  Any out pointer may be NULL.
+ */
+abs_status abs_get_counters(const abs_ctx *ctx, long long *rounds, long long *local_steps, long long *samples);
+
 /* Parity helpers (synchronising).  m in [0, M); buffers are host, n_params floats. */
 abs_status abs_get_params(abs_ctx *ctx, int m, float *out_host);
 abs_status abs_set_params(abs_ctx *ctx, int m, const float *in_host);
 abs_status abs_get_grad(abs_ctx *ctx, int m, float *out_host);    /* last local batch gradient */
+/* Optimizer state of worker m (local to a worker, never averaged: "synchronizing only the models", Sec. 6):
+ * which = 0: heavy-ball buffer v / AdamW second moment / AdaGrad accumulator; which = 1: AdamW first moment. */
+abs_status abs_get_opt_state(abs_ctx *ctx, int m, int which, float *out_host);
 /* Per-sample ||g_i||^2 (and <g_i,gbar> if gathered; else q_host may be NULL) of worker m
  * for the most recent step: host, b floats each (b^m after a ragged step; see
  * abs_local_step_accumulated for what an accumulated step keeps). */

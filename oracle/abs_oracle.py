@@ -175,12 +175,20 @@ def backprop(net: Net, x: np.ndarray, Xb: np.ndarray, yb: np.ndarray,
     for l in range(net.L - 1, 0, -1):
         W = rnd(params[l][0])
         delta[l - 1] = rnd((delta[l] @ W) * dact[l - 1])
+    return {"a": a, "delta": delta, "loss": loss, "G": layer_gradients(a, delta, net.has_bias)}
+
+
+def layer_gradients(a, delta, has_bias: bool):
+    """Local batch gradient, eq. (batch_grad), layer by layer from the layer inputs a[l] [b, in_l] and the
+    per-sample signals delta[l] [b, out_l]: the mean over the batch of the per-sample gradients
+    delta_i^l a_i^{l-1 T} (and delta_i^l for the bias)."""
+    b = a[0].shape[0]
     G = []
-    for l in range(net.L):
-        Gl = (delta[l].T @ a[l]) / b
-        bl = delta[l].sum(axis=0) / b if net.has_bias else None
+    for al, dl in zip(a, delta):
+        Gl = (dl.T @ al) / b
+        bl = dl.sum(axis=0) / b if has_bias else None
         G.append((Gl, bl))
-    return {"a": a, "delta": delta, "loss": loss, "G": G}
+    return G
 
 
 def batch_gradient(net: Net, x, Xb, yb, mixed=False) -> np.ndarray:
@@ -436,6 +444,25 @@ class Replicas:
 
     def average(self):
         self.x = average(self.x)
+
+
+def run_alg2(net: Net, x0, X, y, M: int, H: int, rounds: int, b0: int, cap: int, lr: float,
+             idx_fn: Callable[[int, int, int], np.ndarray], eta=0.5, mixed=False, **opt_kw):
+    """Alg. 2 for a fixed number of rounds: H local steps at one batch size b_k for every worker, then the
+    model average, then ONE test per round from the M local batch gradients of the round's last local step
+    (cross_worker_test), b_{k+1} = max(T, b_k) (never above `cap`), and B grows by H M b_k.
+    idx_fn(k, h, b) -> int [M, b].  Returns (final parameters [M, P], schedule [(k, b_k, T)], samples)."""
+    rep = Replicas(net, x0, X, y, M, mixed=mixed, **opt_kw)
+    b, B, sched = int(b0), 0, []
+    for k in range(rounds):
+        for h in range(H):
+            rep.local_step(idx_fn(k, h, b), lr)
+        rep.average()
+        r = cross_worker_test(rep.grads, b, eta)
+        sched.append((k, b, r["T"]))
+        B += H * M * b
+        b = min(int(cap), max(int(r["T"]), b))
+    return rep.x, sched, B
 
 
 def run(net: Net, x0, X, y, M: int, H: int, rounds: int, b0: int, cap: int,

@@ -27,6 +27,7 @@ EXPORTS = [
     "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
     "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
     "abs_local_step_accumulated", "abs_profile_pause", "abs_local_step_graphed", "abs_graph_count",
+    "abs_get_counters", "abs_get_opt_state",
 ]
 
 
@@ -85,6 +86,9 @@ def load_library(reload: bool = False):
     lib.abs_get_params.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
     lib.abs_set_params.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
     lib.abs_get_grad.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+    lib.abs_get_counters.argtypes = [C.c_void_p, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong),
+                                     C.POINTER(C.c_longlong)]
+    lib.abs_get_opt_state.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.abs_get_per_sample.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     lib.abs_n_params.argtypes = [C.POINTER(_Config), C.POINTER(C.c_int64)]
     lib.abs_layer_stats.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int, C.c_int,
@@ -290,6 +294,17 @@ class Replicas:
         out = np.empty(self.n_params, dtype=np.float32)
         _check(self._lib.abs_get_grad(self._ctx, int(m), out.ctypes.data), self._ctx)
         return out
+
+    def get_opt_state(self, m: int, which: int = 0) -> np.ndarray:
+        out = np.empty(self.n_params, dtype=np.float32)
+        _check(self._lib.abs_get_opt_state(self._ctx, int(m), int(which), out.ctypes.data), self._ctx)
+        return out
+
+    def counters(self):
+        """(rounds k, local steps, samples B) of Alg. 1 as kept by the library."""
+        k, h, B = C.c_longlong(0), C.c_longlong(0), C.c_longlong(0)
+        _check(self._lib.abs_get_counters(self._ctx, C.byref(k), C.byref(h), C.byref(B)), self._ctx)
+        return k.value, h.value, B.value
 
     def get_per_sample(self, m: int, b: int, want_q: bool = False):
         n = np.empty(b, dtype=np.float32)

@@ -209,7 +209,8 @@ static const char *const kTagNames[T_GEMM0 + T_GEMM_KINDS] = {
 struct ProfRec { int tag; hipEvent_t e0, e1; double flops, bytes; };
 
 struct abs_ctx {
-  bool prof_on = false;
+  bool prof_on = false;            // launches are being bracketed right now
+  bool prof_enabled = false;       // abs_profile_enable(1) is in force (abs_profile_pause toggles prof_on under it)
   std::vector<ProfRec> prof_recs;      // event pool, reused
   size_t prof_used = 0;
   double prof_ms[T_COUNT] = {0}, prof_flops[T_COUNT] = {0}, prof_bytes[T_COUNT] = {0};
@@ -224,6 +225,8 @@ struct abs_ctx {
   double *host_stats = nullptr;     // pinned, M*8 + 8 doubles
   double *host_stats_dev = nullptr; // the same memory as the device sees it (the statistics kernel writes there)
   long long t = 0;                  // local steps taken (Adam bias correction)
+  long long n_rounds = 0;           // Alg. 1's k: communication rounds completed (model averages)
+  long long n_samples = 0;          // Alg. 1's B: samples processed, summed over workers and local steps
   int last_b = 0;                 // largest local batch size of the last step
   std::vector<int> last_bm;       // per worker
   int last_ps = -1;               // per-sample outputs stored (accumulated steps; -1: all of them)
@@ -285,7 +288,8 @@ struct ProfScope {
     if (!c->prof_on) return;
     if (c->prof_used == c->prof_recs.size()) {
       ProfRec n{};
-      if (hipEventCreate(&n.e0) != hipSuccess || hipEventCreate(&n.e1) != hipSuccess) return;
+      if (hipEventCreate(&n.e0) != hipSuccess) return;
+      if (hipEventCreate(&n.e1) != hipSuccess) { (void)hipEventDestroy(n.e0); return; }
       c->prof_recs.push_back(n);
     }
     r = &c->prof_recs[c->prof_used++];
@@ -452,7 +456,7 @@ abs_status abs_destroy(abs_ctx *c) try {
 abs_status abs_profile_enable(abs_ctx *c, int on) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   HIPCHK(c, hipStreamSynchronize(c->stream));
-  c->prof_on = on != 0;
+  c->prof_on = c->prof_enabled = on != 0;
   c->prof_used = 0;
   for (int t = 0; t < T_COUNT; ++t) { c->prof_ms[t] = c->prof_flops[t] = c->prof_bytes[t] = 0.0; c->prof_calls[t] = 0; }
   return ABS_OK;
@@ -460,7 +464,7 @@ abs_status abs_profile_enable(abs_ctx *c, int on) try {
 
 abs_status abs_profile_pause(abs_ctx *c, int paused) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
-  c->prof_on = paused == 0;       // no synchronisation, totals and pending records are kept
+  c->prof_on = c->prof_enabled && paused == 0;   // no synchronisation, totals and pending records are kept
   return ABS_OK;
 } catch (...) { return on_exception(); }
 
@@ -500,6 +504,7 @@ static void note_step(abs_ctx *c, int b, const int *b_host) {
   c->last_ragged = b_host != nullptr;
   c->last_ps = -1;
   c->have_stats = true;
+  for (int m = 0; m < c->pl.M; ++m) c->n_samples += c->last_bm[m];      // Alg. 1: B <- B + sum_m b^m
 }
 
 // Which parts of the step one call of local_step_impl runs.  A plain step runs all of them once;
@@ -842,7 +847,10 @@ abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, flo
   float *scal = c->at<float>(pl.o_scal);
   ph.scal = scal;
   // the only launch whose arguments change from step to step: it carries them into fixed device locations
-  HIPCHK(c, launch_stage_step_inputs(idx_dev, idx_in, (long long)pl.M * b, lr, ph.c1, ph.c2, scal, c->stream));
+  {
+    hipError_t e = launch_stage_step_inputs(idx_dev, idx_in, (long long)pl.M * b, lr, ph.c1, ph.c2, scal, c->stream);
+    if (e != hipSuccess) return settle_update(c, cfail(c, ABS_EHIP, std::string("launch_stage_step_inputs: ") + hipGetErrorString(e)));
+  }
   abs_ctx::GraphSlot *slot = nullptr;
   for (auto &g : c->graphs) if (g.b == b) slot = &g;
   if (!slot) {
@@ -852,18 +860,23 @@ abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, flo
       // first step at this batch size: run it directly, which also sets the attributes of every kernel
       // variant this size uses (not something to do inside a capture)
       c->graph_warm.push_back(b);
-      return local_step_impl(c, idx_in, b, b, nullptr, lr, ph);
+      return settle_update(c, local_step_impl(c, idx_in, b, b, nullptr, lr, ph));
     }
     hipGraph_t graph = nullptr;
-    HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+    {
+      hipError_t eb = hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal);
+      if (eb != hipSuccess) return settle_update(c, cfail(c, ABS_EHIP, std::string("hipStreamBeginCapture: ") + hipGetErrorString(eb)));
+    }
+    const long long samples_before = c->n_samples;     // the captured pass only records launches: it is not a step
     abs_status st = local_step_impl(c, idx_in, b, b, nullptr, lr, ph);
     hipError_t e = hipStreamEndCapture(c->stream, &graph);
-    if (st != ABS_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
-    if (e != hipSuccess || !graph) return cfail(c, ABS_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+    c->n_samples = samples_before;
+    if (st != ABS_OK) { if (graph) (void)hipGraphDestroy(graph); return settle_update(c, st); }
+    if (e != hipSuccess || !graph) return settle_update(c, cfail(c, ABS_EHIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e)));
     hipGraphExec_t exec = nullptr;
     e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
     (void)hipGraphDestroy(graph);
-    if (e != hipSuccess) return cfail(c, ABS_EHIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
+    if (e != hipSuccess) return settle_update(c, cfail(c, ABS_EHIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e)));
     if (c->graphs.size() >= 8) {                                  // keep a few sizes: drop the least recently used
       size_t old = 0;
       for (size_t i = 1; i < c->graphs.size(); ++i) if (c->graphs[i].last_use < c->graphs[old].last_use) old = i;
@@ -874,7 +887,10 @@ abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, flo
     slot = &c->graphs.back();
   }
   slot->last_use = c->t;
-  HIPCHK(c, hipGraphLaunch(slot->exec, c->stream));
+  {
+    hipError_t el = hipGraphLaunch(slot->exec, c->stream);
+    if (el != hipSuccess) return settle_update(c, cfail(c, ABS_EHIP, std::string("hipGraphLaunch: ") + hipGetErrorString(el)));
+  }
   note_step(c, b, nullptr);
   return ABS_OK;
 } catch (...) { return on_exception(); }
@@ -1068,6 +1084,29 @@ abs_status abs_average_replicas(abs_ctx *c) try {
     HIPCHK(c, launch_average_f32(c->at<float>(pl.o_xm), pl.bf16 ? c->at<bf16_t>(pl.o_xs) : nullptr, c->at<float>(pl.o_mean), pl.M, pl.Ppad,
                                  c->stream));
   }
+  c->n_rounds += 1;                  // Alg. 1: k <- k + 1
+  return ABS_OK;
+} catch (...) { return on_exception(); }
+
+abs_status abs_get_counters(const abs_ctx *c, long long *rounds, long long *local_steps, long long *samples) try {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (rounds) *rounds = c->n_rounds;
+  if (local_steps) *local_steps = c->t;
+  if (samples) *samples = c->n_samples;
+  return ABS_OK;
+} catch (...) { return on_exception(); }
+
+abs_status abs_get_opt_state(abs_ctx *c, int m, int which, float *out_host) try {
+  if (!c || !out_host) return fail(ABS_EINVAL, "NULL argument");
+  if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
+  const bool has_v = c->cfg.opt != ABS_OPT_SGD, has_m = c->cfg.opt == ABS_OPT_ADAMW;
+  if (!((which == 0 && has_v) || (which == 1 && has_m)))
+    return cfail(c, ABS_EINVAL, "this optimizer keeps no such state vector");
+  std::vector<float> in(c->pl.Ppad);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(in.data(), c->at<float>(which == 0 ? c->pl.o_v : c->pl.o_m) + (size_t)m * c->pl.Ppad,
+                      c->pl.Ppad * sizeof(float), hipMemcpyDeviceToHost));
+  to_external(c->pl, c->cfg.has_bias != 0, in.data(), out_host);
   return ABS_OK;
 } catch (...) { return on_exception(); }
 

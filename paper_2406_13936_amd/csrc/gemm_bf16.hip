@@ -26,6 +26,7 @@
 // bf16 MFMAs with fp32 accumulators.  Work-group ids are remapped so that each XCD (ids are
 // dealt round-robin to the 8 XCDs) works on a contiguous range of tiles and its L2 sees one
 // replica's operands at a time.
+#include <mutex>
 #include "abs_internal.h"
 #include "device_utils.h"
 
@@ -627,13 +628,13 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
   constexpr size_t lds = tile_bytes > epi_bytes ? tile_bytes : epi_bytes;
   static_assert(lds <= 160 * 1024, "LDS budget");
   auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, NS, AT, BT, EPI, ACT>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per kernel variant, also when several host threads (each with a context of its own) launch it first together
+  static std::once_flag attr_once;
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(attr_once, [&] {
+    attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  });
+  if (attr_err != hipSuccess) return attr_err;
   const int tilesM = (p.Md + BM - 1) / BM, tilesN = (p.Nd + BN - 1) / BN;
   const long long nblk = (long long)tilesM * tilesN * p.groups * ((EPI == EPI_WGRAD && p.ksplit > 1) ? p.ksplit : 1);
   if (nblk <= 0) return hipSuccess;

@@ -233,3 +233,39 @@ def test_plain_inner_product_test_ignores_nu():
     aug = rep.test(O.TEST_AUG_IP, theta=0.9, nu=0.5)[0]
     assert plain["T"] == 0 and plain["pass"] and plain["ratio_perp"] == 0.0
     assert aug["T"] == 8 and not aug["pass"] and aug["ratio_perp"] == pytest.approx(8.0)
+
+
+def test_alg2_loop_tests_once_per_round_on_the_last_gradients():
+    rng = np.random.default_rng(41)
+    net = O.Net((6, 5, 3), O.ACT_RELU, True)
+    X, y = rng.normal(size=(128, 6)), rng.integers(0, 3, size=128)
+    x0 = rng.normal(0, 0.4, size=net.n_params)
+    M, H = 3, 2
+
+    def idx(k, h, b):
+        return np.random.default_rng([9, k, h]).integers(0, 128, size=(M, b))
+
+    # constant size (cap = b0): the iterates are those of Alg. 1 at that size, and B = rounds * H * M * b
+    xs2, sched2, B2 = O.run_alg2(net, x0, X, y, M=M, H=H, rounds=3, b0=4, cap=4, lr=0.1, idx_fn=idx)
+    xs1, _, B1 = O.run(net, x0, X, y, M=M, H=H, rounds=3, b0=4, cap=4, lr=0.1, idx_fn=idx)
+    np.testing.assert_array_equal(xs2, xs1)
+    assert B2 == B1 == 3 * H * M * 4 and [s[1] for s in sched2] == [4, 4, 4]
+    # growing: replay the loop by hand with explicit per-sample gradients; the test uses the gradients of the
+    # round's last local step, taken at the iterates before that step, and the round's size for every step
+    xs, sched, B = O.run_alg2(net, x0, X, y, M=M, H=H, rounds=3, b0=4, cap=64, lr=0.1, idx_fn=idx, eta=0.4)
+    x = np.tile(x0, (M, 1))
+    b, Bh = 4, 0
+    for k in range(3):
+        for h in range(H):
+            ii = idx(k, h, b)
+            g = np.stack([O.per_sample_gradients(net, x[m], X[ii[m]], y[ii[m]]).mean(axis=0) for m in range(M)])
+            x = x - 0.1 * g
+        x = np.tile(x.mean(axis=0), (M, 1))
+        gbar = g.mean(axis=0)
+        var = b / (M - 1) * sum(float(((g[m] - gbar) ** 2).sum()) for m in range(M))
+        T = math.ceil(var / (M * 0.16 * float(gbar @ gbar)))
+        assert sched[k] == (k, b, T)
+        Bh += H * M * b
+        b = min(64, max(T, b))
+    assert B == Bh and sched[-1][1] > 4
+    np.testing.assert_allclose(xs, x, rtol=1e-10, atol=1e-13)
