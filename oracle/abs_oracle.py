@@ -412,13 +412,20 @@ class Replicas:
         self.stats: List[dict] = []
         self.grads: Optional[np.ndarray] = None
 
-    def local_step(self, idx: np.ndarray, lr: float):
+    def local_step(self, idx: np.ndarray, lr: float, only: Optional[Sequence[int]] = None):
         """One local step of every worker; idx[m] holds worker m's sample indices (an [M, b]
         array, or M arrays of different lengths for per-worker batch sizes).  The statistics
-        refer to the gradient at the pre-update iterate."""
+        refer to the gradient at the pre-update iterate.  With `only`, just the listed workers
+        are stepped (the workers are independent between averages); the others keep their
+        iterate, their optimizer state does not advance, and their entries of `stats` / `grads`
+        are None / zero."""
         self.stats = []
         grads = []
         for m in range(self.M):
+            if only is not None and m not in only:
+                self.stats.append(None)
+                grads.append(np.zeros(self.net.n_params))
+                continue
             bp = backprop(self.net, self.x[m], self.X[idx[m]], self.y[idx[m]],
                           self.mixed)
             self.stats.append(stats_factored(self.net, bp, self.want_ip, self.mixed))
@@ -433,6 +440,9 @@ class Replicas:
         worker, eq. (approx_norm_local))."""
         out = []
         for m, s in enumerate(self.stats):
+            if s is None:                        # worker left out of the last step
+                out.append(None)
+                continue
             if kind == TEST_NORM:
                 eta_m = eta[m] if np.ndim(eta) else eta
                 out.append(norm_test(s["var"], s["S2"], s["b"], eta_m))
