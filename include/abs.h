@@ -263,6 +263,18 @@ abs_status abs_layer_stats_workspace_bytes(int L, const int *in_dims, const int 
 abs_status abs_average_bf16(void *params_dev, int M, int64_t n, void *scratch_dev, void *hip_stream);
 
 /*
+ * abs_average_bf16 for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the mean buffer of the two-pass form is a 32 MiB array that is part of
+ * the library's code object (each GPU the library runs on holds it until the process ends), so the call
+ * allocates nothing and takes no scratch pointer.  Same kernels, same result bit for bit as abs_average_bf16
+ * with a scratch buffer.   n <= 16 Mi (16 777 216) bf16 values per replica, else ABS_EINVAL.
+ * All calls on one GPU share that GPU's buffer: calls that overlap on one GPU (different streams or host
+ * threads) race; calls on one stream are ordered and safe.  The buffer's address is resolved on the first call
+ * on a device (make that call outside any stream capture).
+ */
+abs_status abs_average_bf16_static(void *params_dev, int M, int64_t n, void *hip_stream);
+
+/*
  * Per-kernel timing (measurement aid; not part of the method).  While enabled, every kernel
  * launch of abs_local_step / abs_average_replicas is bracketed by two HIP events on the
  * context's stream.  abs_profile_read synchronises, folds the elapsed times into per-kernel

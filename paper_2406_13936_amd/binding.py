@@ -27,7 +27,7 @@ EXPORTS = [
     "abs_profile_enable", "abs_profile_read", "abs_copy_probe", "abs_lr_schedule",
     "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
     "abs_local_step_accumulated", "abs_profile_pause", "abs_local_step_graphed", "abs_graph_count",
-    "abs_get_counters", "abs_get_opt_state",
+    "abs_get_counters", "abs_get_opt_state", "abs_average_bf16_static",
 ]
 
 
@@ -98,6 +98,7 @@ def load_library(reload: bool = False):
     lib.abs_layer_stats_workspace_bytes.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int),
                                                     C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     lib.abs_average_bf16.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p, C.c_void_p]
+    lib.abs_average_bf16_static.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_void_p]
     lib.abs_destroy.argtypes = [C.c_void_p]
     lib.abs_lr_schedule.argtypes = [C.c_longlong, C.c_longlong, C.c_longlong, C.c_double, C.c_double,
                                     C.POINTER(C.c_double)]
@@ -405,3 +406,10 @@ def average_bf16(params, scratch=None):
         assert scratch.is_contiguous() and scratch.numel() >= n and scratch.element_size() == 2
     _check(lib.abs_average_bf16(params.data_ptr(), M, n, scratch.data_ptr() if scratch is not None else None,
                                 _stream_ptr()))
+
+
+def average_bf16_static(params):
+    """average_bf16 through the entry point that allocates nothing (the mean buffer lives in the library)."""
+    lib = load_library()
+    M, n = int(params.shape[0]), int(params[0].numel())
+    _check(lib.abs_average_bf16_static(params.data_ptr(), M, n, _stream_ptr()))

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -1293,6 +1294,51 @@ abs_status abs_copy_probe(const void *src_dev, void *dst_dev, int64_t bytes, voi
     return fail(ABS_EINVAL, "bytes must be a positive multiple of 16 and the pointers 16-byte aligned");
   abs_ctx *nc = nullptr;
   HIPCHK(nc, launch_copy_probe(src_dev, dst_dev, bytes, static_cast<hipStream_t>(hip_stream)));
+  return ABS_OK;
+} catch (...) { return on_exception(); }
+
+// ---- the mean buffer of abs_average_bf16_static -----------------------------------------------
+// Device memory that belongs to the library's code object: every GPU the library runs on holds its own copy
+// at its own address until the process ends.  Host code never uses the array's name as an address; it asks the
+// runtime for the address once per device and passes that pointer to the kernels.
+constexpr long long AVG_STATIC_ELEMS = 16LL << 20;            // bf16 values: 32 MiB
+static __device__ __align__(256) unsigned char g_avg_mean[AVG_STATIC_ELEMS * 2];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_avg_mu;
+void *g_avg_mean_ptr[MAX_DEVICES] = {nullptr};
+
+// Address of the current device's copy of g_avg_mean (resolved on the first call on that device).
+abs_status avg_static_ptr(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(ABS_EHIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(ABS_EUNSUPPORTED, "device ordinal beyond the static-scratch table");
+  std::lock_guard<std::mutex> lk(g_avg_mu);
+  if (!g_avg_mean_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_avg_mean));
+    if (e != hipSuccess || !ptr) return fail(ABS_EHIP, std::string("hipGetSymbolAddress: ") + hipGetErrorString(e));
+    g_avg_mean_ptr[dev] = ptr;
+  }
+  *out = g_avg_mean_ptr[dev];
+  return ABS_OK;
+}
+}  // namespace
+
+abs_status abs_average_bf16_static(void *params_dev, int M, int64_t n, void *hip_stream) try {
+  if (!params_dev) return fail(ABS_EINVAL, "params_dev is NULL");
+  if (M < 1 || n < 8 || (n % 8)) return fail(ABS_EINVAL, "M < 1 or n not a positive multiple of 8");
+  if (n > AVG_STATIC_ELEMS) return fail(ABS_EINVAL, "n exceeds the static mean buffer (16 Mi bf16 values per replica)");
+  if (reinterpret_cast<uintptr_t>(params_dev) & 15) return fail(ABS_EINVAL, "params_dev must be 16-byte aligned");
+  void *mean = nullptr;
+  abs_status st = avg_static_ptr(&mean);
+  if (st != ABS_OK) return st;
+  abs_ctx *nc = nullptr;
+  // the first pass writes mean[0, n) before the second reads it: nothing of the last call's contents is used
+  HIPCHK(nc, launch_average_bf16(static_cast<bf16_t *>(params_dev), static_cast<bf16_t *>(mean), M, n,
+                                 static_cast<hipStream_t>(hip_stream)));
   return ABS_OK;
 } catch (...) { return on_exception(); }
 
