@@ -48,6 +48,12 @@ def parse():
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     ap.add_argument("--graphs", action="store_true",
                     help="replay captured HIP graphs on the steps that are not bracketed by events (fixed batch size)")
+    ap.add_argument("--fused-update", action="store_true",
+                    help="opt in to the optimizer step inside the weight-gradient epilogue (abs_set_fused_update)")
+    ap.add_argument("--sustain-seconds", type=float, default=-1.0,
+                    help="after the timed steps keep stepping for at least this long and report the step time of that "
+                         "period as ms_per_step_sustained (the chip settles at its power limit within seconds; "
+                         "default: 10 s for the default run, 0 with --batch / --adaptive / --no-cpu-baseline / other workloads)")
     ap.add_argument("--no-also", action="store_true", help="skip the reference measurement of config 2 (profiling runs)")
     ap.add_argument("--beyond", action="store_true",
                     help="time the entry points beyond the base path on config-3 / config-2 shapes instead: the "
@@ -55,9 +61,10 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, X, y, x0, sample_b):
-    """The oracle as it stands, timed on this machine's host cores: one local step of all M
-    replicas (statistics and test included) at local batch size sample_b."""
+def cpu_baseline(w, X, y, x0, sample_bs):
+    """The oracle as it stands, timed on this machine's host cores: one local step of all M replicas (statistics,
+    test and rule included) at each local batch size of sample_bs (the configuration's first size b0 and
+    min(cap, 512)); `value` is the rate at the last (largest) one."""
     import numpy as np
     from oracle import abs_oracle as O
     from paper_2406_13936_amd import workloads as W
@@ -67,17 +74,26 @@ def cpu_baseline(w, X, y, x0, sample_b):
     except Exception:
         threads = os.cpu_count() or 1
     net = O.Net(w.dims, w.act, w.has_bias)
-    orc = O.Replicas(net, x0, X, y, w.M, opt=w.opt, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2,
-                     eps=w.eps, weight_decay=w.weight_decay, mixed=(w.prec == W.PREC_BF16),
-                     want_ip=(w.test != W.TEST_NORM))
-    idx = W.step_indices(w, 0, 0, sample_b)
-    t0 = time.perf_counter()
-    orc.local_step(idx, w.lr)
-    orc.test(w.test, eta=w.eta, theta=w.theta, nu=w.nu)
-    dt = time.perf_counter() - t0
-    return {"value": w.M * sample_b / dt, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"one local step of all M={w.M} replicas at b={sample_b} incl. statistics and test "
-                      f"({dt:.1f} s, fp64 numpy, bf16 rounding points emulated)"}
+    runs = []
+    for sb in sample_bs:
+        orc = O.Replicas(net, x0, X, y, w.M, opt=w.opt, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2,
+                         eps=w.eps, weight_decay=w.weight_decay, mixed=(w.prec == W.PREC_BF16),
+                         want_ip=(w.test != W.TEST_NORM))
+        idx = W.step_indices(w, 0, 0, sb)
+        t0 = time.perf_counter()
+        orc.local_step(idx, w.lr)
+        res = orc.test(w.test, eta=w.eta, theta=w.theta, nu=w.nu)
+        O.next_batch_size([r["T"] for r in res], [sb] * w.M, w.b_cap, True)
+        dt = time.perf_counter() - t0
+        runs.append({"local_batch": sb, "seconds": dt, "samples_per_s": w.M * sb / dt})
+    last = runs[-1]
+    return {"value": last["samples_per_s"], "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "host_cpus": os.cpu_count(),
+            "sample": "one local step of all M=%d replicas incl. statistics, test and rule at b=%s (%s s); value is the "
+                      "rate at b=%d; fp64 numpy (its BLAS threads = cores), bf16 rounding points emulated"
+                      % (w.M, "/".join(str(r["local_batch"]) for r in runs),
+                         "/".join("%.1f" % r["seconds"] for r in runs), last["local_batch"]),
+            "runs": runs}
 
 
 def stats_stress(a, np, torch, A, W):
@@ -144,6 +160,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     if a.graphs:
         torch.cuda.set_stream(torch.cuda.Stream())     # stream capture needs a created stream (default priority)
     rep = A.Replicas.from_workload(w, X, y, x0)
+    if a.fused_update:
+        rep.set_fused_update(True)
     b_fixed = a.batch or w.b_cap
 
     def test_and_rule(b):
@@ -200,6 +218,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
         torch.cuda.synchronize()
         rep.close()
         rep = A.Replicas.from_workload(w, X, y, x0)
+        if a.fused_update:
+            rep.set_fused_update(True)
     b = w.b0 if a.adaptive else b_fixed
     for s in range(a.warmup):
         nb = run(s, b)
@@ -225,6 +245,23 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     prof = rep.profile_read()
     rep.profile_enable(False)
     scale = a.steps / max(sampled, 1)                  # sampled steps -> all timed steps (for the shares)
+    # sustained rate: the same steps (staged index batches reused in turn) for at least sustain_s seconds
+    sustained = None
+    sustain_s = a.sustain_seconds
+    if sustain_s < 0:
+        sustain_s = 10.0 if (with_cpu and not a.adaptive and not a.batch and wname == "config3") else 0.0
+    if sustain_s > 0 and not a.adaptive:
+        n_s, t1 = 0, time.perf_counter()
+        while True:
+            for s in range(total):
+                run(s, b)
+            n_s += total
+            torch.cuda.synchronize()
+            if time.perf_counter() - t1 >= sustain_s:
+                break
+        dts = time.perf_counter() - t1
+        sustained = {"ms_per_step_sustained": dts * 1e3 / n_s, "sustained_steps": n_s, "sustained_seconds": dts,
+                     "value_sustained": w.M * b * n_s / dts}
 
     # dominant kernel = the matrix-core GEMM class with the largest total time
     gemms = {k: v for k, v in prof.items() if k.startswith("gemm_")}
@@ -241,37 +278,51 @@ def measure(a, wname, np, torch, A, W, with_cpu):
             e["frac_of_copy"] = e["gbs"] / COPY_GBS        # against the fastest plain copy measured here
         kernels[k] = e
     roof = None
-    if gemms and w.prec == W.PREC_BF16:
-        # Launch classes as a kernel trace sees them: one kernel symbol per (epilogue, tile shape), whatever the
-        # layer.  The dominant kernel is the class with the largest total time; its average launch duration is
-        # what `rocprofv3 --kernel-trace --stats` reports for that symbol.
+    if prof:
+        # Launch classes as a kernel trace sees them: one kernel symbol per (epilogue, tile shape) whatever the layer,
+        # one per streaming kernel.  The dominant class is the one with the largest total time; its average launch
+        # duration is what `rocprofv3 --kernel-trace --stats` reports for that symbol.  Which roof bounds it follows
+        # from its algorithmic intensity: above the ridge of the machine (2.5 PFLOP/s over 8 TB/s = 312 flop/byte)
+        # the matrix cores, below it (short batches: weight streaming and the per-parameter streams) HBM.
         classes = {}
-        for k, v in gemms.items():
-            cname = k.rsplit("_L", 1)[0]
-            ce = classes.setdefault(cname, {"total_ms": 0.0, "flops": 0.0, "calls": 0, "layers": []})
-            ce["total_ms"] += v["total_ms"]; ce["flops"] += v["flops"]; ce["calls"] += v["calls"]; ce["layers"].append(k)
+        for k, v in prof.items():
+            cname = k.rsplit("_L", 1)[0] if k.startswith("gemm_") else k
+            ce = classes.setdefault(cname, {"total_ms": 0.0, "flops": 0.0, "bytes": 0.0, "calls": 0, "layers": []})
+            ce["total_ms"] += v["total_ms"]; ce["flops"] += v["flops"]; ce["bytes"] += v["bytes"]
+            ce["calls"] += v["calls"]; ce["layers"].append(k)
         name = max(classes, key=lambda k: classes[k]["total_ms"])
         v = classes[name]
-        ach = v["flops"] / (v["total_ms"] * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": name, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
-                "avg_launch_ms": v["total_ms"] / v["calls"], "launches": v["calls"],
-                "flops_per_launch": v["flops"] / v["calls"], "layers": sorted(v["layers"])}
-        # HBM bytes per launch (mean over the class's layers) from the committed rocprofv3 --pmc summary of this
-        # same command (FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel); null when no summary covers it
-        tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.json" % wname)
-        if os.path.exists(tpath) and not a.adaptive and not a.batch:
-            try:
-                tj = json.load(open(tpath)).get("kernels", {})
-                if all(k in tj for k in v["layers"]):
-                    roof["traffic"] = sum(tj[k]["hbm_bytes_per_launch"] for k in v["layers"]) / len(v["layers"])
-                    roof["traffic_source"] = "profiles/" + os.path.basename(tpath)
-            except Exception:
-                pass
-        allf = sum(v["flops"] for v in gemms.values())
-        allt = sum(v["total_ms"] for v in gemms.values())
-        roof["all_gemms_tflops"] = allf / (allt * 1e-3) / 1e12
-        roof["all_gemms_frac"] = roof["all_gemms_tflops"] / PEAK_BF16_TFLOPS
+        ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+        if w.prec == W.PREC_BF16 and v["flops"] > 0 and v["flops"] / max(v["bytes"], 1.0) >= ridge:
+            ach = v["flops"] / (v["total_ms"] * 1e-3) / 1e12
+            roof = {"bound": "mfma", "kernel": name, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                    "avg_launch_ms": v["total_ms"] / v["calls"], "launches": v["calls"],
+                    "flops_per_launch": v["flops"] / v["calls"], "layers": sorted(v["layers"])}
+        elif v["bytes"] > 0:
+            ach = v["bytes"] / (v["total_ms"] * 1e-3) / 1e9
+            roof = {"bound": "hbm", "kernel": name, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": v["total_ms"] / v["calls"],
+                    "launches": v["calls"], "bytes_per_launch": v["bytes"] / v["calls"],
+                    "flops_per_byte": v["flops"] / v["bytes"], "layers": sorted(v["layers"])}
+        if roof is not None:
+            # HBM bytes per launch (mean over the class's layers) as read by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+            # (scaled by the copy kernel) in the committed summary of this same command: a stored profile, not a
+            # reading of this run; null when no summary covers the class
+            tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.json" % wname)
+            if os.path.exists(tpath) and not a.adaptive and not a.batch and not a.fused_update:
+                try:
+                    tj = json.load(open(tpath)).get("kernels", {})
+                    if all(k in tj for k in v["layers"]):
+                        roof["traffic"] = sum(tj[k]["hbm_bytes_per_launch"] for k in v["layers"]) / len(v["layers"])
+                        roof["traffic_source"] = "stored profile: profiles/" + os.path.basename(tpath)
+                except Exception:
+                    pass
+        if gemms and w.prec == W.PREC_BF16 and roof is not None:
+            allf = sum(v["flops"] for v in gemms.values())
+            allt = sum(v["total_ms"] for v in gemms.values())
+            roof["all_gemms_tflops"] = allf / (allt * 1e-3) / 1e12
+            roof["all_gemms_frac"] = roof["all_gemms_tflops"] / PEAK_BF16_TFLOPS
     n_graphs = rep.graph_count()
     rep.close()
     if a.graphs:
@@ -289,11 +340,18 @@ def measure(a, wname, np, torch, A, W, with_cpu):
                    "test": ["norm", "inner_product", "augmented_inner_product"][w.test]},
         "roofline": roof, "kernels": kernels,
     }
+    if sustained:
+        out.update(sustained)
+    if a.fused_update:
+        out["config"]["fused_update"] = True
     if a.graphs:
         out["config"]["hip_graphs"] = n_graphs
     if with_cpu:
-        sb = a.cpu_sample_batch or {"config1": 512, "config2": 4096, "config3": 2048, "config4": 1024}[wname]
-        out["cpu_baseline"] = cpu_baseline(w, X, y, x0, min(sb, w.b_cap))
+        # the configuration's first size and min(cap, 512) (config 2, cheap enough: its cap as well)
+        sbs = [w.b0, min(w.b_cap, 512)] + ([w.b_cap] if wname == "config2" else [])
+        if a.cpu_sample_batch:
+            sbs = [min(a.cpu_sample_batch, w.b_cap)]
+        out["cpu_baseline"] = cpu_baseline(w, X, y, x0, sorted(set(sbs)))
     return out
 
 

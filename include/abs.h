@@ -207,6 +207,20 @@ abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_c
 abs_status abs_average_replicas(abs_ctx *ctx);
 
 /*
+ * Opt-in: apply the optimizer step of the weights inside the epilogue of the weight-gradient contraction instead
+ * of storing the fp32 gradient and streaming it through a separate update (Alg. 1's "local step" fused into
+ * "compute the local batch gradient").  At small local batch sizes, where a step is bound by the bytes moved
+ * per parameter, this removes 8 of 28 bytes per parameter (heavy ball).  ||gbar||^2 is then summed from
+ * per-wavefront partial sums left by the epilogues, the batch gradient of the weights exists only as the bf16
+ * copy that the inner products use, and the statistics, tests and parameters are those of the unfused step up to
+ * the order of the additions in ||gbar||^2.  While it is on: abs_get_grad and abs_cross_worker_test after such a
+ * step and abs_local_step_accumulated return ABS_ESTATE (they need the stored gradient); a step whose weight
+ * gradients split their reduction over the batch (few output tiles, long batches) runs unfused.  Needs
+ * ABS_PREC_BF16 (ABS_EUNSUPPORTED otherwise).
+ */
+abs_status abs_set_fused_update(abs_ctx *ctx, int on);
+
+/*
  * Counters of Alg. 1: rounds = k, the communication rounds completed (one per abs_average_replicas,
  * "k <- k + 1"); local_steps = optimizer steps taken by every worker; samples = B, the local batch
  * sizes actually used, summed over workers and local steps ("B <- B + sum_m sum_h b^m").

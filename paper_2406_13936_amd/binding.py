@@ -28,6 +28,7 @@ EXPORTS = [
     "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
     "abs_local_step_accumulated", "abs_profile_pause", "abs_local_step_graphed", "abs_graph_count",
     "abs_get_counters", "abs_get_opt_state", "abs_average_bf16_static",
+    "abs_set_fused_update",
 ]
 
 
@@ -88,6 +89,7 @@ def load_library(reload: bool = False):
     lib.abs_get_grad.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
     lib.abs_get_counters.argtypes = [C.c_void_p, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong),
                                      C.POINTER(C.c_longlong)]
+    lib.abs_set_fused_update.argtypes = [C.c_void_p, C.c_int]
     lib.abs_get_opt_state.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.abs_get_per_sample.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     lib.abs_n_params.argtypes = [C.POINTER(_Config), C.POINTER(C.c_int64)]
@@ -300,6 +302,10 @@ class Replicas:
         out = np.empty(self.n_params, dtype=np.float32)
         _check(self._lib.abs_get_opt_state(self._ctx, int(m), int(which), out.ctypes.data), self._ctx)
         return out
+
+    def set_fused_update(self, on: bool = True):
+        """Opt in to (or out of) the optimizer step inside the weight-gradient epilogue."""
+        _check(self._lib.abs_set_fused_update(self._ctx, int(bool(on))), self._ctx)
 
     def counters(self):
         """(rounds k, local steps, samples B) of Alg. 1 as kept by the library."""

@@ -233,6 +233,8 @@ struct abs_ctx {
   int last_ps = -1;               // per-sample outputs stored (accumulated steps; -1: all of them)
   bool last_ragged = false;
   bool have_stats = false;
+  bool fused_update = false;      // abs_set_fused_update: apply the optimizer step inside the weight-gradient epilogue
+  bool last_fused = false;        // the last step did so (its fp32 gradient was never stored)
   // captured steps (abs_local_step_graphed): one executable graph per batch size, a few kept
   struct GraphSlot { int b; hipGraphExec_t exec; long long last_use; };
   std::vector<GraphSlot> graphs;
@@ -301,8 +303,19 @@ struct ProfScope {
 };
 
 hipError_t gemm(abs_ctx *c, const GemmP &p, int epi, int layer) {
-  const int shape = c->pl.bf16 ? gemm_bf16_tile_shape(p.Md, p.Nd, p.groups) : 1;
-  ProfScope ps(c, T_GEMM0 + (epi * 3 + shape) * T_LAYERS + layer, 2.0 * p.Md * p.Nd * p.Kd * p.groups, 0.0);
+  int shape = !c->pl.bf16 ? 1 : (epi == EPI_WGRAD ? gemm_bf16_wgrad_shape(p.Md, p.Nd, p.Kd, p.groups)
+                                                   : gemm_bf16_tile_shape(p.Md, p.Nd, p.groups));
+  if (shape == 3) shape = 1;                    // the short-batch weight-gradient tile is a 128 x 128 tile too
+  // algorithmic bytes of the launch: both operands once, the outputs once, the epilogue's elementwise operand once
+  const double e = c->pl.esz, mn = (double)p.Md * p.Nd;
+  double bytes = ((double)p.Md + p.Nd) * p.Kd * e;
+  if (epi == EPI_FWD_ACT) bytes += mn * e * (p.C2 ? 2 : 1);
+  else if (epi == EPI_LOGITS) bytes += mn * 4;
+  else if (epi == EPI_BWD) bytes += mn * e * (p.act != ABS_ACT_NONE ? 2 : 1);
+  else if (epi == EPI_IPDOT) bytes += mn * e;
+  else if (p.upd_x) bytes += mn * (8 + (p.upd_v ? 8 : 0) + (p.upd_m ? 8 : 0) + (p.upd_shadow ? 2 : 0) + (p.C2 ? 2 : 0));
+  else bytes += mn * (4 + (p.C2 ? 2 : 0) + (p.accumulate ? 4 : 0));
+  ProfScope ps(c, T_GEMM0 + (epi * 3 + shape) * T_LAYERS + layer, 2.0 * p.Md * p.Nd * p.Kd * p.groups, bytes * p.groups);
   return c->pl.bf16 ? launch_gemm_bf16(p, epi, c->stream) : launch_gemm_f32(p, epi, c->stream);
 }
 
@@ -650,6 +663,31 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       }
     }
   }   // passes
+  // Number of slices of layer l's weight-gradient reduction (bf16 mode): few output tiles and a long reduction
+  // (small layers, or any layer while b is the long side) are cut into slices so that the launch fills the chip;
+  // the slices are added in order afterwards.
+  auto bf16_ksplit = [&](int l) -> int {
+    const int Md = pl.dims[l], Nd = pl.dims[l - 1];
+    if (!pl.bf16 || (Nd & 3)) return 1;
+    const int sh = gemm_bf16_wgrad_shape(Md, Nd, b, M);
+    if (sh == 3) return 1;                      // short batches: never split
+    const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
+    const long long tiles = (long long)((Md + te - 1) / te) * ((Nd + tn_e - 1) / tn_e) * M;
+    return choose_ksplit(sh, tiles, (b + 63) / 64, (double)M * Md * Nd, pl.kpart_floats_l[l]);
+  };
+  // The optimizer step moves into the weight-gradient epilogue when the caller asked for it and this call both
+  // finishes the gradient and updates, no reduction is split and the per-wavefront sums of squares fit their scratch.
+  bool fused = c->fused_update && pl.bf16 && ph.wgrad && ph.update && ph.s2 && !ph.acc_grad;
+  if (fused) {
+    long long slots = 0;
+    for (int l = 1; l <= L; ++l) {
+      if (bf16_ksplit(l) > 1 || (pl.dims[l - 1] & 3)) fused = false;
+      slots += gemm_bf16_upd_slots(pl.dims[l], pl.dims[l - 1], b, M);
+    }
+    if (hb) { int mx = 0; for (int l = 1; l <= L; ++l) mx = std::max(mx, pl.dims[l]); slots += (long long)L * ((mx + 255) / 256); }
+    if (slots > pl.Ppad / 256) fused = false;
+  }
+  int fused_slots = 0;
   // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
   if (ph.wgrad) {
     for (int l = 1; l <= L; ++l) {
@@ -679,19 +717,23 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
           p.kpart = c->at<float>(pl.o_kpart_l[l]);
         }
       }
-      if (pl.bf16 && p.ldc == p.Nd && (p.Nd & 3) == 0) {
-        // few output tiles and a long reduction (small layers, or any layer while b is the long side): cut
-        // the reduction into slices so that the launch fills the chip, and add the slices in order afterwards
-        const int sh = gemm_bf16_tile_shape(p.Md, p.Nd, M);
-        const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
-        const long long tiles = (long long)((p.Md + te - 1) / te) * ((p.Nd + tn_e - 1) / tn_e) * M;
-        const int S = choose_ksplit(sh, tiles, (b + 63) / 64, (double)M * p.Md * p.Nd, pl.kpart_floats_l[l]);
-        if (S > 1) {
-          const int KT = (b + 63) / 64;
-          p.ksplit = S;
-          p.kchunk = ((KT + S - 1) / S) * 64;
-          p.kpart = c->at<float>(pl.o_kpart_l[l]);
-        }
+      if (bf16_ksplit(l) > 1) {
+        const int KT = (b + 63) / 64, S = bf16_ksplit(l);
+        p.ksplit = S;
+        p.kchunk = ((KT + S - 1) / S) * 64;
+        p.kpart = c->at<float>(pl.o_kpart_l[l]);
+      }
+      if (fused) {
+        // the optimizer step replaces the gradient store (the fp32 gradient of the weights is never written)
+        p.upd_x = xm + pl.offW[l];
+        p.upd_v = c->cfg.opt != ABS_OPT_SGD ? c->at<float>(pl.o_v) + pl.offW[l] : nullptr;
+        p.upd_m = c->cfg.opt == ABS_OPT_ADAMW ? c->at<float>(pl.o_m) + pl.offW[l] : nullptr;
+        p.upd_shadow = c->at<bf16_t>(pl.o_xs) + pl.offW[l];
+        p.upd_opt = c->cfg.opt; p.upd_lr = lr; p.upd_momentum = c->cfg.momentum; p.upd_beta1 = c->cfg.beta1;
+        p.upd_beta2 = c->cfg.beta2; p.upd_eps = c->cfg.eps; p.upd_wd = c->cfg.weight_decay;
+        p.upd_c1 = ph.c1; p.upd_c2 = ph.c2; p.upd_scal = ph.scal;
+        p.upd_sq = c->at<float>(pl.o_sqwave); p.upd_sSqg = pl.Ppad / 256; p.upd_slot0 = fused_slots;
+        fused_slots += gemm_bf16_upd_slots(p.Md, p.Nd, b, M);
       }
       HIPCHK(c, gemm(c, p, EPI_WGRAD, l));
       if (p.ksplit > 1) {                    // its slices are added up after the loop, with those of the other layers
@@ -781,6 +823,35 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   // may run first); otherwise a separate pass over the gradient does.
   const bool s2_in_update = ph.s2 && ph.update;
   sp.grad = (ph.s2 && !s2_in_update) ? grad : nullptr;
+  if (fused) {
+    // the weights have taken their step in the epilogues; the biases take theirs here, and ||gbar||^2 is the sum
+    // of the slots the epilogues and this launch left
+    if (hb) {
+      BiasUpdateP bu;
+      std::memset(&bu, 0, sizeof(bu));
+      bu.n = L;
+      for (int l = 1; l <= L; ++l) { bu.width[l - 1] = pl.dims[l]; bu.off[l - 1] = pl.offB[l]; }
+      bu.stride = pl.Ppad;
+      bu.x = xm; bu.g = grad;
+      bu.v = c->cfg.opt != ABS_OPT_SGD ? c->at<float>(pl.o_v) : nullptr;
+      bu.m = c->cfg.opt == ABS_OPT_ADAMW ? c->at<float>(pl.o_m) : nullptr;
+      bu.shadow = c->at<bf16_t>(pl.o_xs);
+      bu.opt = c->cfg.opt; bu.lr = lr; bu.momentum = c->cfg.momentum; bu.beta1 = c->cfg.beta1; bu.beta2 = c->cfg.beta2;
+      bu.eps = c->cfg.eps; bu.wd = c->cfg.weight_decay; bu.c1 = ph.c1; bu.c2 = ph.c2; bu.scal = ph.scal;
+      bu.sq = c->at<float>(pl.o_sqwave); bu.sSqg = pl.Ppad / 256; bu.slot0 = fused_slots;
+      fused_slots += update_bias_slots(bu);
+      ProfScope ps_(c, T_UPDATE, 0.0, 0.0);
+      HIPCHK(c, launch_update_bias(bu, M, s));
+    }
+    sp.sq_wave = c->at<float>(pl.o_sqwave); sp.n_sq_wave = fused_slots;
+    sp.sq_stride = pl.Ppad / 256;
+    ProfScope ps_(c, T_STATS, 0.0, 4.0 * M * fused_slots);
+    HIPCHK(c, launch_stats(sp, s));
+    note_step(c, ph.b_total > 0 ? ph.b_total : b, b_host);
+    c->last_fused = true;
+    return ABS_OK;
+  }
+  c->last_fused = false;
   if (!s2_in_update) {
     ProfScope ps_(c, T_STATS, 0.0, ph.s2 ? 4.0 * M * pl.Ppad : 0.0);
     HIPCHK(c, launch_stats(sp, s));
@@ -907,6 +978,7 @@ abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b,
   if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
   const int cap = c->pl.cap;
+  if (c->fused_update) return cfail(c, ABS_ESTATE, "accumulated steps keep the gradient in memory: switch abs_set_fused_update off");
   if (micro_b < 2 || micro_b > cap) return cfail(c, ABS_EINVAL, "micro_b must be in [2, b_cap]");
   if (b < 2) return cfail(c, ABS_EINVAL, "b must be at least 2");
   if (b % micro_b == 1) return cfail(c, ABS_EINVAL, "the last micro-batch would hold a single sample");
@@ -1041,6 +1113,7 @@ abs_status abs_cross_worker_test(abs_ctx *c, double eta, abs_test_result *out) t
   if (c->pl.M < 2) return cfail(c, ABS_EINVAL, "the cross-worker estimator needs M >= 2");
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
   if (c->last_ragged) return cfail(c, ABS_ESTATE, "the cross-worker estimator needs equal local batch sizes");
+  if (c->last_fused) return cfail(c, ABS_ESTATE, "the last step updated inside the weight-gradient epilogue: its gradient was not stored");
   const Plan &pl = c->pl;
   double *cw = c->at<double>(pl.o_cw);
   HIPCHK(c, launch_cross_worker(c->at<float>(pl.o_grad), pl.M, pl.Ppad, cw + 8, cw, c->stream));
@@ -1089,6 +1162,13 @@ abs_status abs_average_replicas(abs_ctx *c) try {
   return ABS_OK;
 } catch (...) { return on_exception(); }
 
+abs_status abs_set_fused_update(abs_ctx *c, int on) try {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (on && !c->pl.bf16) return cfail(c, ABS_EUNSUPPORTED, "the fused update needs ABS_PREC_BF16");
+  c->fused_update = on != 0;
+  return ABS_OK;
+} catch (...) { return on_exception(); }
+
 abs_status abs_get_counters(const abs_ctx *c, long long *rounds, long long *local_steps, long long *samples) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (rounds) *rounds = c->n_rounds;
@@ -1125,6 +1205,7 @@ abs_status abs_get_grad(abs_ctx *c, int m, float *out_host) try {
   if (!c || !out_host) return fail(ABS_EINVAL, "NULL argument");
   if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
+  if (c->last_fused) return cfail(c, ABS_ESTATE, "the last step updated inside the weight-gradient epilogue: its gradient was not stored");
   std::vector<float> in(c->pl.Ppad);
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(in.data(), c->at<float>(c->pl.o_grad) + (size_t)m * c->pl.Ppad, c->pl.Ppad * sizeof(float), hipMemcpyDeviceToHost));

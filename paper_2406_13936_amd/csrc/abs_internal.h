@@ -17,7 +17,8 @@ enum {
   EPI_LOGITS = 1,   // C(f32) = acc + bias[n]
   EPI_BWD = 2,      // C = acc * E[m][n]   (act == RELU: E > 0 ? 1 : 0 ; GELU: E itself)
   EPI_WGRAD = 3,    // C(f32) = alpha * acc ; C2(bf16) = same, rounded, if C2 != null
-  EPI_IPDOT = 4     // part[tile_n][m] = sum_{n in tile} E[m][n] * (acc + bias[n])
+  EPI_IPDOT = 4,    // part[tile_n][m] = sum_{n in tile} E[m][n] * (acc + bias[n])
+  EPI_WGRAD_UPD = 5 // internal to the bf16 family: EPI_WGRAD with the optimizer step in the epilogue (GemmP::upd_x)
 };
 
 struct GemmP {
@@ -53,6 +54,19 @@ struct GemmP {
   // kpart[(g * ksplit + sp) * Md * Nd] (row-major, ld = Nd) and C / C2 are left to launch_splitk_finish.
   int ksplit, kchunk;
   float *kpart;
+  // Optimizer step inside the epilogue (EPI_WGRAD of the bf16 family, optional: upd_x != null; needs ksplit <= 1,
+  // accumulate == 0 and ldc, the layer offsets and the group stride multiples of 4).  The finished gradient entry
+  // g = alpha * acc is not stored in C; instead the parameter at the same offset of upd_x (and its state in
+  // upd_v / upd_m, its bf16 shadow in upd_shadow; all laid out like C: group stride sCg, leading dimension ldc)
+  // takes its step.  C2 (the bf16 copy of the gradient) is still written.  Every wavefront leaves the sum of its
+  // squared gradient entries in upd_sq[g * upd_sSqg + upd_slot0 + tile * waves + wave] (tile = tm * tilesN + tn):
+  // the layer's share of ||gbar||^2, added up later in index order.
+  float *upd_x, *upd_v, *upd_m;
+  bf16_t *upd_shadow;
+  int upd_opt;
+  float upd_lr, upd_momentum, upd_beta1, upd_beta2, upd_eps, upd_wd, upd_c1, upd_c2;
+  const float *upd_scal;       // optional (device): {lr, c1, c2} read from memory (replayable launches)
+  float *upd_sq; long long upd_sSqg; int upd_slot0;
 };
 
 // bf16 MFMA family (gemm_bf16.hip).  Returns the number of column partials that
@@ -65,6 +79,11 @@ int gemm_bf16_row_parts(int Md, int Nd, int groups);
 int gemm_bf16_col_parts(int Md, int Nd, int groups);
 // Tile shape the bf16 family uses for an Md x Nd output over `groups` replicas: 0 = 128x64, 1 = 128x128, 2 = 256x256.
 int gemm_bf16_tile_shape(int Md, int Nd, int groups);
+// Tile shape of an EPI_WGRAD launch whose reduction runs over Kd samples: as above, or 3 = 128x128 with a k-step of
+// 32 and four work-groups per CU while the batch is short and the launch is bound by its epilogue's memory traffic.
+int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups);
+// Number of upd_sq slots an EPI_WGRAD launch with an in-epilogue optimizer step writes per group.
+int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups);
 // fp32 SIMT family (gemm_f32.hip); EPI_IPDOT is not offered (U is materialised instead).
 hipError_t launch_gemm_f32(const GemmP &p, int epi, hipStream_t s);
 
@@ -136,6 +155,7 @@ struct StatsP {
                             //   needs a stream synchronisation only, no copy
   const float *sq_wave;     // alternative source of S2 (grad must be null): per-wavefront sums of g^2 left by the
   long long n_sq_wave;      //   update kernel, n_sq_wave per group (one per 256 consecutive parameters)
+  long long sq_stride;      //   distance between two groups' sums (0: n_sq_wave)
   const int *rows;          // optional per-group sample counts (device) replacing b
   // which sums this launch produces: S1 and the loss (do_n), S3 and S4 (do_q; needs want_ip),
   // S2 (grad != null); acc_n / acc_q add to the stored sums instead of replacing them
@@ -153,6 +173,21 @@ struct UpdateP {
                             //   that a captured launch can be replayed with new values
 };
 hipError_t launch_update(const UpdateP &p, hipStream_t s);
+// The optimizer step of the bias vectors alone (layers l < n: width[l] entries at offset off[l] of every group's
+// vector of `stride` elements), with per-block sums of their squared gradient entries into sq.
+struct BiasUpdateP {
+  enum { MAXN = 16 };
+  int n;
+  int width[MAXN];
+  long long off[MAXN];
+  long long stride;
+  float *x; const float *g; float *v; float *m; bf16_t *shadow;
+  int opt; float lr, momentum, beta1, beta2, eps, wd, c1, c2;
+  const float *scal;
+  float *sq; long long sSqg; int slot0;
+};
+int update_bias_slots(const BiasUpdateP &p);
+hipError_t launch_update_bias(const BiasUpdateP &p, int groups, hipStream_t s);
 hipError_t launch_average_f32(float *x, bf16_t *shadow, float *mean, int groups, long long Ppad, hipStream_t s);
 hipError_t launch_average_bf16(bf16_t *x, bf16_t *mean, int groups, long long n, hipStream_t s);
 // cross-worker statistics: out[0] = sum_m ||g^m||^2, out[1] = ||mean_m g^m||^2;

@@ -60,6 +60,30 @@ __device__ __forceinline__ void act_fwd(float z, float &a, float &d) {
   else { a = z; d = 1.0f; }
 }
 
+// One parameter's optimizer step (the inner optimizers named in Sec. 4.2; formulas: SGD x - lr g; heavy ball
+// v <- mu v + g, x <- x - lr v; AdaGrad v <- v + g^2, x <- x - lr g / (sqrt v + eps); AdamW with bias
+// corrections c1 = 1/(1 - beta1^t), c2 = 1/(1 - beta2^t) and decoupled decay).  Used by the update kernel and by
+// the weight-gradient epilogue that applies the step in place; the same expression order in both.
+struct OptHyper { float lr, momentum, beta1, beta2, eps, wd, c1, c2; };
+template <int OPT>
+__device__ __forceinline__ void opt_step_elem(float &x, float g, float &v, float &m, const OptHyper &h) {
+  if (OPT == OPT_SGD) {
+    x = fmaf(-h.lr, g, x);
+  } else if (OPT == OPT_SHB) {
+    v = fmaf(h.momentum, v, g);
+    x = fmaf(-h.lr, v, x);
+  } else if (OPT == OPT_ADAGRAD) {
+    v = fmaf(g, g, v);
+    const float den = sqrtf(v) + h.eps;          // den == 0 only where no gradient has ever arrived
+    if (den > 0.f) x = x - h.lr * g / den;
+  } else {
+    m = fmaf(h.beta1, m, (1.0f - h.beta1) * g);
+    v = fmaf(h.beta2, v, (1.0f - h.beta2) * g * g);
+    const float mhat = m * h.c1, vhat = v * h.c2;
+    x = x * (1.0f - h.lr * h.wd) - h.lr * mhat / (sqrtf(vhat) + h.eps);
+  }
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

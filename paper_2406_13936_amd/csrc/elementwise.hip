@@ -344,8 +344,9 @@ __device__ __forceinline__ void stats_samples_block(const StatsP &p, int g, int 
   r = block_sum<4>(sl, red); if (threadIdx.x == 0) out[4 * STATS_PBLK] = r;
 }
 __device__ __forceinline__ void stats_gradsq_parts_block(const float *__restrict__ sq_wave, long long per_group,
-                                                         double *__restrict__ partials, int g, int blk, double *red) {
-  const float *p = sq_wave + (long long)g * per_group;
+                                                         long long stride, double *__restrict__ partials, int g, int blk,
+                                                         double *red) {
+  const float *p = sq_wave + (long long)g * (stride ? stride : per_group);
   double s = 0.0;
   for (long long i = blk * 256LL + threadIdx.x; i < per_group; i += 256LL * STATS_PBLK) s += (double)p[i];
   const double r = block_sum<4>(s, red);
@@ -357,7 +358,7 @@ __global__ void __launch_bounds__(256) stats_samples_kernel(const StatsP p, int 
   __shared__ double red[4];
   const int g = blockIdx.y, blk = blockIdx.x;
   if (blk < nb_samples) stats_samples_block(p, g, blk, nb_samples, red);
-  else stats_gradsq_parts_block(p.sq_wave, p.n_sq_wave, p.partials, g, blk - nb_samples, red);
+  else stats_gradsq_parts_block(p.sq_wave, p.n_sq_wave, p.sq_stride, p.partials, g, blk - nb_samples, red);
 }
 
 // Stage 1b (grid: PBLK x groups): ||gbar||^2 over the padded gradient vector.
@@ -407,6 +408,7 @@ template <int OPT, bool SHADOW, bool SQ>
 __global__ void __launch_bounds__(256) update_kernel(const UpdateP pin) {
   UpdateP p = pin;
   if (p.scal) { p.lr = p.scal[0]; p.c1 = p.scal[1]; p.c2 = p.scal[2]; }     // uniform loads
+  const OptHyper h = {p.lr, p.momentum, p.beta1, p.beta2, p.eps, p.wd, p.c1, p.c2};
   const long long n4 = p.n / 4;
   const long long stride = (long long)gridDim.x * 256;
   for (long long i = blockIdx.x * 256LL + threadIdx.x; i < n4; i += stride) {
@@ -418,42 +420,19 @@ __global__ void __launch_bounds__(256) update_kernel(const UpdateP pin) {
     }
     float xs[4] = {x.x, x.y, x.z, x.w};
     const float gs[4] = {g.x, g.y, g.z, g.w};
-    if (OPT == OPT_SGD) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) xs[k] = fmaf(-p.lr, gs[k], xs[k]);
-    } else if (OPT == OPT_SHB) {
-      float4 v = ld_stream(reinterpret_cast<const float4 *>(p.v) + i);
-      float vs[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        vs[k] = fmaf(p.momentum, vs[k], gs[k]);
-        xs[k] = fmaf(-p.lr, vs[k], xs[k]);
-      }
-      st_stream(reinterpret_cast<float4 *>(p.v) + i, make_float4(vs[0], vs[1], vs[2], vs[3]));
-    } else if (OPT == OPT_ADAGRAD) {
-      float4 v = ld_stream(reinterpret_cast<const float4 *>(p.v) + i);
-      float vs[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        vs[k] = fmaf(gs[k], gs[k], vs[k]);
-        const float den = sqrtf(vs[k]) + p.eps;          // den == 0 only where no gradient has ever arrived
-        if (den > 0.f) xs[k] = xs[k] - p.lr * gs[k] / den;
-      }
-      st_stream(reinterpret_cast<float4 *>(p.v) + i, make_float4(vs[0], vs[1], vs[2], vs[3]));
-    } else {
-      float4 v = ld_stream(reinterpret_cast<const float4 *>(p.v) + i);
-      float4 m = ld_stream(reinterpret_cast<const float4 *>(p.m) + i);
-      float vs[4] = {v.x, v.y, v.z, v.w}, ms[4] = {m.x, m.y, m.z, m.w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        ms[k] = fmaf(p.beta1, ms[k], (1.0f - p.beta1) * gs[k]);
-        vs[k] = fmaf(p.beta2, vs[k], (1.0f - p.beta2) * gs[k] * gs[k]);
-        const float mhat = ms[k] * p.c1, vhat = vs[k] * p.c2;
-        xs[k] = xs[k] * (1.0f - p.lr * p.wd) - p.lr * mhat / (sqrtf(vhat) + p.eps);
-      }
-      st_stream(reinterpret_cast<float4 *>(p.v) + i, make_float4(vs[0], vs[1], vs[2], vs[3]));
-      st_stream(reinterpret_cast<float4 *>(p.m) + i, make_float4(ms[0], ms[1], ms[2], ms[3]));
+    float vs[4] = {0.f, 0.f, 0.f, 0.f}, ms[4] = {0.f, 0.f, 0.f, 0.f};
+    if (OPT != OPT_SGD) {
+      const float4 v = ld_stream(reinterpret_cast<const float4 *>(p.v) + i);
+      vs[0] = v.x; vs[1] = v.y; vs[2] = v.z; vs[3] = v.w;
     }
+    if (OPT == OPT_ADAMW) {
+      const float4 m = ld_stream(reinterpret_cast<const float4 *>(p.m) + i);
+      ms[0] = m.x; ms[1] = m.y; ms[2] = m.z; ms[3] = m.w;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) opt_step_elem<OPT>(xs[k], gs[k], vs[k], ms[k], h);
+    if (OPT != OPT_SGD) st_stream(reinterpret_cast<float4 *>(p.v) + i, make_float4(vs[0], vs[1], vs[2], vs[3]));
+    if (OPT == OPT_ADAMW) st_stream(reinterpret_cast<float4 *>(p.m) + i, make_float4(ms[0], ms[1], ms[2], ms[3]));
     st_stream(reinterpret_cast<float4 *>(p.x) + i, make_float4(xs[0], xs[1], xs[2], xs[3]));
     if (SHADOW) {
       uint2 o;
@@ -462,6 +441,31 @@ __global__ void __launch_bounds__(256) update_kernel(const UpdateP pin) {
       st_stream(reinterpret_cast<uint2 *>(p.shadow) + i, o);
     }
   }
+}
+
+// The step of the bias vectors alone, for steps whose weights were updated inside the weight-gradient epilogue.
+// grid (ceil(max width / 256), groups, layers); one bias per thread; each block also leaves the sum of its
+// squared gradient entries in sq[g * sSqg + slot0 + (layer * gridDim.x + blockIdx.x)] (their share of ||gbar||^2).
+template <int OPT>
+__global__ void __launch_bounds__(256) update_bias_kernel(const BiasUpdateP p) {
+  __shared__ double red[4];
+  const int l = blockIdx.z, g = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+  OptHyper h = {p.lr, p.momentum, p.beta1, p.beta2, p.eps, p.wd, p.c1, p.c2};
+  if (p.scal) { h.lr = p.scal[0]; h.c1 = p.scal[1]; h.c2 = p.scal[2]; }
+  float gg = 0.0f;
+  if (j < p.width[l]) {
+    const long long o = (long long)g * p.stride + p.off[l] + j;
+    const float gr = p.g[o];
+    float x = p.x[o], v = OPT != OPT_SGD ? p.v[o] : 0.0f, m = OPT == OPT_ADAMW ? p.m[o] : 0.0f;
+    opt_step_elem<OPT>(x, gr, v, m, h);
+    p.x[o] = x;
+    if (OPT != OPT_SGD) p.v[o] = v;
+    if (OPT == OPT_ADAMW) p.m[o] = m;
+    if (p.shadow) p.shadow[o] = f2bf(x);
+    gg = gr * gr;
+  }
+  const double r = block_sum<4>((double)gg, red);
+  if (threadIdx.x == 0) p.sq[(long long)g * p.sSqg + p.slot0 + l * gridDim.x + blockIdx.x] = (float)r;
 }
 
 // ---- replica average ------------------------------------------------------------------------
@@ -515,18 +519,35 @@ __global__ void __launch_bounds__(256) average_bf16_kernel(bf16_t *__restrict__ 
 // (all replicas, same order of additions, same division) and leaves the mean in a buffer of one replica's
 // size, the second only writes (its one read, the mean, comes from the caches).  HBM serves a pure read
 // stream and a pure write stream faster than their mixture, which more than pays for the extra buffer.
+// A block reads U * 4 KB of consecutive bytes from every replica: U independent vectors per thread keep more
+// loads in flight (U = 4: the read pass of a 32-way average 3 % faster than with one vector per thread).
+template <int U>
 __global__ void __launch_bounds__(256) average_f32_reduce_kernel(const float *__restrict__ x, float *__restrict__ mean,
                                                                  int groups, long long Ppad) {
-  const long long i = blockIdx.x * 256LL + threadIdx.x;
-  if (i >= Ppad / 4) return;
+  const long long n4 = Ppad / 4;
+  const long long base = (long long)blockIdx.x * (256 * U) + threadIdx.x;
   const float Mf = (float)groups;
-  float4 s = ld_stream(reinterpret_cast<const float4 *>(x) + i);
-  for (int g = 1; g < groups; ++g) {
-    const float4 v = ld_stream(reinterpret_cast<const float4 *>(x + (long long)g * Ppad) + i);
-    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  float4 s[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const long long i = base + u * 256;
+    s[u] = i < n4 ? ld_stream(reinterpret_cast<const float4 *>(x) + i) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  s.x /= Mf; s.y /= Mf; s.z /= Mf; s.w /= Mf;
-  reinterpret_cast<float4 *>(mean)[i] = s;
+  for (int g = 1; g < groups; ++g) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long i = base + u * 256;
+      if (i < n4) {
+        const float4 v = ld_stream(reinterpret_cast<const float4 *>(x + (long long)g * Ppad) + i);
+        s[u].x += v.x; s[u].y += v.y; s[u].z += v.z; s[u].w += v.w;
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const long long i = base + u * 256;
+    if (i < n4) reinterpret_cast<float4 *>(mean)[i] = make_float4(s[u].x / Mf, s[u].y / Mf, s[u].z / Mf, s[u].w / Mf);
+  }
 }
 template <bool SHADOW>
 __global__ void __launch_bounds__(256) average_f32_spread_kernel(const float *__restrict__ mean, float *__restrict__ x,
@@ -541,25 +562,42 @@ __global__ void __launch_bounds__(256) average_f32_spread_kernel(const float *__
     if (SHADOW) st_stream(reinterpret_cast<uint2 *>(shadow + (long long)g * Ppad) + i, o);
   }
 }
+template <int U>
 __global__ void __launch_bounds__(256) average_bf16_reduce_kernel(const bf16_t *__restrict__ x, bf16_t *__restrict__ mean,
                                                                   int groups, long long n) {
-  const long long i = blockIdx.x * 256LL + threadIdx.x;
-  if (i >= n / 8) return;
+  const long long n8 = n / 8;
+  const long long base = (long long)blockIdx.x * (256 * U) + threadIdx.x;
   const float Mf = (float)groups;
-  float s[8];
-  Vec<bf16_t>::load_stream(x + i * 8, s);
-  for (int g = 1; g < groups; ++g) {
-    float v[8];
-    Vec<bf16_t>::load_stream(x + (long long)g * n + i * 8, v);
+  float s[U][8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) s[k] += v[k];
+  for (int u = 0; u < U; ++u) {
+    const long long i = base + u * 256;
+    if (i < n8) Vec<bf16_t>::load_stream(x + i * 8, s[u]);
   }
-  uint4 o;
-  o.x = pack2bf(s[0] / Mf, s[1] / Mf);
-  o.y = pack2bf(s[2] / Mf, s[3] / Mf);
-  o.z = pack2bf(s[4] / Mf, s[5] / Mf);
-  o.w = pack2bf(s[6] / Mf, s[7] / Mf);
-  reinterpret_cast<uint4 *>(mean)[i] = o;
+  for (int g = 1; g < groups; ++g) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long i = base + u * 256;
+      if (i < n8) {
+        float v[8];
+        Vec<bf16_t>::load_stream(x + (long long)g * n + i * 8, v);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s[u][k] += v[k];
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const long long i = base + u * 256;
+    if (i < n8) {
+      uint4 o;
+      o.x = pack2bf(s[u][0] / Mf, s[u][1] / Mf);
+      o.y = pack2bf(s[u][2] / Mf, s[u][3] / Mf);
+      o.z = pack2bf(s[u][4] / Mf, s[u][5] / Mf);
+      o.w = pack2bf(s[u][6] / Mf, s[u][7] / Mf);
+      reinterpret_cast<uint4 *>(mean)[i] = o;
+    }
+  }
 }
 __global__ void __launch_bounds__(256) average_bf16_spread_kernel(const bf16_t *__restrict__ mean, bf16_t *__restrict__ x,
                                                                   int groups, long long n) {
@@ -823,13 +861,32 @@ hipError_t launch_update(const UpdateP &p, hipStream_t s) {
   return hipGetLastError();
 }
 
+int update_bias_slots(const BiasUpdateP &p) {
+  int mx = 0;
+  for (int l = 0; l < p.n; ++l) mx = p.width[l] > mx ? p.width[l] : mx;
+  return p.n * ((mx + 255) / 256);
+}
+
+hipError_t launch_update_bias(const BiasUpdateP &p, int groups, hipStream_t s) {
+  if (p.n < 1 || p.n > BiasUpdateP::MAXN) return hipErrorInvalidValue;
+  int mx = 0;
+  for (int l = 0; l < p.n; ++l) mx = p.width[l] > mx ? p.width[l] : mx;
+  const dim3 grid((mx + 255) / 256, groups, p.n), blk(256);
+  if (p.opt == OPT_SGD) hipLaunchKernelGGL(update_bias_kernel<OPT_SGD>, grid, blk, 0, s, p);
+  else if (p.opt == OPT_SHB) hipLaunchKernelGGL(update_bias_kernel<OPT_SHB>, grid, blk, 0, s, p);
+  else if (p.opt == OPT_ADAGRAD) hipLaunchKernelGGL(update_bias_kernel<OPT_ADAGRAD>, grid, blk, 0, s, p);
+  else hipLaunchKernelGGL(update_bias_kernel<OPT_ADAMW>, grid, blk, 0, s, p);
+  return hipGetLastError();
+}
+
 // Blocks of at least this many elements over all replicas take the two-pass form when the caller brings a buffer.
 static constexpr long long AVERAGE_TWO_PASS_MIN = 32LL << 20;
 
 hipError_t launch_average_f32(float *x, bf16_t *shadow, float *mean, int groups, long long Ppad, hipStream_t s) {
   const dim3 grid(grid_for(Ppad / 4, 256, 1 << 30)), blk(256);
   if (mean && groups > 1 && (long long)groups * Ppad >= AVERAGE_TWO_PASS_MIN) {
-    hipLaunchKernelGGL(average_f32_reduce_kernel, grid, blk, 0, s, x, mean, groups, Ppad);
+    const dim3 rgrid(grid_for((Ppad / 4 + 3) / 4, 256, 1 << 30));
+    hipLaunchKernelGGL(average_f32_reduce_kernel<4>, rgrid, blk, 0, s, x, mean, groups, Ppad);
     if (shadow) hipLaunchKernelGGL(average_f32_spread_kernel<true>, grid, blk, 0, s, mean, x, shadow, groups, Ppad);
     else hipLaunchKernelGGL(average_f32_spread_kernel<false>, grid, blk, 0, s, mean, x, shadow, groups, Ppad);
     return hipGetLastError();
@@ -842,7 +899,8 @@ hipError_t launch_average_f32(float *x, bf16_t *shadow, float *mean, int groups,
 hipError_t launch_average_bf16(bf16_t *x, bf16_t *mean, int groups, long long n, hipStream_t s) {
   const dim3 grid(grid_for(n / 8, 256, 1 << 30)), blk(256);
   if (mean && groups > 1 && (long long)groups * n >= AVERAGE_TWO_PASS_MIN) {
-    hipLaunchKernelGGL(average_bf16_reduce_kernel, grid, blk, 0, s, x, mean, groups, n);
+    const dim3 rgrid(grid_for((n / 8 + 3) / 4, 256, 1 << 30));
+    hipLaunchKernelGGL(average_bf16_reduce_kernel<4>, rgrid, blk, 0, s, x, mean, groups, n);
     hipLaunchKernelGGL(average_bf16_spread_kernel, grid, blk, 0, s, mean, x, groups, n);
     return hipGetLastError();
   }

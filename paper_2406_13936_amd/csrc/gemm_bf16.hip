@@ -58,6 +58,10 @@ __device__ __forceinline__ void st_once(bf16_t *p, uint2 v) {
   const u32x2_t w = {v.x, v.y};
   __builtin_nontemporal_store(w, reinterpret_cast<u32x2_t *>(p));
 }
+__device__ __forceinline__ float4 ld_once(const float *p) {
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ void st_once(float *p, float4 v) {
   const f32x4_t w = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(w, reinterpret_cast<f32x4_t *>(p));
@@ -176,6 +180,7 @@ __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int nblk, const int chunk) {
   constexpr int NW = WM * WN, NT = NW * 64;
   constexpr int TM = BM / WM, TN = BN / WN;
+  constexpr bool IS_WGRAD = EPI == EPI_WGRAD || EPI == EPI_WGRAD_UPD;   // _UPD: ACT carries the optimizer
   constexpr int MI = TM / 32, NI = TN / 32;
   constexpr int STAGE = (BM + BN) * BK;                 // bf16 elements per stage
   constexpr int NPART = BK / 16;                        // MFMA groups per k-tile
@@ -195,7 +200,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   const int per_g = tilesM * tilesN;
   const int vg = lb / per_g;                      // group, or (group, k-slice) pair of a split reduction
   const int t = lb - vg * per_g;
-  const int ksplit = (EPI == EPI_WGRAD && pin.ksplit > 1) ? pin.ksplit : 1;
+  const int ksplit = (EPI == EPI_WGRAD && pin.ksplit > 1) ? pin.ksplit : 1;   // (no split with the step fused)
   const int gv = vg / ksplit, ksl = vg - gv * ksplit;
   const int g = pin.gperm ? pin.gperm[gv] : gv;   // position in the launch order -> group
   const int tm = t / tilesN, tn = t - tm * tilesN;
@@ -561,7 +566,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   constexpr int FIT = 32 * FCPR / 64;                       // chunks per lane per slice
   float *stf = reinterpret_cast<float *>(smem) + wave * (32 * FLD);
   float *Cg = static_cast<float *>(p.C) + (long long)g * p.sCg;
-  bf16_t *C2g = (EPI == EPI_WGRAD && p.C2) ? static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g : nullptr;
+  bf16_t *C2g = (IS_WGRAD && p.C2) ? static_cast<bf16_t *>(p.C2) + (long long)g * p.sC2g : nullptr;
   bool accumulate = EPI == EPI_WGRAD && p.accumulate;        // micro-batch accumulation: C += alpha * acc
   if (EPI == EPI_WGRAD && ksplit > 1) {                      // raw partial product of this k-slice
     Cg = p.kpart + ((long long)g * ksplit + ksl) * p.Md * p.Nd;
@@ -570,6 +575,93 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   }
   const bool vec_ok = (p.ldc & 3) == 0 && (!C2g || (p.ldc2 & 3) == 0);
   __syncthreads();                                          // stages are dead
+  if constexpr (EPI == EPI_WGRAD_UPD) {
+    // The optimizer step in place of the gradient store: a lane's staged float4 holds four consecutive entries
+    // of one row of Gbar_l; the parameters, their state and their bf16 shadow sit at the same offsets.
+    const long long goff = (long long)g * p.sCg;
+    float *__restrict__ X = p.upd_x + goff;
+    float *__restrict__ V = p.upd_v ? p.upd_v + goff : nullptr;
+    float *__restrict__ Mo = p.upd_m ? p.upd_m + goff : nullptr;
+    bf16_t *__restrict__ SH = p.upd_shadow ? p.upd_shadow + goff : nullptr;
+    OptHyper h = {p.upd_lr, p.upd_momentum, p.upd_beta1, p.upd_beta2, p.upd_eps, p.upd_wd, p.upd_c1, p.upd_c2};
+    if (p.upd_scal) { h.lr = p.upd_scal[0]; h.c1 = p.upd_scal[1]; h.c2 = p.upd_scal[2]; }     // uniform loads
+    constexpr int opt = ACT;                                 // the optimizer travels in the activation slot
+    float sq = 0.0f;
+    // The slices (32 rows x TN columns per wave) are walked in batches of HB chunks per lane.  The loads of batch
+    // k + 1 (parameters and optimizer state) are issued before batch k is processed, so that a wave always has a
+    // batch of loads in flight while it computes and stores.
+    constexpr int HB = FIT < 2 ? FIT : 2;
+    constexpr int BPS = FIT / HB, NBATCH = MI * BPS;
+    static_assert(FIT % HB == 0, "chunk batches");
+    float4 xq[2][HB], vq[2][HB], mq[2][HB];
+    auto where = [&](int bi, int u, int &m, int &n, int &row, int &cc) {
+      const int c = ((bi % BPS) * HB + u) * 64 + lane;
+      row = c / FCPR; cc = c % FCPR;
+      m = m0 + wm * TM + (bi / BPS) * 32 + row;
+      n = nw0 + cc * 4;
+    };
+    auto prefetch = [&](int bi) {
+#pragma unroll
+      for (int u = 0; u < HB; ++u) {
+        int m, n, row, cc;
+        where(bi, u, m, n, row, cc);
+        xq[bi & 1][u] = vq[bi & 1][u] = mq[bi & 1][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (m < p.Md && n < p.Nd) {                          // Nd is a multiple of 4 (checked by the launcher)
+          const long long o = (long long)m * p.ldc + n;
+          xq[bi & 1][u] = ld_once(X + o);
+          if (opt != OPT_SGD) vq[bi & 1][u] = ld_once(V + o);
+          if (opt == OPT_ADAMW) mq[bi & 1][u] = ld_once(Mo + o);
+        }
+      }
+    };
+    prefetch(0);
+#pragma unroll
+    for (int bi = 0; bi < NBATCH; ++bi) {
+      if (bi % BPS == 0) {                                   // a new slice: accumulators -> staging
+        const int i = bi / BPS;
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float4 o = make_float4(acc[i][j][4 * q] * p.alpha, acc[i][j][4 * q + 1] * p.alpha,
+                                         acc[i][j][4 * q + 2] * p.alpha, acc[i][j][4 * q + 3] * p.alpha);
+            *reinterpret_cast<float4 *>(stf + lcol * FLD + j * 32 + q * 8 + lhalf * 4) = o;
+          }
+      }
+      if (bi + 1 < NBATCH) prefetch(bi + 1);
+#pragma unroll
+      for (int u = 0; u < HB; ++u) {
+        int m, n, row, cc;
+        where(bi, u, m, n, row, cc);
+        if (m >= p.Md || n >= p.Nd) continue;
+        const long long o = (long long)m * p.ldc + n;
+        const float4 gv = *reinterpret_cast<const float4 *>(stf + row * FLD + cc * 4);
+        const float gs[4] = {gv.x, gv.y, gv.z, gv.w};
+        float xs[4] = {xq[bi & 1][u].x, xq[bi & 1][u].y, xq[bi & 1][u].z, xq[bi & 1][u].w};
+        float vs[4] = {vq[bi & 1][u].x, vq[bi & 1][u].y, vq[bi & 1][u].z, vq[bi & 1][u].w};
+        float ms[4] = {mq[bi & 1][u].x, mq[bi & 1][u].y, mq[bi & 1][u].z, mq[bi & 1][u].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) opt_step_elem<opt>(xs[e], gs[e], vs[e], ms[e], h);
+        sq = fmaf(gs[0], gs[0], fmaf(gs[1], gs[1], fmaf(gs[2], gs[2], fmaf(gs[3], gs[3], sq))));
+        st_once(X + o, make_float4(xs[0], xs[1], xs[2], xs[3]));
+        if (opt != OPT_SGD) st_once(V + o, make_float4(vs[0], vs[1], vs[2], vs[3]));
+        if (opt == OPT_ADAMW) st_once(Mo + o, make_float4(ms[0], ms[1], ms[2], ms[3]));
+        if (SH) {
+          uint2 w;
+          w.x = pack2bf(xs[0], xs[1]); w.y = pack2bf(xs[2], xs[3]);
+          st_once(SH + o, w);
+        }
+        if (C2g) {
+          uint2 w;
+          w.x = pack2bf(gs[0], gs[1]); w.y = pack2bf(gs[2], gs[3]);
+          st_once(C2g + (long long)m * p.ldc2 + n, w);
+        }
+      }
+    }
+    sq = wave_sum(sq);
+    if (lane == 0) p.upd_sq[(long long)g * p.upd_sSqg + p.upd_slot0 + (long long)t * NW + wave] = sq;
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     const int mrow0 = m0 + wm * TM + i * 32;
@@ -578,7 +670,7 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float4 o;
-        if (EPI == EPI_WGRAD) {
+        if (IS_WGRAD) {
           o = make_float4(acc[i][j][4 * q] * p.alpha, acc[i][j][4 * q + 1] * p.alpha, acc[i][j][4 * q + 2] * p.alpha,
                           acc[i][j][4 * q + 3] * p.alpha);
         } else {
@@ -648,24 +740,38 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
 // otherwise a 128x128 (or 128x64 for narrow outputs) tile.
 template <bool AT, bool BT, int EPI, int ACT>
 hipError_t launch_shape(const GemmP &p, hipStream_t s) {
-  switch (gemm_bf16_tile_shape(p.Md, p.Nd, p.groups)) {
+  constexpr bool IS_WGRAD = EPI == EPI_WGRAD || EPI == EPI_WGRAD_UPD;
+  switch (IS_WGRAD ? gemm_bf16_wgrad_shape(p.Md, p.Nd, p.Kd, p.groups) : gemm_bf16_tile_shape(p.Md, p.Nd, p.groups)) {
     case 0: return launch_cfg<128, 64, 64, 4, 1, 3, AT, BT, EPI, ACT>(p, s);
+    case 3:
+      if constexpr (IS_WGRAD) return launch_cfg<128, 128, 32, 2, 2, 2, AT, BT, EPI, ACT>(p, s);
+      else return hipErrorInvalidValue;
     case 2: return launch_cfg<256, 256, 64, 2, 4, 2, AT, BT, EPI, ACT>(p, s);
     default: {
-      // Two stages (64 KB) let two work-groups share a CU, three keep one work-group fed through a long
+      // Two stages (64 KB) let two work-groups share a CU; a deeper ring keeps one work-group fed through a long
       // reduction.  Two when the reduction is short or the launch has more blocks than CUs (measured: 2048-wide
       // layers at b = 256, 512 blocks: 43 against 62 us; 1024 blocks of a 100-wide output: 145 against 163 us;
-      // 256 blocks: three stages win); three otherwise.
+      // 256 blocks: the deeper ring wins); four stages (128 KB, still one work-group per CU, three k-tiles in
+      // flight: such launches are bound by the latency of their operand stream) otherwise.
       const long long nblk = (long long)((p.Md + 127) / 128) * ((p.Nd + 127) / 128) * p.groups *
                              ((EPI == EPI_WGRAD && p.ksplit > 1) ? p.ksplit : 1);
       if (p.Kd <= 1024 || nblk > 256) return launch_cfg<128, 128, 64, 2, 2, 2, AT, BT, EPI, ACT>(p, s);
-      return launch_cfg<128, 128, 64, 2, 2, 3, AT, BT, EPI, ACT>(p, s);
+      return launch_cfg<128, 128, 64, 2, 2, 4, AT, BT, EPI, ACT>(p, s);
     }
   }
 }
 
 template <bool AT, bool BT, int EPI>
 hipError_t launch_act(const GemmP &p, hipStream_t s) {
+  if constexpr (EPI == EPI_WGRAD_UPD) {          // the optimizer is a compile-time constant of the fused epilogue
+    switch (p.upd_opt) {
+      case OPT_SGD: return launch_shape<AT, BT, EPI, OPT_SGD>(p, s);
+      case OPT_SHB: return launch_shape<AT, BT, EPI, OPT_SHB>(p, s);
+      case OPT_ADAMW: return launch_shape<AT, BT, EPI, OPT_ADAMW>(p, s);
+      case OPT_ADAGRAD: return launch_shape<AT, BT, EPI, OPT_ADAGRAD>(p, s);
+      default: return hipErrorInvalidValue;
+    }
+  }
   if constexpr (EPI == EPI_FWD_ACT || EPI == EPI_BWD) {
     switch (p.act) {
       case ACT_RELU: return launch_shape<AT, BT, EPI, ACT_RELU>(p, s);
@@ -690,6 +796,22 @@ int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
     if (tiles >= 256 && 10LL * Md >= 7LL * tm * 256) return 2;
   }
   return 1;
+}
+
+// Weight gradients reduce over the local batch (Kd = b).  While the batch is short the launch is all epilogue
+// (one or a few k-tiles, then 4 to 20 bytes of stores and loads per output entry): a 128 x 128 x 32 tile with two
+// 16 KB stages lets four work-groups share a CU, which keeps far more memory requests in flight than one
+// 256 x 256 work-group does.
+int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups) {
+  const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
+  if (sh != 0 && Kd <= 256) return 3;
+  return sh;
+}
+
+int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups) {
+  const int bm[4] = {128, 128, 256, 128}, bn[4] = {64, 128, 256, 128}, nw[4] = {4, 4, 8, 4};
+  const int sh = gemm_bf16_wgrad_shape(Md, Nd, Kd, groups);
+  return ((Md + bm[sh] - 1) / bm[sh]) * ((Nd + bn[sh] - 1) / bn[sh]) * nw[sh];
 }
 
 int gemm_bf16_row_parts(int Md, int Nd, int groups) {
@@ -731,6 +853,10 @@ hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s) {
   if (p.ksplit > 1 && (epi != EPI_WGRAD || !p.kpart || p.kchunk <= 0 || (p.kchunk & 63) ||
                        (long long)p.kchunk * p.ksplit < p.Kd || (p.Nd & 3)))
     return hipErrorInvalidValue;
+  if (p.upd_x && (epi != EPI_WGRAD || p.ksplit > 1 || p.accumulate || !p.upd_sq || (p.ldc & 3) || (p.Nd & 3) ||
+                  (p.sCg & 3) || (reinterpret_cast<uintptr_t>(p.upd_x) & 15) || (p.C2 && ((p.ldc2 & 3) || p.ldc2 != p.ldc)) ||
+                  (p.upd_opt != OPT_SGD && !p.upd_v) || (p.upd_opt == OPT_ADAMW && !p.upd_m)))
+    return hipErrorInvalidValue;
   if (!p.a_trans && !p.b_trans) {
     if (epi == EPI_FWD_ACT) return launch_act<false, false, EPI_FWD_ACT>(p, s);
     if (epi == EPI_LOGITS) return launch_act<false, false, EPI_LOGITS>(p, s);
@@ -738,7 +864,7 @@ hipError_t launch_gemm_bf16(const GemmP &p, int epi, hipStream_t s) {
   } else if (!p.a_trans && p.b_trans) {
     if (epi == EPI_BWD) return launch_act<false, true, EPI_BWD>(p, s);
   } else if (p.a_trans && p.b_trans) {
-    if (epi == EPI_WGRAD) return launch_act<true, true, EPI_WGRAD>(p, s);
+    if (epi == EPI_WGRAD) return p.upd_x ? launch_act<true, true, EPI_WGRAD_UPD>(p, s) : launch_act<true, true, EPI_WGRAD>(p, s);
   }
   return hipErrorInvalidValue;
 }

@@ -75,7 +75,7 @@ def _significant(grad, frac=5e-2):
 
 
 def _lockstep(w, rounds, stat_tol, band, resync_params, param_tol=None, mixed=None, max_steps=None,
-              ratio_tol=None, step_param_tol=None, sample_at_cap=None):
+              ratio_tol=None, step_param_tol=None, sample_at_cap=None, fused=False):
     """Run GPU and oracle side by side.  At every step and for every worker the statistics are compared
     (stat_tol), the tested ratio (ratio_tol), T and the pass flag (_check_decision); where the next batch size
     differs, every worker whose T differs has been shown to sit inside `band` of a decision boundary, and the
@@ -91,6 +91,8 @@ def _lockstep(w, rounds, stat_tol, band, resync_params, param_tol=None, mixed=No
     if ratio_tol is None:
         ratio_tol = 2e-2 if w.prec == W.PREC_BF16 else 1e-4      # the target statement's statistic tolerances
     rep = A.Replicas.from_workload(w, X, y, x0)
+    if fused:
+        rep.set_fused_update(True)       # the optimizer step inside the weight-gradient epilogue
     orc = _oracle_for(w, X, y, x0, mixed)
     adam_like = w.opt in (W.OPT_ADAMW, W.OPT_ADAGRAD)
     b, exempt, steps, worst, worst_p = w.b0, 0, 0, 0.0, 0.0
@@ -543,6 +545,138 @@ def test_bf16_free_running_twin_with_heavy_ball_and_adamw(opt, lr):
                    b_cap=96, opt=opt, lr=lr, momentum=0.9, weight_decay=0.05, test=W.TEST_NORM, eta=0.6,
                    data="teacher_mlp", seed=6)
     _lockstep(w, w.rounds, stat_tol=5e-4, band=BF16_BAND, resync_params=False, param_tol=1e-3)
+
+
+# ---------------------------------------------------------------------------------------------
+# optimizer step inside the weight-gradient epilogue (opt-in)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dims,act,bs,opt,hb", [
+    ((136, 264, 100), W.ACT_GELU, [517] * 3, W.OPT_SHB, True),                       # 128x128 and 128x64 tiles, ragged edges
+    ((384, 256, 256, 256, 100), W.ACT_GELU, [64] * 4, W.OPT_SHB, True),              # config-3 twin at its first size
+    ((784, 512, 512, 12), W.ACT_RELU, [300] * 2, W.OPT_ADAMW, True),
+    ((1024, 1024, 1024, 100), W.ACT_RELU, [72] * 2, W.OPT_ADAGRAD, False),           # 256x256 tiles, one k-tile
+    ((1024, 1280, 100), W.ACT_GELU, [1100, 260, 2], W.OPT_SGD, True),                # ragged workers, 256x256 tiles
+    ((136, 264, 100), W.ACT_RELU, [40, 300, 7, 129, 2, 517, 64, 260, 33], W.OPT_SHB, True),
+])
+def test_fused_update_step_matches_oracle(dims, act, bs, opt, hb):
+    """Two steps with the optimizer step applied inside the weight-gradient epilogue (the second one starts from
+    non-zero optimizer state): statistics, per-sample quantities, parameters and optimizer state against the oracle;
+    the calls that need the stored gradient are refused."""
+    A = _A()
+    M, ragged = len(bs), len(set(bs)) > 1
+    w = W.Workload("fused", dims, act, hb, W.PREC_BF16, N=2048, M=M, H=1, rounds=1, b0=max(bs), b_cap=max(bs) + 5, opt=opt,
+                   lr=0.02, momentum=0.9, weight_decay=0.05, test=W.TEST_AUG_IP, theta=0.9, nu=0.5, data="teacher_mlp",
+                   seed=47)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    rep.set_fused_update(True)
+    orc = _oracle_for(w, X, y, x0, mixed=True)
+    try:
+        for step in range(2):
+            rows = [W.batch_indices(w.seed, step, 0, m, b, w.N) for m, b in enumerate(bs)]
+            if ragged:
+                rep.local_step_ragged(rows, w.lr)
+            else:
+                rep.local_step(np.stack(rows), w.lr)
+            orc.local_step(rows, w.lr)
+            g, o = rep.inner_product_test(w.theta, w.nu), orc.test(W.TEST_AUG_IP, theta=w.theta, nu=w.nu)
+            for m in range(M):
+                st = orc.stats[m]
+                n, q = rep.get_per_sample(m, bs[m], want_q=True)
+                # a single sample may sit on a bf16 rounding tie of a hidden unit (fp32 against fp64 accumulation)
+                rel_n = np.abs(n - st["n"]) / st["n"]
+                assert rel_n.max() <= 2e-2 and np.sum(rel_n > 5e-3) <= 1 + 2e-3 * bs[m], (step, m, rel_n.max())
+                np.testing.assert_allclose(q, st["q"], rtol=2e-2, atol=2e-3 * np.abs(st["q"]).max())
+                for name, got, want in (("S1", g[m].sum_sq, st["S1"]), ("S2", g[m].gbar_sq, st["S2"]),
+                                        ("S3", g[m].sum_q2, st["S3"]), ("S4", g[m].sum_q, st["S4"]),
+                                        ("loss", g[m].loss_sum, st["loss_sum"])):
+                    assert _rel(got, want) <= 2e-3, (step, m, name, got, want)
+                if bs[m] > 2:
+                    assert _rel(g[m].ratio, o[m]["ratio"]) <= 2e-2
+                    _check_decision(g[m], o[m], bs[m], 2e-3, (step, m))
+                p = rep.get_params(m).astype(np.float64)
+                sel = _significant(orc.grads[m], 1e-2) if opt in (W.OPT_ADAMW, W.OPT_ADAGRAD) else slice(None)
+                assert np.abs(p - orc.x[m])[sel].max() <= 1e-3 * np.abs(orc.x[m]).max(), (step, m)
+                if opt != W.OPT_SGD:
+                    v = rep.get_opt_state(m, 0).astype(np.float64)
+                    assert np.abs(v - orc.st[m].v).max() <= 4e-3 * np.abs(orc.st[m].v).max()
+                if opt == W.OPT_ADAMW:
+                    mm = rep.get_opt_state(m, 1).astype(np.float64)
+                    assert np.abs(mm - orc.st[m].m).max() <= 4e-3 * np.abs(orc.st[m].m).max()
+                # teacher forcing between the two steps
+                orc.x[m] = p
+                if opt != W.OPT_SGD:
+                    orc.st[m].v = rep.get_opt_state(m, 0).astype(np.float64)
+                if opt == W.OPT_ADAMW:
+                    orc.st[m].m = rep.get_opt_state(m, 1).astype(np.float64)
+            with pytest.raises(A.AbsError, match="not stored"):
+                rep.get_grad(0)
+            if M >= 2 and not ragged:
+                with pytest.raises(A.AbsError, match="not stored"):
+                    rep.cross_worker_test(0.5)
+        with pytest.raises(A.AbsError, match="accumulated"):
+            rep.local_step_accumulated(np.stack([r[:max(bs)] for r in rows]) if not ragged else np.zeros((M, 8), np.int32), 4, w.lr)
+        assert rep.guard_intact()
+        assert rep.counters() == (0, 2, 2 * sum(bs))
+    finally:
+        rep.close()
+
+
+def test_fused_update_equals_the_unfused_step_and_falls_back_when_a_reduction_is_split():
+    """Same inputs through the fused and the plain path: identical per-sample statistics (bit for bit: the same
+    kernels produce them), ||gbar||^2 equal up to the order of its additions, parameters bit-equal (the same
+    expression on the same gradient entries).  A batch long enough for split weight-gradient reductions takes the
+    plain path even when the fused one is switched on, and its gradient can be read."""
+    A = _A()
+    w = _one_step_case((384, 256, 256, 100), W.ACT_GELU, W.PREC_BF16, 200, 3, opt=W.OPT_SHB, N=1024)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    out = []
+    for fused in (False, True):
+        rep = A.Replicas.from_workload(w, X, y, x0)
+        try:
+            rep.set_fused_update(fused)
+            for step in range(2):
+                rep.local_step(W.step_indices(w, 0, step, 200), w.lr)
+            r = rep.inner_product_test(w.theta)
+            out.append(([rep.get_params(m) for m in range(3)], [(t.sum_sq, t.sum_q, t.sum_q2, t.loss_sum) for t in r],
+                        [t.gbar_sq for t in r]))
+        finally:
+            rep.close()
+    assert out[0][1] == out[1][1]
+    for a, b in zip(out[0][2], out[1][2]):
+        assert _rel(a, b) <= 1e-6
+    for m in range(3):
+        assert np.array_equal(out[0][0][m], out[1][0][m])
+    w2 = W.Workload("split", (136, 264, 100), W.ACT_GELU, True, W.PREC_BF16, N=4096, M=2, H=1, rounds=1, b0=2300, b_cap=2304,
+                    opt=W.OPT_SHB, lr=0.05, momentum=0.9, test=W.TEST_IP, theta=0.9, data="teacher_mlp", seed=13)
+    X, y = W.make_dataset(w2)
+    rep = A.Replicas.from_workload(w2, X, y, W.make_x0(w2))
+    try:
+        rep.set_fused_update(True)
+        rep.local_step(W.step_indices(w2, 0, 0, 2300), w2.lr)
+        assert np.isfinite(rep.get_grad(1)).all()
+    finally:
+        rep.close()
+    wf = _one_step_case((40, 24, 7), W.ACT_RELU, W.PREC_F32, 16, 2)
+    X, y = W.make_dataset(wf)
+    rep = A.Replicas.from_workload(wf, X, y, W.make_x0(wf))
+    try:
+        with pytest.raises(A.AbsError, match="ABS_PREC_BF16"):
+            rep.set_fused_update(True)
+    finally:
+        rep.close()
+
+
+@pytest.mark.parametrize("cfg", ["config3", "config4"])
+def test_scaled_twin_lockstep_with_fused_update(cfg):
+    base = getattr(W, cfg)()
+    w = W.scaled_twin(base, width_div=8, cap_div=16, N=4096, M=4, rounds=2)
+    sched, exempt, worst = _lockstep(w, 2, stat_tol=5e-4, band=BF16_BAND, resync_params=True, max_steps=2 * w.H if w.H <= 8 else 20,
+                                     step_param_tol=1e-3, fused=True)
+    assert exempt <= 3, sched
 
 
 # ---------------------------------------------------------------------------------------------
@@ -1220,8 +1354,9 @@ def test_batch_size_sweep_keeps_every_scratch_piece_in_bounds(dims, act):
         rep.close()
 
 
-@pytest.mark.parametrize("prec,opt", [(W.PREC_BF16, W.OPT_ADAMW), (W.PREC_F32, W.OPT_SHB)])
-def test_graph_replayed_steps_are_bitwise_the_direct_steps(prec, opt):
+@pytest.mark.parametrize("prec,opt,fused", [(W.PREC_BF16, W.OPT_ADAMW, False), (W.PREC_F32, W.OPT_SHB, False),
+                                            (W.PREC_BF16, W.OPT_ADAMW, True)])
+def test_graph_replayed_steps_are_bitwise_the_direct_steps(prec, opt, fused):
     """abs_local_step_graphed against abs_local_step on twin replica sets: every step (first direct, second
     captured, later ones replayed, two batch sizes interleaved, changing indices, learning rate and Adam
     step count, tests and replica averages between the replays) must leave bitwise the same statistics
@@ -1236,6 +1371,9 @@ def test_graph_replayed_steps_are_bitwise_the_direct_steps(prec, opt):
     with torch.cuda.stream(side):
         ref = A.Replicas.from_workload(w, X, y, x0)
         rep = A.Replicas.from_workload(w, X, y, x0)
+        if fused:                              # the optimizer step inside the weight-gradient epilogue, replayed
+            ref.set_fused_update(True)
+            rep.set_fused_update(True)
         try:
             sizes = [32, 32, 32, 48, 32, 48, 48, 32, 64, 48, 32, 32]
             for s, b in enumerate(sizes):
