@@ -673,6 +673,9 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     if (sh == 3) return 1;                      // short batches: never split
     const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
     const long long tiles = (long long)((Md + te - 1) / te) * ((Nd + tn_e - 1) / tn_e) * M;
+    // with the optimizer step in the epilogue a launch that gives every CU a work-group stays whole (measured on the
+    // 100 x 2048 layer of config 3 at b = 8192: 256 tiles un-split take as long as the split launch and its finish)
+    if (c->fused_update && tiles >= 256) return 1;
     return choose_ksplit(sh, tiles, (b + 63) / 64, (double)M * Md * Nd, pl.kpart_floats_l[l]);
   };
   // The optimizer step moves into the weight-gradient epilogue when the caller asked for it and this call both
