@@ -153,6 +153,64 @@ __global__ void softmax_ce_kernel(const float *__restrict__ Z, long long sZg, in
   }
 }
 
+// The same head for 17 .. 128 (padded) classes: 32 lanes per row (two rows per wavefront), four consecutive
+// classes per lane, so the logits are read once as 16-byte vectors, every exponential is taken once and the
+// signal leaves as 8-byte (bf16) or 16-byte (fp32) vectors.
+template <class T>
+__global__ void __launch_bounds__(256) softmax_ce_vec_kernel(const float *__restrict__ Z, long long sZg, int ldz, int K,
+                                                             const int32_t *__restrict__ y, int N,
+                                                             const int32_t *__restrict__ idx, int ldi, int b,
+                                                             T *__restrict__ D, long long sDg, int ldd,
+                                                             float *__restrict__ dn, float *__restrict__ loss,
+                                                             long long sNg, const int *__restrict__ rows) {
+  const int g = blockIdx.y;
+  const int i = (blockIdx.x * 256 + threadIdx.x) >> 5;
+  if (i >= (rows ? rows[g] : b)) return;          // uniform over a row's 32 lanes
+  const int lane = threadIdx.x & 31, c0 = 4 * lane;
+  const float *z = Z + (long long)g * sZg + (long long)i * ldz;
+  const int label = min(max(y[min(max(idx[(long long)g * ldi + i], 0), N - 1)], 0), K - 1);
+  float zv[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  if (c0 < ldz) {                                  // ldz is a multiple of 4: the whole vector lies inside the row
+    const float4 v = *reinterpret_cast<const float4 *>(z + c0);
+    zv[0] = v.x; zv[1] = v.y; zv[2] = v.z; zv[3] = v.w;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) if (c0 + e >= K) zv[e] = -INFINITY;
+  float mx = fmaxf(fmaxf(zv[0], zv[1]), fmaxf(zv[2], zv[3]));
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  float ev[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) ev[e] = c0 + e < K ? expf(zv[e] - mx) : 0.0f;
+  float se = ((ev[0] + ev[1]) + ev[2]) + ev[3];
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+  const float inv = 1.0f / se;
+  float dv[4], sq = 0.0f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    dv[e] = c0 + e < K ? ev[e] * inv - (c0 + e == label ? 1.0f : 0.0f) : 0.0f;
+    const float st = Elem<T>::rnd(dv[e]);
+    sq = fmaf(st, st, sq);
+  }
+  if (c0 < ldd) {                                  // ldd is a multiple of 4 as well; pad columns receive zeros
+    T *drow = D + (long long)g * sDg + (long long)i * ldd + c0;
+    if (sizeof(T) == 2) {
+      uint2 o;
+      o.x = pack2bf(dv[0], dv[1]); o.y = pack2bf(dv[2], dv[3]);
+      *reinterpret_cast<uint2 *>(drow) = o;
+    } else {
+      *reinterpret_cast<float4 *>(drow) = make_float4(dv[0], dv[1], dv[2], dv[3]);
+    }
+  }
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+  if (lane == 0) {
+    dn[(long long)g * sNg + i] = sq;
+    loss[(long long)g * sNg + i] = -(z[label] - mx - logf(se));
+  }
+}
+
 template <class T>
 __global__ void row_sqnorm_kernel(const T *__restrict__ X, long long sXg, int ld, int cols, int b,
                                   float *__restrict__ out, long long sOg, const int *__restrict__ rows) {
@@ -736,6 +794,16 @@ hipError_t launch_softmax_ce(int is_bf16, const float *Z, long long sZg, int ldz
                          static_cast<bf16_t *>(D), sDg, ldd, dn, loss, sNg, rows);
     else
       hipLaunchKernelGGL((softmax_ce_kernel<float, 16>), grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+                         static_cast<float *>(D), sDg, ldd, dn, loss, sNg, rows);
+    return hipGetLastError();
+  }
+  if (ldd <= 128 && (ldd & 3) == 0 && (ldz & 3) == 0 && ldz >= ldd && (sZg & 3) == 0 && (sDg & 3) == 0) {
+    const dim3 grid((b + 7) / 8, groups);
+    if (is_bf16)
+      hipLaunchKernelGGL((softmax_ce_vec_kernel<bf16_t>), grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
+                         static_cast<bf16_t *>(D), sDg, ldd, dn, loss, sNg, rows);
+    else
+      hipLaunchKernelGGL((softmax_ce_vec_kernel<float>), grid, blk, 0, s, Z, sZg, ldz, K, y, N, idx, ldi, b,
                          static_cast<float *>(D), sDg, ldd, dn, loss, sNg, rows);
     return hipGetLastError();
   }
