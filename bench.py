@@ -278,7 +278,7 @@ def measure(a, wname, np, torch, A, W, with_cpu):
             e["frac_of_copy"] = e["gbs"] / COPY_GBS        # against the fastest plain copy measured here
         kernels[k] = e
     roof = None
-    if prof:
+    if prof and w.prec == W.PREC_BF16:       # (the fp32 configuration is launch- and latency-bound: no roof is meaningful)
         # Launch classes as a kernel trace sees them: one kernel symbol per (epilogue, tile shape) whatever the layer,
         # one per streaming kernel.  The dominant class is the one with the largest total time; its average launch
         # duration is what `rocprofv3 --kernel-trace --stats` reports for that symbol.  Which roof bounds it follows
