@@ -1,6 +1,8 @@
 // C ABI of the library (declared in include/abs.h): context, workspace plan, the call
 // sequence of one local step, host-side tests and the batch-size rule.
 #include <algorithm>
+#include <atomic>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -225,6 +227,8 @@ struct abs_ctx {
   long long N = 0;
   double *host_stats = nullptr;     // pinned, M*8 + 8 doubles
   double *host_stats_dev = nullptr; // the same memory as the device sees it (the statistics kernel writes there)
+  double ticket = 0.0;              // number of the last statistics launch that mirrors its sums (exact in a double)
+  bool ticket_live = false;         // that launch carried the ticket as a kernel argument (not a replayed graph)
   long long t = 0;                  // local steps taken (Adam bias correction)
   long long n_rounds = 0;           // Alg. 1's k: communication rounds completed (model averages)
   long long n_samples = 0;          // Alg. 1's B: samples processed, summed over workers and local steps
@@ -342,6 +346,20 @@ abs_status read_stats(abs_ctx *c) {
   if (!c->host_stats_dev)
     HIPCHK(c, hipMemcpyAsync(c->host_stats, c->at<double>(c->pl.o_stats), (size_t)c->pl.M * 8 * sizeof(double),
                              hipMemcpyDeviceToHost, c->stream));
+  if (c->host_stats_dev && c->ticket_live) {
+    // The final statistics kernel writes its launch number behind each worker's sums in the pinned mirror: poll
+    // for it (a stream synchronisation costs tens of microseconds of wake-up latency, which is a third of a step of
+    // the small configurations).  Bounded: after 20 ms the stream synchronisation below takes over.
+    const volatile double *h = c->host_stats;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (unsigned spin = 0;; ++spin) {
+      bool done = true;
+      for (int m = 0; m < c->pl.M && done; ++m) done = h[m * 8 + 7] == c->ticket;
+      if (done) { std::atomic_thread_fence(std::memory_order_acquire); return ABS_OK; }
+      if ((spin & 63) == 63 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(20)) break;
+      __builtin_ia32_pause();
+    }
+  }
   HIPCHK(c, hipStreamSynchronize(c->stream));      // the statistics kernel has written the pinned mirror itself
   return ABS_OK;
 }
@@ -821,6 +839,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   sp.Ppad = pl.Ppad;
   sp.partials = c->at<double>(pl.o_partials); sp.stats = c->at<double>(pl.o_stats);
   sp.stats_host = c->host_stats_dev;
+  if (sp.stats_host) { c->ticket += 1.0; sp.ticket = c->ticket; c->ticket_live = true; }
   // When this call both finishes the gradient and updates, the update kernel gathers ||gbar||^2 on
   // its way through the gradient (none of the statistics depends on the parameters, so the update
   // may run first); otherwise a separate pass over the gradient does.
@@ -962,6 +981,7 @@ abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, flo
     slot = &c->graphs.back();
   }
   slot->last_use = c->t;
+  c->ticket_live = false;             // a replayed launch carries the ticket of its capture: synchronise instead
   {
     hipError_t el = hipGraphLaunch(slot->exec, c->stream);
     if (el != hipSuccess) return settle_update(c, cfail(c, ABS_EHIP, std::string("hipGraphLaunch: ") + hipGetErrorString(el)));

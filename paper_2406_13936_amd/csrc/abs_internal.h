@@ -151,6 +151,8 @@ struct StatsP {
   long long Ppad;
   double *partials;         // scratch: [groups][5][PBLK]
   double *stats;            // out: [groups][8] = S1, S2, S3, S4, loss, 0,0,0
+  double ticket;            // with stats_host: written to stats_host[g * 8 + 7] after group g's sums have been
+                            //   made visible to the host (a host that polls that word needs no stream synchronisation)
   double *stats_host;       // optional mirror in device-visible pinned host memory (same layout): the host then
                             //   needs a stream synchronisation only, no copy
   const float *sq_wave;     // alternative source of S2 (grad must be null): per-wavefront sums of g^2 left by the

@@ -441,7 +441,7 @@ __global__ void __launch_bounds__(256) stats_gradsq_kernel(const float *__restri
 // nb_samples: how many partials of the per-sample sums (all but k = 1) this step wrote; the rest count as zero.
 __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restrict__ partials,
                                                           double *__restrict__ stats, double *__restrict__ stats_host,
-                                                          int sel, int acc, int nb_samples) {
+                                                          int sel, int acc, int nb_samples, double ticket) {
   __shared__ double red[4];
   const int g = blockIdx.x;
   static_assert(STATS_PBLK == 256, "one partial per thread");
@@ -455,6 +455,10 @@ __global__ void __launch_bounds__(256) stats_final_kernel(const double *__restri
       stats[g * 8 + k] = v;
       if (stats_host) stats_host[g * 8 + k] = v;
     }
+  }
+  if (stats_host && threadIdx.x == 0) {
+    __threadfence_system();                       // the sums above reach host memory before the ticket does
+    *reinterpret_cast<volatile double *>(stats_host + g * 8 + 7) = ticket;
   }
 }
 
@@ -892,7 +896,7 @@ hipError_t launch_stats(const StatsP &p, hipStream_t s) {
   if (p.do_q) { sel |= 4 | 8; if (p.acc_q) acc |= 4 | 8; }
   if (p.grad && p.sq_wave) return hipErrorInvalidValue;
   if (p.grad || p.sq_wave) sel |= 2;
-  if (!sel) return hipSuccess;
+  if (!sel && !p.stats_host) return hipSuccess;       // (with a mirror the final kernel still delivers the ticket)
   int nb_samples = 0;
   if (p.do_n || p.do_q) {
     nb_samples = (p.b + 255) / 256;
@@ -905,7 +909,7 @@ hipError_t launch_stats(const StatsP &p, hipStream_t s) {
     hipLaunchKernelGGL(stats_gradsq_kernel, dim3(STATS_PBLK, p.groups), dim3(256), 0, s, p.grad, p.Ppad,
                        p.partials);
   hipLaunchKernelGGL(stats_final_kernel, dim3(p.groups), dim3(256), 0, s, p.partials, p.stats, p.stats_host, sel, acc,
-                     nb_samples);
+                     nb_samples, p.ticket);
   return hipGetLastError();
 }
 
