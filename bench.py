@@ -430,6 +430,20 @@ def main():
             "value": o2["value"], "unit": o2["unit"], "ms_per_step": o2["ms_per_step"],
             "local_batch": o2["config"]["local_batch"], "M": o2["config"]["M"],
             "all_gemms_tflops": (o2.get("roofline") or {}).get("all_gemms_tflops")}}
+        # the same configuration in its short-batch regime (its first size, where the adaptive run stays): bound by
+        # HBM, plain and with the optimizer step inside the weight-gradient epilogue; and the latter at the cap
+        import copy
+        for key, batch, fused in (("cfg3_b64", 64, False), ("cfg3_b64_fused_update", 64, True),
+                                  ("cfg3_cap_fused_update", 0, True)):
+            if fused and a.fused_update:
+                continue
+            a2 = copy.copy(a)
+            a2.batch, a2.fused_update, a2.steps, a2.warmup = batch, fused or a.fused_update, 40 if batch else a.steps, 5
+            o3 = measure(a2, "config3", np, torch, A, W, False)
+            r3 = o3.get("roofline") or {}
+            out["also"][key] = {"value": o3["value"], "unit": o3["unit"], "ms_per_step": o3["ms_per_step"],
+                                "local_batch": o3["config"]["local_batch"],
+                                "roofline": {k: r3.get(k) for k in ("bound", "kernel", "achieved", "peak", "unit", "frac")}}
     print(json.dumps(out))
 
 

@@ -21,7 +21,10 @@
  *    the statistics).  The library allocates no device memory: all of it is carved from
  *    the caller's workspace (abs_workspace_bytes says how much).
  *  - abs_local_step and abs_average_replicas are asynchronous on the context's stream.
- *    The *_test, get/set calls synchronise that stream.
+ *    The *_test calls return once the statistics of the most recent step have reached the host; the
+ *    statistics are the step's last launch, so every kernel of that step has finished by then (work
+ *    enqueued after the step, e.g. an average, may still be running).  The get/set calls synchronise
+ *    the stream.
  *  - One context per host thread and stream; calls on one context are not re-entrant.
  *  - Parameter vector layout (x0, get/set_params, get_grad): layer-major; for each layer
  *    the weight W_l row-major [out_l x in_l], then (if has_bias) the bias [out_l].
