@@ -217,9 +217,9 @@ abs_status abs_average_replicas(abs_ctx *ctx);
  * per-wavefront partial sums left by the epilogues, the batch gradient of the weights exists only as the bf16
  * copy that the inner products use, and the statistics, tests and parameters are those of the unfused step up to
  * the order of the additions in ||gbar||^2.  While it is on: abs_get_grad and abs_cross_worker_test after such a
- * step and abs_local_step_accumulated return ABS_ESTATE (they need the stored gradient); a step whose weight
- * gradients split their reduction over the batch (few output tiles, long batches) runs unfused.  Needs
- * ABS_PREC_BF16 (ABS_EUNSUPPORTED otherwise).
+ * step and abs_local_step_accumulated return ABS_ESTATE (they need the stored gradient).  A layer whose weight
+ * gradient splits its reduction over the batch (few output tiles, long batches) takes its step in the launch that
+ * adds the slices.  Needs ABS_PREC_BF16 (ABS_EUNSUPPORTED otherwise).
  */
 abs_status abs_set_fused_update(abs_ctx *ctx, int on);
 

@@ -702,8 +702,10 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   if (fused) {
     long long slots = 0;
     for (int l = 1; l <= L; ++l) {
-      if (bf16_ksplit(l) > 1 || (pl.dims[l - 1] & 3)) fused = false;
-      slots += gemm_bf16_upd_slots(pl.dims[l], pl.dims[l - 1], b, M);
+      if (pl.dims[l - 1] & 3) fused = false;
+      // a layer whose reduction is split takes its step in the launch that adds the slices
+      slots += bf16_ksplit(l) > 1 ? splitk_finish_slots((long long)pl.dims[l] * pl.dims[l - 1])
+                                  : gemm_bf16_upd_slots(pl.dims[l], pl.dims[l - 1], b, M);
     }
     if (hb) { int mx = 0; for (int l = 1; l <= L; ++l) mx = std::max(mx, pl.dims[l]); slots += (long long)L * ((mx + 255) / 256); }
     if (slots > pl.Ppad / 256) fused = false;
@@ -744,7 +746,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         p.kchunk = ((KT + S - 1) / S) * 64;
         p.kpart = c->at<float>(pl.o_kpart_l[l]);
       }
-      if (fused) {
+      if (fused && p.ksplit <= 1) {
         // the optimizer step replaces the gradient store (the fp32 gradient of the weights is never written)
         p.upd_x = xm + pl.offW[l];
         p.upd_v = c->cfg.opt != ABS_OPT_SGD ? c->at<float>(pl.o_v) + pl.offW[l] : nullptr;
@@ -761,6 +763,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
         const int e = kf.n++;
         kf.kpart[e] = p.kpart; kf.ksplit[e] = p.ksplit; kf.mn[e] = (long long)p.Md * p.Nd; kf.c_off[e] = pl.offW[l];
         kf_bytes += (4.0 * p.ksplit + 6.0) * M * p.Md * p.Nd;
+        if (fused) { kf.upd_slot0[e] = fused_slots; fused_slots += splitk_finish_slots(kf.mn[e]); }
       }
       if (hb && !pl.bf16) {
         ProfScope ps_(c, T_COLSUM, 0.0, 1.0 * M * b * pl.ld[l] * pl.esz);
@@ -783,6 +786,16 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       kf.alpha = inv_b; kf.rows = rows; kf.C = grad; kf.sCg = pl.Ppad;
       kf.C2 = (pl.bf16 && pl.want_ip) ? c->at<bf16_t>(pl.o_gradbf) : nullptr; kf.sC2g = pl.Ppad;
       kf.accumulate = ph.acc_grad ? 1 : 0;
+      if (fused) {
+        kf.upd_x = xm;
+        kf.upd_v = c->cfg.opt != ABS_OPT_SGD ? c->at<float>(pl.o_v) : nullptr;
+        kf.upd_m = c->cfg.opt == ABS_OPT_ADAMW ? c->at<float>(pl.o_m) : nullptr;
+        kf.upd_shadow = c->at<bf16_t>(pl.o_xs);
+        kf.upd_opt = c->cfg.opt; kf.upd_lr = lr; kf.upd_momentum = c->cfg.momentum; kf.upd_beta1 = c->cfg.beta1;
+        kf.upd_beta2 = c->cfg.beta2; kf.upd_eps = c->cfg.eps; kf.upd_wd = c->cfg.weight_decay;
+        kf.upd_c1 = ph.c1; kf.upd_c2 = ph.c2; kf.upd_scal = ph.scal;
+        kf.upd_sq = c->at<float>(pl.o_sqwave); kf.upd_sSqg = pl.Ppad / 256;
+      }
       HIPCHK(c, launch_splitk_finish(kf, M, s));
     }
     if (cf.n > 0) {                        // all bias gradients of the step in one launch

@@ -214,8 +214,19 @@ struct SplitKFinishMany {
   float *C; long long sCg;
   bf16_t *C2; long long sC2g;
   int accumulate;
+  // Optional (upd_x != null, accumulate == 0): the optimizer step in place of the store to C, as in the
+  // weight-gradient epilogue (GemmP::upd_*): parameters, state and shadow at upd_* + g * sCg + c_off_l + e; block j of
+  // layer l leaves the sum of its squared gradient entries in upd_sq[g * upd_sSqg + upd_slot0[l] + j]
+  // (launch_splitk_finish_slots(mn_l) blocks per layer).
+  float *upd_x, *upd_v, *upd_m;
+  bf16_t *upd_shadow;
+  int upd_opt;
+  float upd_lr, upd_momentum, upd_beta1, upd_beta2, upd_eps, upd_wd, upd_c1, upd_c2;
+  const float *upd_scal;
+  float *upd_sq; long long upd_sSqg; int upd_slot0[MAXN];
 };
 hipError_t launch_splitk_finish(const SplitKFinishMany &p, int groups, hipStream_t s);
+inline int splitk_finish_slots(long long mn) { return (int)((mn / 4 + 255) / 256); }
 // Inputs of a replayed step: idx_dst[0..n) = idx_src[0..n), scal[0..3) = {lr, c1, c2}
 hipError_t launch_stage_step_inputs(const int32_t *idx_src, int32_t *idx_dst, long long n, float lr, float c1, float c2,
                                     float *scal, hipStream_t s);

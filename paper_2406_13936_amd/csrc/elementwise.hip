@@ -716,27 +716,66 @@ __global__ void __launch_bounds__(256) copy_probe_kernel(const uint4 *__restrict
 }
 
 // blockIdx.z = layer; the layers of a step share one launch
+// OPT < 0: store the finished gradient; OPT >= 0: apply that optimizer's step to the parameters instead.
+template <int OPT>
 __global__ void __launch_bounds__(256) splitk_finish_kernel(const SplitKFinishMany p) {
+  __shared__ double red[4];
   const int l = blockIdx.z, g = blockIdx.y;
   const long long mn = p.mn[l];
   const long long i = blockIdx.x * 256LL + threadIdx.x;          // float4 index inside the group's layer
-  if (i * 4 >= mn) return;
-  const int ksplit = p.ksplit[l];
-  const float alpha = p.rows ? 1.0f / (float)p.rows[g] : p.alpha;
-  const float *q = p.kpart[l] + (long long)g * ksplit * mn + i * 4;
-  float4 s = ld_stream(reinterpret_cast<const float4 *>(q));
-  for (int sp = 1; sp < ksplit; ++sp) {
-    const float4 v = ld_stream(reinterpret_cast<const float4 *>(q + (long long)sp * mn));
-    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  if (blockIdx.x * 1024LL >= mn) return;                         // uniform over the block
+  const bool live = i * 4 < mn;
+  float gg = 0.0f;
+  if (live) {
+    const int ksplit = p.ksplit[l];
+    const float alpha = p.rows ? 1.0f / (float)p.rows[g] : p.alpha;
+    const float *q = p.kpart[l] + (long long)g * ksplit * mn + i * 4;
+    float4 s = ld_stream(reinterpret_cast<const float4 *>(q));
+    for (int sp = 1; sp < ksplit; ++sp) {
+      const float4 v = ld_stream(reinterpret_cast<const float4 *>(q + (long long)sp * mn));
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
+    const long long o = (long long)g * p.sCg + p.c_off[l] + i * 4;
+    if (OPT < 0) {
+      float4 *c = reinterpret_cast<float4 *>(p.C + o);
+      if (p.accumulate) { const float4 old = *c; s.x += old.x; s.y += old.y; s.z += old.z; s.w += old.w; }
+      *c = s;
+    } else {
+      OptHyper h = {p.upd_lr, p.upd_momentum, p.upd_beta1, p.upd_beta2, p.upd_eps, p.upd_wd, p.upd_c1, p.upd_c2};
+      if (p.upd_scal) { h.lr = p.upd_scal[0]; h.c1 = p.upd_scal[1]; h.c2 = p.upd_scal[2]; }
+      const float4 x4 = ld_stream(reinterpret_cast<const float4 *>(p.upd_x + o));
+      float xs[4] = {x4.x, x4.y, x4.z, x4.w}, vs[4] = {0.f, 0.f, 0.f, 0.f}, ms[4] = {0.f, 0.f, 0.f, 0.f};
+      const float gs[4] = {s.x, s.y, s.z, s.w};
+      if (OPT != OPT_SGD) {
+        const float4 v4 = ld_stream(reinterpret_cast<const float4 *>(p.upd_v + o));
+        vs[0] = v4.x; vs[1] = v4.y; vs[2] = v4.z; vs[3] = v4.w;
+      }
+      if (OPT == OPT_ADAMW) {
+        const float4 m4 = ld_stream(reinterpret_cast<const float4 *>(p.upd_m + o));
+        ms[0] = m4.x; ms[1] = m4.y; ms[2] = m4.z; ms[3] = m4.w;
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) opt_step_elem<(OPT < 0 ? 0 : OPT)>(xs[k], gs[k], vs[k], ms[k], h);
+      st_stream(reinterpret_cast<float4 *>(p.upd_x + o), make_float4(xs[0], xs[1], xs[2], xs[3]));
+      if (OPT != OPT_SGD) st_stream(reinterpret_cast<float4 *>(p.upd_v + o), make_float4(vs[0], vs[1], vs[2], vs[3]));
+      if (OPT == OPT_ADAMW) st_stream(reinterpret_cast<float4 *>(p.upd_m + o), make_float4(ms[0], ms[1], ms[2], ms[3]));
+      if (p.upd_shadow) {
+        uint2 w;
+        w.x = pack2bf(xs[0], xs[1]); w.y = pack2bf(xs[2], xs[3]);
+        st_stream(reinterpret_cast<uint2 *>(p.upd_shadow + o), w);
+      }
+      gg = fmaf(s.x, s.x, fmaf(s.y, s.y, fmaf(s.z, s.z, s.w * s.w)));
+    }
+    if (p.C2) {
+      uint2 w;
+      w.x = pack2bf(s.x, s.y); w.y = pack2bf(s.z, s.w);
+      reinterpret_cast<uint2 *>(p.C2 + (long long)g * p.sC2g + p.c_off[l])[i] = w;
+    }
   }
-  s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
-  float4 *c = reinterpret_cast<float4 *>(p.C + (long long)g * p.sCg + p.c_off[l]) + i;
-  if (p.accumulate) { const float4 o = *c; s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w; }
-  *c = s;
-  if (p.C2) {
-    uint2 o;
-    o.x = pack2bf(s.x, s.y); o.y = pack2bf(s.z, s.w);
-    reinterpret_cast<uint2 *>(p.C2 + (long long)g * p.sC2g + p.c_off[l])[i] = o;
+  if (OPT >= 0) {
+    const double r = block_sum<4>((double)gg, red);
+    if (threadIdx.x == 0) p.upd_sq[(long long)g * p.upd_sSqg + p.upd_slot0[l] + blockIdx.x] = (float)r;
   }
 }
 
@@ -1005,7 +1044,17 @@ hipError_t launch_splitk_finish(const SplitKFinishMany &p, int groups, hipStream
     if ((p.mn[l] & 3) || (p.c_off[l] & 3) || p.ksplit[l] < 1 || !p.kpart[l]) return hipErrorInvalidValue;
     mx = p.mn[l] > mx ? p.mn[l] : mx;
   }
-  hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((mx / 4 + 255) / 256), groups, p.n), dim3(256), 0, s, p);
+  const dim3 grid((unsigned)((mx / 4 + 255) / 256), groups, p.n), blk(256);
+  if (!p.upd_x) {
+    hipLaunchKernelGGL(splitk_finish_kernel<-1>, grid, blk, 0, s, p);
+    return hipGetLastError();
+  }
+  if (p.accumulate || !p.upd_sq || (p.upd_opt != OPT_SGD && !p.upd_v) || (p.upd_opt == OPT_ADAMW && !p.upd_m))
+    return hipErrorInvalidValue;
+  if (p.upd_opt == OPT_SGD) hipLaunchKernelGGL(splitk_finish_kernel<OPT_SGD>, grid, blk, 0, s, p);
+  else if (p.upd_opt == OPT_SHB) hipLaunchKernelGGL(splitk_finish_kernel<OPT_SHB>, grid, blk, 0, s, p);
+  else if (p.upd_opt == OPT_ADAGRAD) hipLaunchKernelGGL(splitk_finish_kernel<OPT_ADAGRAD>, grid, blk, 0, s, p);
+  else hipLaunchKernelGGL(splitk_finish_kernel<OPT_ADAMW>, grid, blk, 0, s, p);
   return hipGetLastError();
 }
 

@@ -558,6 +558,10 @@ def test_bf16_free_running_twin_with_heavy_ball_and_adamw(opt, lr):
     ((1024, 1024, 1024, 100), W.ACT_RELU, [72] * 2, W.OPT_ADAGRAD, False),           # 256x256 tiles, one k-tile
     ((1024, 1280, 100), W.ACT_GELU, [1100, 260, 2], W.OPT_SGD, True),                # ragged workers, 256x256 tiles
     ((136, 264, 100), W.ACT_RELU, [40, 300, 7, 129, 2, 517, 64, 260, 33], W.OPT_SHB, True),
+    # batches long enough for split weight-gradient reductions: the step is taken by the launch that adds the slices
+    ((136, 264, 100), W.ACT_GELU, [2300] * 2, W.OPT_SHB, True),
+    ((136, 264, 72, 100), W.ACT_GELU, [2300, 300, 1152, 2, 1153, 2049], W.OPT_ADAMW, True),
+    ((784, 512, 512, 10), W.ACT_RELU, [4096] * 2, W.OPT_SGD, True),                  # config 2 at its cap
 ])
 def test_fused_update_step_matches_oracle(dims, act, bs, opt, hb):
     """Two steps with the optimizer step applied inside the weight-gradient epilogue (the second one starts from
@@ -565,7 +569,7 @@ def test_fused_update_step_matches_oracle(dims, act, bs, opt, hb):
     the calls that need the stored gradient are refused."""
     A = _A()
     M, ragged = len(bs), len(set(bs)) > 1
-    w = W.Workload("fused", dims, act, hb, W.PREC_BF16, N=2048, M=M, H=1, rounds=1, b0=max(bs), b_cap=max(bs) + 5, opt=opt,
+    w = W.Workload("fused", dims, act, hb, W.PREC_BF16, N=max(2048, max(bs)), M=M, H=1, rounds=1, b0=max(bs), b_cap=max(bs) + 5, opt=opt,
                    lr=0.02, momentum=0.9, weight_decay=0.05, test=W.TEST_AUG_IP, theta=0.9, nu=0.5, data="teacher_mlp",
                    seed=47)
     X, y = W.make_dataset(w)
@@ -597,8 +601,14 @@ def test_fused_update_step_matches_oracle(dims, act, bs, opt, hb):
                     assert _rel(g[m].ratio, o[m]["ratio"]) <= 2e-2
                     _check_decision(g[m], o[m], bs[m], 2e-3, (step, m))
                 p = rep.get_params(m).astype(np.float64)
-                sel = _significant(orc.grads[m], 1e-2) if opt in (W.OPT_ADAMW, W.OPT_ADAGRAD) else slice(None)
-                assert np.abs(p - orc.x[m])[sel].max() <= 1e-3 * np.abs(orc.x[m]).max(), (step, m)
+                if opt in (W.OPT_ADAMW, W.OPT_ADAGRAD):
+                    # sign-like steps: where a hidden unit sits on a bf16 tie, one sample's contribution can turn the
+                    # sign of a small gradient entry and the parameter then moves the other way; all but a few per
+                    # ten thousand of the entries with a non-negligible gradient must agree
+                    e = np.abs(p - orc.x[m])[_significant(orc.grads[m], 1e-2)] / np.abs(orc.x[m]).max()
+                    assert np.mean(e > 1e-3) <= 2e-4, (step, m, np.mean(e > 1e-3))
+                else:
+                    assert np.abs(p - orc.x[m]).max() <= 1e-3 * np.abs(orc.x[m]).max(), (step, m)
                 if opt != W.OPT_SGD:
                     v = rep.get_opt_state(m, 0).astype(np.float64)
                     assert np.abs(v - orc.st[m].v).max() <= 4e-3 * np.abs(orc.st[m].v).max()
@@ -624,13 +634,14 @@ def test_fused_update_step_matches_oracle(dims, act, bs, opt, hb):
         rep.close()
 
 
-def test_fused_update_equals_the_unfused_step_and_falls_back_when_a_reduction_is_split():
-    """Same inputs through the fused and the plain path: identical per-sample statistics (bit for bit: the same
+@pytest.mark.parametrize("dims,b", [((384, 256, 256, 100), 200), ((136, 264, 100), 2300)])
+def test_fused_update_equals_the_unfused_step(dims, b):
+    """Same inputs through the fused and the plain path (the second shape splits its weight-gradient reductions, so
+    its step is taken by the launch that adds the slices): identical per-sample statistics (bit for bit: the same
     kernels produce them), ||gbar||^2 equal up to the order of its additions, parameters bit-equal (the same
-    expression on the same gradient entries).  A batch long enough for split weight-gradient reductions takes the
-    plain path even when the fused one is switched on, and its gradient can be read."""
+    expression on the same gradient entries)."""
     A = _A()
-    w = _one_step_case((384, 256, 256, 100), W.ACT_GELU, W.PREC_BF16, 200, 3, opt=W.OPT_SHB, N=1024)
+    w = _one_step_case(dims, W.ACT_GELU, W.PREC_BF16, b, 3, opt=W.OPT_SHB, N=4096)
     X, y = W.make_dataset(w)
     x0 = W.make_x0(w)
     out = []
@@ -639,27 +650,26 @@ def test_fused_update_equals_the_unfused_step_and_falls_back_when_a_reduction_is
         try:
             rep.set_fused_update(fused)
             for step in range(2):
-                rep.local_step(W.step_indices(w, 0, step, 200), w.lr)
+                rep.local_step(W.step_indices(w, 0, step, b), w.lr)
             r = rep.inner_product_test(w.theta)
             out.append(([rep.get_params(m) for m in range(3)], [(t.sum_sq, t.sum_q, t.sum_q2, t.loss_sum) for t in r],
                         [t.gbar_sq for t in r]))
+            if fused:
+                with pytest.raises(A.AbsError, match="not stored"):
+                    rep.get_grad(1)
+            else:
+                assert np.isfinite(rep.get_grad(1)).all()
         finally:
             rep.close()
     assert out[0][1] == out[1][1]
-    for a, b in zip(out[0][2], out[1][2]):
-        assert _rel(a, b) <= 1e-6
+    for a, b_ in zip(out[0][2], out[1][2]):
+        assert _rel(a, b_) <= 1e-6
     for m in range(3):
         assert np.array_equal(out[0][0][m], out[1][0][m])
-    w2 = W.Workload("split", (136, 264, 100), W.ACT_GELU, True, W.PREC_BF16, N=4096, M=2, H=1, rounds=1, b0=2300, b_cap=2304,
-                    opt=W.OPT_SHB, lr=0.05, momentum=0.9, test=W.TEST_IP, theta=0.9, data="teacher_mlp", seed=13)
-    X, y = W.make_dataset(w2)
-    rep = A.Replicas.from_workload(w2, X, y, W.make_x0(w2))
-    try:
-        rep.set_fused_update(True)
-        rep.local_step(W.step_indices(w2, 0, 0, 2300), w2.lr)
-        assert np.isfinite(rep.get_grad(1)).all()
-    finally:
-        rep.close()
+
+
+def test_fused_update_needs_the_bf16_path():
+    A = _A()
     wf = _one_step_case((40, 24, 7), W.ACT_RELU, W.PREC_F32, 16, 2)
     X, y = W.make_dataset(wf)
     rep = A.Replicas.from_workload(wf, X, y, W.make_x0(wf))
