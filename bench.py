@@ -50,6 +50,9 @@ def parse():
                     help="replay captured HIP graphs on the steps that are not bracketed by events (fixed batch size)")
     ap.add_argument("--fused-update", action="store_true",
                     help="opt in to the optimizer step inside the weight-gradient epilogue (abs_set_fused_update)")
+    ap.add_argument("--gram-ip-max-batch", type=int, default=-1,
+                    help="largest local batch whose inner products come from Gram matrices "
+                         "(abs_set_gram_ip_max_batch; default: the library's, 256; 0: never)")
     ap.add_argument("--sustain-seconds", type=float, default=-1.0,
                     help="after the timed steps keep stepping for at least this long and report the step time of that "
                          "period as ms_per_step_sustained (the chip settles at its power limit within seconds; "
@@ -162,6 +165,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     rep = A.Replicas.from_workload(w, X, y, x0)
     if a.fused_update:
         rep.set_fused_update(True)
+    if a.gram_ip_max_batch >= 0:
+        rep.set_gram_ip_max_batch(a.gram_ip_max_batch)
     b_fixed = a.batch or w.b_cap
 
     def test_and_rule(b):
@@ -220,6 +225,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
         rep = A.Replicas.from_workload(w, X, y, x0)
         if a.fused_update:
             rep.set_fused_update(True)
+        if a.gram_ip_max_batch >= 0:
+            rep.set_gram_ip_max_batch(a.gram_ip_max_batch)
     b = w.b0 if a.adaptive else b_fixed
     for s in range(a.warmup):
         nb = run(s, b)

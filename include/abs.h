@@ -224,6 +224,20 @@ abs_status abs_average_replicas(abs_ctx *ctx);
 abs_status abs_set_fused_update(abs_ctx *ctx, int on);
 
 /*
+ * How the inner products q_i = <g_i, gbar> of the inner-product test are formed (ABS_PREC_BF16 with ABS_STATS_IP;
+ * ignored otherwise).  Steps with b <= b_max (every worker's b^m for a ragged step) use
+ *   <g_i, g_j> = sum_l (delta_i^l . delta_j^l)(a_i^{l-1} . a_j^{l-1} + [bias]),   q_i = (1/b) sum_j <g_i, g_j>,
+ * i.e. the b x b Gram matrices of the layer inputs and backprop signals (the per-sample gradient of a layer is the
+ * outer product delta_i a_i^T), which reads b (in + out) values per layer instead of every parameter; longer
+ * batches contract the stored bf16 copy of Gbar with the activations (cost linear in b).  Both are the same sum
+ * in exact arithmetic.  In the Gram form Gbar is never rounded to bf16 on its way into the product, so q_i differs
+ * from the other form's by that rounding (relative 2^-9 per entry of Gbar, far less in the sums).
+ * b_max in [0, 256]; 0 switches the Gram form off; the default is 256 (measured on config 3: the Gram form is the faster one for every b up to there).  abs_local_step_accumulated always uses the
+ * contraction with Gbar.
+ */
+abs_status abs_set_gram_ip_max_batch(abs_ctx *ctx, int b_max);
+
+/*
  * Counters of Alg. 1: rounds = k, the communication rounds completed (one per abs_average_replicas,
  * "k <- k + 1"); local_steps = optimizer steps taken by every worker; samples = B, the local batch
  * sizes actually used, summed over workers and local steps ("B <- B + sum_m sum_h b^m").

@@ -34,8 +34,11 @@ not by the paper.  Two numeric modes:
           stores bf16: dataset, weight shadow, stored activations a^l, stored
           activation derivative phi'(z^l), every backprop signal delta^l, and
           the batch gradient when it is used as the operand of the
-          inner-product contraction.  Biases, batch gradients, statistics,
-          optimizer state and master weights are never rounded.
+          inner-product contraction (long batches only: for short ones the
+          device sums the products <g_i, g_j> over j and never stores a bf16
+          batch gradient, see `Replicas.gram_max_b`).  Biases, batch
+          gradients, statistics, optimizer state and master weights are never
+          rounded.
 
 Parity status: every function here is pinned by tests/test_oracle_*.py (finite
 differences, explicit per-sample gradients, closed forms, invariants).  The
@@ -234,7 +237,8 @@ def stats_explicit(g: np.ndarray) -> dict:
             "var_perp": var_perp, "n": (g * g).sum(axis=1), "q": q, "gbar": gbar}
 
 
-def stats_factored(net: Net, bp: dict, want_ip: bool = True, mixed: bool = False) -> dict:
+def stats_factored(net: Net, bp: dict, want_ip: bool = True, mixed: bool = False,
+                   round_gbar: bool = True) -> dict:
     """The same statistics without per-sample gradients.
 
     g_i restricted to layer l is the outer product delta_i^l a_i^{l-1 T} (plus
@@ -243,7 +247,7 @@ def stats_factored(net: Net, bp: dict, want_ip: bool = True, mixed: bool = False
       <g_i, gbar> = sum_l delta_i^l . (Gbar_l a_i^{l-1} + betabar_l)
       sum_i ||g_i - gbar||^2 = S1 - b S2.
     In mixed mode Gbar_l is rounded to bf16 where it enters the contraction
-    Gbar_l a_i (betabar_l stays unrounded)."""
+    Gbar_l a_i (betabar_l stays unrounded), unless round_gbar is False."""
     a, delta, G = bp["a"], bp["delta"], bp["G"]
     b = a[0].shape[0]
     n = np.zeros(b)
@@ -261,7 +265,7 @@ def stats_factored(net: Net, bp: dict, want_ip: bool = True, mixed: bool = False
     if want_ip:
         q = np.zeros(b)
         for l in range(net.L):
-            Gl = bf16_round(G[l][0]) if mixed else G[l][0]
+            Gl = bf16_round(G[l][0]) if (mixed and round_gbar) else G[l][0]
             u = a[l] @ Gl.T
             if net.has_bias:
                 u = u + G[l][1]
@@ -400,8 +404,11 @@ def average(xs: np.ndarray) -> np.ndarray:
 class Replicas:
     def __init__(self, net: Net, x0, X, y, M: int, opt: int = OPT_SGD,
                  momentum=0.0, beta1=0.9, beta2=0.999, eps=1e-8,
-                 weight_decay=0.0, mixed=False, want_ip=False):
+                 weight_decay=0.0, mixed=False, want_ip=False, gram_max_b=0):
         self.net, self.M, self.opt, self.mixed = net, M, opt, mixed
+        # mixed mode: a step whose largest local batch is at most this size keeps Gbar unrounded in
+        # <g_i, gbar> (the device then adds <g_i, g_j> over j instead of contracting a stored bf16 Gbar)
+        self.gram_max_b = gram_max_b
         self.hp = dict(momentum=momentum, beta1=beta1, beta2=beta2, eps=eps,
                        weight_decay=weight_decay)
         self.X = np.asarray(X, dtype=np.float64)
@@ -421,6 +428,8 @@ class Replicas:
         are None / zero."""
         self.stats = []
         grads = []
+        stepped = [m for m in range(self.M) if only is None or m in only]
+        round_gbar = max(len(idx[m]) for m in stepped) > self.gram_max_b
         for m in range(self.M):
             if only is not None and m not in only:
                 self.stats.append(None)
@@ -428,7 +437,7 @@ class Replicas:
                 continue
             bp = backprop(self.net, self.x[m], self.X[idx[m]], self.y[idx[m]],
                           self.mixed)
-            self.stats.append(stats_factored(self.net, bp, self.want_ip, self.mixed))
+            self.stats.append(stats_factored(self.net, bp, self.want_ip, self.mixed, round_gbar))
             g = self.net.pack(bp["G"])
             grads.append(g)
             self.x[m] = opt_step(self.x[m], g, self.st[m], self.opt, lr, **self.hp)

@@ -28,7 +28,7 @@ EXPORTS = [
     "abs_lr_linear_scaling", "abs_norm_test_fpc", "abs_local_step_ragged", "abs_norm_test_per_worker",
     "abs_local_step_accumulated", "abs_profile_pause", "abs_local_step_graphed", "abs_graph_count",
     "abs_get_counters", "abs_get_opt_state", "abs_average_bf16_static",
-    "abs_set_fused_update",
+    "abs_set_fused_update", "abs_set_gram_ip_max_batch",
 ]
 
 
@@ -90,6 +90,7 @@ def load_library(reload: bool = False):
     lib.abs_get_counters.argtypes = [C.c_void_p, C.POINTER(C.c_longlong), C.POINTER(C.c_longlong),
                                      C.POINTER(C.c_longlong)]
     lib.abs_set_fused_update.argtypes = [C.c_void_p, C.c_int]
+    lib.abs_set_gram_ip_max_batch.argtypes = [C.c_void_p, C.c_int]
     lib.abs_get_opt_state.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.abs_get_per_sample.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     lib.abs_n_params.argtypes = [C.POINTER(_Config), C.POINTER(C.c_int64)]
@@ -306,6 +307,10 @@ class Replicas:
     def set_fused_update(self, on: bool = True):
         """Opt in to (or out of) the optimizer step inside the weight-gradient epilogue."""
         _check(self._lib.abs_set_fused_update(self._ctx, int(bool(on))), self._ctx)
+
+    def set_gram_ip_max_batch(self, b_max: int):
+        """Largest local batch whose inner products <g_i, gbar> come from Gram matrices (0: never)."""
+        _check(self._lib.abs_set_gram_ip_max_batch(self._ctx, int(b_max)), self._ctx)
 
     def counters(self):
         """(rounds k, local steps, samples B) of Alg. 1 as kept by the library."""

@@ -22,6 +22,7 @@ namespace {
 thread_local std::string g_err;
 
 constexpr int MAXL = 16;
+constexpr int GRAM_IP_DEFAULT_B = 256;   // largest local batch that takes the Gram form of the inner products by default
 
 inline long long rup(long long v, long long a) { return (v + a - 1) / a * a; }
 
@@ -42,7 +43,7 @@ struct Plan {
   // byte offsets into the workspace
   size_t o_xm = 0, o_xs = 0, o_grad = 0, o_gradbf = 0, o_v = 0, o_m = 0, o_Xbf = 0;
   size_t o_A[MAXL] = {0}, o_Dact[MAXL] = {0}, o_Dl[MAXL + 1] = {0};
-  size_t o_Z = 0, o_U = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
+  size_t o_Z = 0, o_U = 0, o_gram = 0, o_an[MAXL] = {0}, o_dn[MAXL + 1] = {0}, o_loss = 0, o_nout = 0, o_qout = 0;
   size_t o_qpart[MAXL] = {0}, o_partials = 0, o_stats = 0, o_cw = 0, o_colpart = 0, o_rows = 0, o_sqwave = 0, o_idx = 0, o_scal = 0, o_mean = 0;
   size_t o_kpart_l[MAXL + 1] = {0};    // per layer: partial products of a split weight-gradient reduction
   size_t kpart_floats_l[MAXL + 1] = {0};
@@ -131,6 +132,8 @@ void make_plan(const abs_config *c, long long N, Plan &pl) {
       pl.qparts[l - 1] = pl.bf16 ? gemm_bf16_ipdot_parts(pl.dims[l]) : (l == 1 ? 1 : 0);
       if (pl.qparts[l - 1]) pl.o_qpart[l - 1] = take(MB * 4 * pl.qparts[l - 1]);
     }
+    // partial Gram matrices of the short-batch form of the inner products
+    if (pl.bf16) pl.o_gram = take((size_t)gram_ip_scratch_floats(2 * pl.L, pl.M) * 4);
   }
   if (c->has_bias && !pl.bf16) {
     int mx = 0;
@@ -196,13 +199,13 @@ int choose_ksplit(int shape, long long tiles, int KT, double outputs, size_t kpa
 
 // Event-timed launch classes (abs_profile_*): one entry per kernel symbol of interest.
 enum {
-  T_GATHER = 0, T_SOFTMAX, T_ROWNORM, T_COLSUM, T_STATS, T_UPDATE, T_AVERAGE, T_ROWDOT,
+  T_GATHER = 0, T_SOFTMAX, T_ROWNORM, T_COLSUM, T_STATS, T_UPDATE, T_AVERAGE, T_ROWDOT, T_GRAM,
   T_GEMM0,                       // + epi * 3 + tile shape (bf16) ; fp32 family uses shape 1
   T_GEMM_KINDS = 5 * 3, T_LAYERS = 17,   // GEMM classes are resolved per layer
   T_COUNT = T_GEMM0 + T_GEMM_KINDS * T_LAYERS
 };
 static const char *const kTagNames[T_GEMM0 + T_GEMM_KINDS] = {
-  "gather_rows", "softmax_ce", "row_sqnorm", "col_sum", "stats", "update", "average", "rowdot",
+  "gather_rows", "softmax_ce", "row_sqnorm", "col_sum", "stats", "update", "average", "rowdot", "gram_ip",
   "gemm_fwd_128x64", "gemm_fwd_128x128", "gemm_fwd_256x256",
   "gemm_logits_128x64", "gemm_logits_128x128", "gemm_logits_256x256",
   "gemm_bwd_128x64", "gemm_bwd_128x128", "gemm_bwd_256x256",
@@ -237,6 +240,7 @@ struct abs_ctx {
   int last_ps = -1;               // per-sample outputs stored (accumulated steps; -1: all of them)
   bool last_ragged = false;
   bool have_stats = false;
+  int gram_ip_max_b = GRAM_IP_DEFAULT_B;   // abs_set_gram_ip_max_batch: batches up to this size take the Gram form of <g_i, gbar>
   bool fused_update = false;      // abs_set_fused_update: apply the optimizer step inside the weight-gradient epilogue
   bool last_fused = false;        // the last step did so (its fp32 gradient was never stored)
   // captured steps (abs_local_step_graphed): one executable graph per batch size, a few kept
@@ -711,6 +715,11 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     if (slots > pl.Ppad / 256) fused = false;
   }
   int fused_slots = 0;
+  // Short batches take the inner products <g_i, gbar> from the Gram matrices of activations and backprop signals:
+  // the bf16 copy of Gbar is then neither written nor read.  Only a call that runs the whole step can do so (an
+  // accumulated step needs the products between samples of different micro-batches).
+  const bool use_gram = pl.bf16 && pl.want_ip && ph.ip && ph.passes && ph.wgrad && !ph.acc_grad && !ph.acc_q &&
+                        ph.b_total == 0 && b <= c->gram_ip_max_b && b <= GRAM_MAX_B;
   // local batch gradient, eq. (batch_grad): Gbar_l = delta^T a / b, betabar_l = mean_i delta_i
   if (ph.wgrad) {
     for (int l = 1; l <= L; ++l) {
@@ -721,7 +730,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
       p.Md = pl.dims[l]; p.Nd = pl.dims[l - 1]; p.Kd = b; p.groups = M; p.rows = rows; p.gperm = gperm; p.rows_is_k = 1;
       p.C = grad + pl.offW[l]; p.sCg = pl.Ppad; p.ldc = pl.dims[l - 1];
       p.alpha = inv_b; p.accumulate = ph.acc_grad ? 1 : 0;
-      if (pl.bf16 && pl.want_ip) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
+      if (pl.bf16 && pl.want_ip && !use_gram) { p.C2 = c->at<bf16_t>(pl.o_gradbf) + pl.offW[l]; p.sC2g = pl.Ppad; p.ldc2 = pl.dims[l - 1]; }
       if (!pl.bf16 && p.ldc == p.Nd && (((long long)p.Md * p.Nd) & 3) == 0) {
         // fp32 mode (small problems): a block walks its reduction 32 samples at a time, about 2.7 us a step, so
         // a long batch over few 64 x 64 output tiles is cut into up to 8 slices (finish launch: about 8 us)
@@ -784,7 +793,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     if (kf.n > 0) {                        // all split reductions of the step in one launch
       ProfScope ps_(c, T_COLSUM, 0.0, kf_bytes);
       kf.alpha = inv_b; kf.rows = rows; kf.C = grad; kf.sCg = pl.Ppad;
-      kf.C2 = (pl.bf16 && pl.want_ip) ? c->at<bf16_t>(pl.o_gradbf) : nullptr; kf.sC2g = pl.Ppad;
+      kf.C2 = (pl.bf16 && pl.want_ip && !use_gram) ? c->at<bf16_t>(pl.o_gradbf) : nullptr; kf.sC2g = pl.Ppad;
       kf.accumulate = ph.acc_grad ? 1 : 0;
       if (fused) {
         kf.upd_x = xm;
@@ -808,7 +817,25 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   StatsP sp;
   std::memset(&sp, 0, sizeof(sp));
   const bool do_ip = pl.want_ip && ph.ip;
-  if (do_ip) {
+  if (do_ip && use_gram) {
+    GramP gp;
+    std::memset(&gp, 0, sizeof(gp));
+    gp.n = 2 * L; gp.b = b; gp.groups = M; gp.rows = rows;
+    gp.part = c->at<float>(pl.o_gram);
+    double bytes = 0.0;
+    for (int l = 1; l <= L; ++l) {
+      const int a = 2 * (l - 1), d = a + 1;
+      gp.X[a] = static_cast<const bf16_t *>(act_ptr(pl.o_A[l - 1])); gp.sXg[a] = cap * pl.ld[l - 1]; gp.ld[a] = pl.ld[l - 1]; gp.K[a] = pl.dims[l - 1];
+      gp.X[d] = static_cast<const bf16_t *>(act_ptr(pl.o_Dl[l])); gp.sXg[d] = cap * pl.ld[l]; gp.ld[d] = pl.ld[l]; gp.K[d] = pl.dims[l];
+      bytes += 2.0 * M * b * (pl.dims[l - 1] + pl.dims[l]);
+    }
+    float *q = c->at<float>(pl.o_qpart[0]);
+    { ProfScope ps_(c, T_GRAM, 2.0 * M * b * b * (bytes / (2.0 * M * b)), bytes);
+      HIPCHK(c, launch_gram_ip(gp, hb ? 1 : 0, q, cap * pl.qparts[0], s)); }
+    for (int l = 1; l <= L; ++l) {          // one finished vector: it takes the place of the first layer's partials
+      sp.qpart[l - 1] = q; sp.nparts[l - 1] = (l == 1) ? 1 : 0; sp.sQg[l - 1] = cap * pl.qparts[0]; sp.sQpart[l - 1] = cap;
+    }
+  } else if (do_ip) {
     for (int l = 1; l <= L; ++l) {
       GemmP p;
       std::memset(&p, 0, sizeof(p));
@@ -1202,6 +1229,13 @@ abs_status abs_set_fused_update(abs_ctx *c, int on) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (on && !c->pl.bf16) return cfail(c, ABS_EUNSUPPORTED, "the fused update needs ABS_PREC_BF16");
   c->fused_update = on != 0;
+  return ABS_OK;
+} catch (...) { return on_exception(); }
+
+abs_status abs_set_gram_ip_max_batch(abs_ctx *c, int b_max) try {
+  if (!c) return fail(ABS_EINVAL, "ctx is NULL");
+  if (b_max < 0 || b_max > GRAM_MAX_B) return cfail(c, ABS_EINVAL, "b_max must be in [0, 256]");
+  c->gram_ip_max_b = b_max;
   return ABS_OK;
 } catch (...) { return on_exception(); }
 

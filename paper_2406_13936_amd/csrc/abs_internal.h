@@ -87,6 +87,27 @@ int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups);
 // fp32 SIMT family (gemm_f32.hip); EPI_IPDOT is not offered (U is materialised instead).
 hipError_t launch_gemm_f32(const GemmP &p, int epi, hipStream_t s);
 
+// ---- gram_ip.hip -----------------------------------------------------------
+// q[g][i] = (1 / b_g) sum_l sum_j (D_l D_l^T)[i][j] ((A_l A_l^T)[i][j] + [has_bias]),  i, j < b_g: the inner products
+// <g_i, gbar> of a short batch from the Gram matrices of the layer inputs A_l = a^{l-1} and backprop signals
+// D_l = delta^l (bf16, rows = samples, K[.] features at leading dimension ld[.], a multiple of 8).  Matrices come
+// in pairs: X[2 l] = A_l, X[2 l + 1] = D_l.  part: scratch of gram_ip_scratch_floats(n, groups) floats.  The
+// launcher fills in the slicing fields.  b <= GRAM_MAX_B.
+enum { GRAM_MAX_B = 256, GRAM_SLICE_ELEMS = 2 * GRAM_MAX_B * GRAM_MAX_B };
+struct GramP {
+  enum { MAXL = 16 };
+  int n;                                   // matrices (two per layer)
+  const bf16_t *X[2 * MAXL];
+  long long sXg[2 * MAXL];                 // group strides in elements
+  int ld[2 * MAXL], K[2 * MAXL];
+  int b, groups;
+  const int *rows;                         // optional per-group sample counts (device) replacing b
+  float *part;                             // [g][matrix][slice][bp][bp] partial Gram matrices
+  int bp, S, kslice[2 * MAXL], nsl[2 * MAXL];   // set by the launcher: padded b, slices, features per slice, slices in use
+};
+long long gram_ip_scratch_floats(int n, int groups);
+hipError_t launch_gram_ip(GramP p, int has_bias, float *q, long long sQg, hipStream_t s);
+
 // ---- elementwise.hip -------------------------------------------------------
 // T = activation element type: 0 float, 1 bf16
 hipError_t launch_convert_f32_to_bf16(const float *src, bf16_t *dst, long long n, hipStream_t s);

@@ -26,11 +26,16 @@ def _A():
     return A
 
 
-def _oracle_for(w, X, y, x0, mixed):
+# The library's default limit for the Gram form of <g_i, gbar> (abs_set_gram_ip_max_batch): up to this local
+# batch size the bf16 path never rounds Gbar on its way into the inner products, and the mixed oracle is told so.
+GRAM_B = 256
+
+
+def _oracle_for(w, X, y, x0, mixed, gram_b=GRAM_B):
     net = O.Net(w.dims, w.act, w.has_bias)
     return O.Replicas(net, x0, X, y, w.M, opt=w.opt, momentum=w.momentum, beta1=w.beta1,
                       beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay, mixed=mixed,
-                      want_ip=(w.test != W.TEST_NORM))
+                      want_ip=(w.test != W.TEST_NORM), gram_max_b=gram_b if mixed else 0)
 
 
 def _gpu_test(rep, w):
@@ -353,7 +358,8 @@ def test_full_size_at_the_cap_sampled_replicas(cfg, sampled):
                 assert r.sum_q2 * b >= r.sum_q ** 2 * (1 - 1e-6)               # Cauchy-Schwarz on (q_i)
         for m in sampled:
             one = O.Replicas(net, x0, X[idx[m]], y[idx[m]], 1, opt=w.opt, momentum=w.momentum, beta1=w.beta1,
-                             beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay, mixed=True, want_ip=want_ip)
+                             beta2=w.beta2, eps=w.eps, weight_decay=w.weight_decay, mixed=True, want_ip=want_ip,
+                             gram_max_b=GRAM_B)
             one.local_step([np.arange(b)], w.lr)
             s, o = one.stats[0], one.test(w.test, w.eta, w.theta, w.nu)[0]
             grad = rep.get_grad(m).astype(np.float64)
@@ -411,7 +417,7 @@ def test_full_size_from_an_evolved_state(cfg, sampled):
         x_before = rep.get_params(m).astype(np.float64)
         assert np.abs(x_before - x0).max() > 1e-3 * np.abs(x0).max()        # the parameters did move
         one = O.Replicas(net, x_before, X, y, 1, opt=w.opt, momentum=w.momentum, beta1=w.beta1, beta2=w.beta2,
-                         eps=w.eps, weight_decay=w.weight_decay, mixed=True, want_ip=want_ip)
+                         eps=w.eps, weight_decay=w.weight_decay, mixed=True, want_ip=want_ip, gram_max_b=GRAM_B)
         if w.opt != W.OPT_SGD:
             one.st[0].v = rep.get_opt_state(m, 0).astype(np.float64)
         if w.opt == W.OPT_ADAMW:
@@ -782,6 +788,83 @@ def test_ragged_step_with_equal_sizes_is_bitwise_the_uniform_step():
         assert np.array_equal(out[0][0][m], out[1][0][m])
 
 
+@pytest.mark.parametrize("dims,act,hb,bs,limit", [
+    ((384, 256, 256, 256, 100), W.ACT_GELU, True, [64, 64, 64], 256),        # one tile per matrix, several slices
+    ((384, 256, 256, 256, 100), W.ACT_GELU, True, [128, 97, 2], 128),        # two tiles a side; a worker inside the first
+    ((136, 264, 100), W.ACT_RELU, False, [65, 17, 64, 33], 256),             # widths that are no chunk multiple, no bias
+    ((784, 512, 512, 10), W.ACT_RELU, True, [200, 256, 129], 256),           # the largest batch of the Gram form
+    ((40, 24, 5), W.ACT_GELU, True, [2, 3], 256),                            # features fit one ragged chunk
+    ((3072, 2048, 100), W.ACT_GELU, True, [64, 33], 256),                    # config-3 widths: slices of 512 and 384 features
+])
+def test_short_batch_inner_products_from_gram_matrices(dims, act, hb, bs, limit):
+    """<g_i, gbar> from the Gram matrices of activations and backprop signals (short batches) against the mixed
+    oracle that keeps Gbar unrounded, and against the contraction with the stored bf16 Gbar on the same step: the
+    two device forms differ by what the two oracle readings differ by (the bf16 rounding of Gbar), no more."""
+    A = _A()
+    M = len(bs)
+    w = W.Workload("gram", dims, act, hb, W.PREC_BF16, N=2048, M=M, H=1, rounds=1, b0=max(bs), b_cap=max(bs) + 7,
+                   opt=W.OPT_SHB, lr=0.05, momentum=0.9, test=W.TEST_IP, theta=0.9, data="teacher_mlp", seed=13)
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    rows = _ragged_rows(w, bs)
+    full = W.step_indices(w, 3, 1, max(bs))
+    got, want, params = {}, {}, {}
+    for lim in (limit, 0):
+        rep = A.Replicas.from_workload(w, X, y, x0)
+        orc = _oracle_for(w, X, y, x0, mixed=True, gram_b=lim)
+        try:
+            rep.set_gram_ip_max_batch(lim)
+            rep.local_step(full, 0.0)                       # stale rows of a full step in every buffer
+            orc.local_step(full, 0.0)
+            rep.local_step_ragged(rows, w.lr)
+            orc.local_step(rows, w.lr)
+            g = rep.inner_product_test(w.theta)
+            o = orc.test(W.TEST_IP, theta=w.theta)
+            got[lim], want[lim] = [], []
+            for m in range(M):
+                s = orc.stats[m]
+                n, q = rep.get_per_sample(m, bs[m], want_q=True)
+                nerr = np.abs(n - s["n"]) / s["n"]
+                assert nerr.max() <= (2e-2 if act == W.ACT_RELU else 5e-3) and np.median(nerr) <= 1e-4, (lim, m, nerr.max())
+                # measured: 4e-5 of max |q| at worst with GELU; with ReLU a unit whose pre-activation changes sign
+                # under the device's fp32 accumulation moves single samples by up to 1.2e-3 (in either form)
+                err = np.abs(q - s["q"]) / np.abs(s["q"]).max()
+                worst, typical = float(err.max()), float(np.median(err))
+                assert worst <= (3e-3 if act == W.ACT_RELU else 5e-4) and typical <= 1e-4, (lim, m, worst, typical)
+                for name, gv, ov in (("S1", g[m].sum_sq, s["S1"]), ("S2", g[m].gbar_sq, s["S2"]),
+                                     ("S3", g[m].sum_q2, s["S3"]), ("S4", g[m].sum_q, s["S4"])):
+                    assert _rel(gv, ov) <= 5e-4, (lim, m, name, gv, ov)
+                if bs[m] > 2:
+                    assert _rel(g[m].ratio, o[m]["ratio"]) <= 2e-2, (lim, m)
+                got[lim].append(q.astype(np.float64))
+                want[lim].append(s["q"])
+            params[lim] = [rep.get_params(m) for m in range(M)]
+        finally:
+            rep.close()
+    for m in range(M):
+        # the step itself does not depend on the form of the inner products
+        assert np.array_equal(params[limit][m], params[0][m])
+        dev = np.abs(got[limit][m] - got[0][m]).max() / np.abs(got[0][m]).max()
+        ref = np.abs(want[limit][m] - want[0][m]).max() / np.abs(want[0][m]).max()
+        assert 0.0 < ref <= 2e-3                         # the rounding of Gbar is visible, and small
+        assert abs(dev - ref) <= 0.25 * ref + 2e-5, (m, dev, ref)
+
+
+def test_gram_limit_argument_is_checked():
+    A = _A()
+    w = _one_step_case((64, 32, 10), W.ACT_RELU, W.PREC_BF16, 24, 2, N=256)
+    X, y = W.make_dataset(w)
+    rep = A.Replicas.from_workload(w, X, y, W.make_x0(w))
+    try:
+        for bad in (-1, 257):
+            with pytest.raises(A.AbsError, match="b_max"):
+                rep.set_gram_ip_max_batch(bad)
+        rep.set_gram_ip_max_batch(0)
+        rep.set_gram_ip_max_batch(256)
+    finally:
+        rep.close()
+
+
 def test_per_worker_schedule_lockstep_fp32():
     """Alg. 1 with each worker keeping its own batch size (no max over workers) and its own eta."""
     A = _A()
@@ -890,6 +973,7 @@ def test_accumulated_step_in_one_micro_batch_equals_the_plain_step():
     for accumulated in (False, True):
         rep = A.Replicas.from_workload(w, X, y, x0)
         try:
+            rep.set_gram_ip_max_batch(0)      # accumulated steps always contract the stored bf16 Gbar: same form for both
             if accumulated:
                 rep.local_step_accumulated(idx, 200, w.lr)
             else:
@@ -1351,7 +1435,7 @@ def test_batch_size_sweep_keeps_every_scratch_piece_in_bounds(dims, act):
             idx = W.step_indices(w, 0, 1, b)
             rep.local_step(idx, 0.0)                                  # lr = 0: the parameters stay at x0
             g = rep.inner_product_test(w.theta)
-            one = O.Replicas(net, x0, X[idx[0]], y[idx[0]], 1, mixed=True, want_ip=True)
+            one = O.Replicas(net, x0, X[idx[0]], y[idx[0]], 1, mixed=True, want_ip=True, gram_max_b=GRAM_B)
             one.local_step([np.arange(b)], 0.0)
             s = one.stats[0]
             for name, got, want in (("S1", g[0].sum_sq, s["S1"]), ("S2", g[0].gbar_sq, s["S2"]),

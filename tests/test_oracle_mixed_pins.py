@@ -269,3 +269,60 @@ def test_alg2_loop_tests_once_per_round_on_the_last_gradients():
         b = min(64, max(T, b))
     assert B == Bh and sched[-1][1] > 4
     np.testing.assert_allclose(xs, x, rtol=1e-10, atol=1e-13)
+
+
+# ---- <g_i, gbar> with and without the rounding of Gbar ----------------------------------------
+
+def test_unrounded_gbar_operand_equals_the_sum_of_per_sample_products():
+    """With round_gbar off the mixed q_i is the mean over j of <g_i, g_j> taken from per-sample gradients
+    that were each formed on their own (batches of one sample through the same rounding points); with it on,
+    q_i is the product with the rounded mean, which differs by at most the bf16 rounding of that mean."""
+    rng = np.random.default_rng(23)
+    net = O.Net((12, 9, 7, 4), O.ACT_GELU, True)
+    x = O.bf16_round(rng.normal(0, 0.5, size=net.n_params))
+    Xb = rng.normal(0, 1, size=(11, 12))
+    yb = rng.integers(0, 4, size=11)
+    g = O.per_sample_gradients(net, x, Xb, yb, mixed=True)              # [b, P], one backprop per sample
+    gram = g @ g.T
+    want = gram.mean(axis=1)
+    bp = O.backprop(net, x, Xb, yb, mixed=True)
+    plain = O.stats_factored(net, bp, True, mixed=True, round_gbar=False)
+    np.testing.assert_allclose(plain["q"], want, rtol=1e-12, atol=1e-15)
+    # the same sum layer by layer: (delta_i . delta_j)(a_i . a_j + 1), the form the short-batch device path adds up
+    by_layer = np.zeros_like(gram)
+    for a, d in zip(bp["a"], bp["delta"]):
+        by_layer += (d @ d.T) * (a @ a.T + 1.0)
+    np.testing.assert_allclose(by_layer, gram, rtol=1e-12, atol=1e-15)
+    rounded = O.stats_factored(net, bp, True, mixed=True, round_gbar=True)
+    diff = np.abs(rounded["q"] - plain["q"])
+    assert diff.max() > 0.0
+    # |<g_i, bf16(gbar) - gbar>| <= 2^-9 sum_k |g_ik gbar_k| over the weight entries
+    gbar = g.mean(axis=0)
+    assert np.all(diff <= 2.0 ** -9 * (np.abs(g) * np.abs(gbar)).sum(axis=1) + 1e-15)
+    # exact mode has no rounding to switch off
+    e1 = O.stats_factored(net, O.backprop(net, x, Xb, yb), True, round_gbar=False)
+    e2 = O.stats_factored(net, O.backprop(net, x, Xb, yb), True, round_gbar=True)
+    assert np.array_equal(e1["q"], e2["q"])
+
+
+def test_replicas_choose_the_operand_rounding_by_the_largest_local_batch():
+    rng = np.random.default_rng(29)
+    net = O.Net((6, 5, 3), O.ACT_RELU, True)
+    X, y = rng.normal(size=(64, 6)), rng.integers(0, 3, size=64)
+    x0 = rng.normal(0, 0.4, size=net.n_params)
+
+    def q_of(gram_max_b, sizes):
+        rep = O.Replicas(net, x0, X, y, len(sizes), mixed=True, want_ip=True, gram_max_b=gram_max_b)
+        rep.local_step([np.arange(n) for n in sizes], 0.1)
+        return [s["q"] for s in rep.stats]
+
+    def direct(n, round_gbar):
+        bp = O.backprop(net, x0, X[:n], y[:n], mixed=True)
+        return O.stats_factored(net, bp, True, mixed=True, round_gbar=round_gbar)["q"]
+
+    assert np.array_equal(q_of(0, [8, 8])[0], direct(8, True))          # default: always the rounded operand
+    assert np.array_equal(q_of(8, [8, 8])[1], direct(8, False))         # b <= limit: unrounded
+    assert np.array_equal(q_of(7, [8, 8])[1], direct(8, True))          # b above the limit
+    ragged = q_of(8, [6, 9])                                            # the largest batch decides for every worker
+    assert np.array_equal(ragged[0], direct(6, True)) and np.array_equal(ragged[1], direct(9, True))
+    assert not np.array_equal(direct(8, True), direct(8, False))
