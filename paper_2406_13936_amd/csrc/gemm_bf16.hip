@@ -590,7 +590,10 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
     // The slices (32 rows x TN columns per wave) are walked in batches of HB chunks per lane.  The loads of batch
     // k + 1 (parameters and optimizer state) are issued before batch k is processed, so that a wave always has a
     // batch of loads in flight while it computes and stores.
-    constexpr int HB = FIT < 2 ? FIT : 2;
+    // (four chunks for the 128 x 128 tiles: config 3 at b = 64 2.4 % faster than with two, b = 256 unchanged; the
+    // 256 x 256 tile has no registers to spare for more than two)
+    constexpr int HBW = (BM == 128 && BN == 128) ? 4 : 2;
+    constexpr int HB = FIT < HBW ? FIT : HBW;
     constexpr int BPS = FIT / HB, NBATCH = MI * BPS;
     static_assert(FIT % HB == 0, "chunk batches");
     float4 xq[2][HB], vq[2][HB], mq[2][HB];
