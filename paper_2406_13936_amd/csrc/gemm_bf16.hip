@@ -265,6 +265,48 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
 #pragma unroll
   for (int j = 0; j < NI; ++j) fb[j].init(wn * TN + j * 32, lane);
 
+  // Fused optimizer step (EPI_WGRAD_UPD): the epilogue walks this wave's slices (32 rows x TN columns) in batches of
+  // UHB 16-byte chunks per lane, and the loads of batch k + 1 (parameters and optimizer state) are issued before
+  // batch k is processed, so that a wave always has a batch of loads in flight while it computes and stores.
+  // (Four chunks for the 128 x 128 tiles: config 3 at b = 64 2.4 % faster than with two, b = 256 unchanged; the
+  // 256 x 256 tile has no registers to spare for more than two.)
+  constexpr bool UPD = EPI == EPI_WGRAD_UPD;
+  constexpr int UFCPR = TN / 4;                             // float4 chunks per slice row
+  constexpr int UFIT = 32 * UFCPR / 64;                     // chunks per lane per slice
+  constexpr int UHBW = (BM == 128 && BN == 128) ? 4 : 2;
+  constexpr int UHB = UFIT < UHBW ? UFIT : UHBW;
+  constexpr int UBPS = UFIT / UHB;
+  static_assert(!UPD || UFIT % UHB == 0, "chunk batches");
+  // The 128 x 128 tiles (short batches: a launch is all epilogue) issue the first batch before the operand loads of
+  // the reduction, so that its latency passes behind the main loop; being older than every operand load, these
+  // loads do not disturb the counting of the main loop's waits (loads return in order).
+  constexpr bool UPD_EARLY = UPD && BM == 128 && BN == 128;
+  float4 xq[2][UPD ? UHB : 1], vq[2][UPD ? UHB : 1], mq[2][UPD ? UHB : 1];
+  const long long ugoff = UPD ? (long long)g * p.sCg : 0;
+  auto upd_where = [&](int bi, int u, int &m, int &n, int &row, int &cc) {
+    const int c = ((bi % UBPS) * UHB + u) * 64 + lane;
+    row = c / UFCPR; cc = c % UFCPR;
+    m = m0 + wm * TM + (bi / UBPS) * 32 + row;
+    n = n0 + wn * TN + cc * 4;
+  };
+  auto upd_prefetch = [&](int bi) {
+    if constexpr (UPD) {
+#pragma unroll
+      for (int u = 0; u < UHB; ++u) {
+        int m, n, row, cc;
+        upd_where(bi, u, m, n, row, cc);
+        xq[bi & 1][u] = vq[bi & 1][u] = mq[bi & 1][u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (m < p.Md && n < p.Nd) {                          // Nd is a multiple of 4 (checked by the launcher)
+          const long long o = ugoff + (long long)m * p.ldc + n;
+          xq[bi & 1][u] = ld_once(p.upd_x + o);
+          if (ACT != OPT_SGD) vq[bi & 1][u] = ld_once(p.upd_v + o);       // (the optimizer travels in the activation slot)
+          if (ACT == OPT_ADAMW) mq[bi & 1][u] = ld_once(p.upd_m + o);
+        }
+      }
+    }
+  };
+  if constexpr (UPD_EARLY) upd_prefetch(0);
+
   const int KT = (p.Kd + BK - 1) / BK;
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s) {
@@ -579,45 +621,18 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
     // The optimizer step in place of the gradient store: a lane's staged float4 holds four consecutive entries
     // of one row of Gbar_l; the parameters, their state and their bf16 shadow sit at the same offsets.
     const long long goff = (long long)g * p.sCg;
-    float *__restrict__ X = p.upd_x + goff;
-    float *__restrict__ V = p.upd_v ? p.upd_v + goff : nullptr;
-    float *__restrict__ Mo = p.upd_m ? p.upd_m + goff : nullptr;
+    float *X = p.upd_x + goff;                               // (loaded through upd_prefetch, stored through these)
+    float *V = p.upd_v ? p.upd_v + goff : nullptr;
+    float *Mo = p.upd_m ? p.upd_m + goff : nullptr;
     bf16_t *__restrict__ SH = p.upd_shadow ? p.upd_shadow + goff : nullptr;
     OptHyper h = {p.upd_lr, p.upd_momentum, p.upd_beta1, p.upd_beta2, p.upd_eps, p.upd_wd, p.upd_c1, p.upd_c2};
     if (p.upd_scal) { h.lr = p.upd_scal[0]; h.c1 = p.upd_scal[1]; h.c2 = p.upd_scal[2]; }     // uniform loads
     constexpr int opt = ACT;                                 // the optimizer travels in the activation slot
     float sq = 0.0f;
-    // The slices (32 rows x TN columns per wave) are walked in batches of HB chunks per lane.  The loads of batch
-    // k + 1 (parameters and optimizer state) are issued before batch k is processed, so that a wave always has a
-    // batch of loads in flight while it computes and stores.
-    // (four chunks for the 128 x 128 tiles: config 3 at b = 64 2.4 % faster than with two, b = 256 unchanged; the
-    // 256 x 256 tile has no registers to spare for more than two)
-    constexpr int HBW = (BM == 128 && BN == 128) ? 4 : 2;
-    constexpr int HB = FIT < HBW ? FIT : HBW;
-    constexpr int BPS = FIT / HB, NBATCH = MI * BPS;
-    static_assert(FIT % HB == 0, "chunk batches");
-    float4 xq[2][HB], vq[2][HB], mq[2][HB];
-    auto where = [&](int bi, int u, int &m, int &n, int &row, int &cc) {
-      const int c = ((bi % BPS) * HB + u) * 64 + lane;
-      row = c / FCPR; cc = c % FCPR;
-      m = m0 + wm * TM + (bi / BPS) * 32 + row;
-      n = nw0 + cc * 4;
-    };
-    auto prefetch = [&](int bi) {
-#pragma unroll
-      for (int u = 0; u < HB; ++u) {
-        int m, n, row, cc;
-        where(bi, u, m, n, row, cc);
-        xq[bi & 1][u] = vq[bi & 1][u] = mq[bi & 1][u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (m < p.Md && n < p.Nd) {                          // Nd is a multiple of 4 (checked by the launcher)
-          const long long o = (long long)m * p.ldc + n;
-          xq[bi & 1][u] = ld_once(X + o);
-          if (opt != OPT_SGD) vq[bi & 1][u] = ld_once(V + o);
-          if (opt == OPT_ADAMW) mq[bi & 1][u] = ld_once(Mo + o);
-        }
-      }
-    };
-    prefetch(0);
+    constexpr int HB = UHB, BPS = UBPS, NBATCH = MI * BPS;
+    auto &where = upd_where;
+    auto &prefetch = upd_prefetch;
+    if constexpr (!UPD_EARLY) prefetch(0);
 #pragma unroll
     for (int bi = 0; bi < NBATCH; ++bi) {
       if (bi % BPS == 0) {                                   // a new slice: accumulators -> staging
