@@ -394,6 +394,58 @@ def test_full_size_at_the_cap_sampled_replicas(cfg, sampled):
         rep.close()
 
 
+@pytest.mark.parametrize("fused", [False, True])
+def test_config3_full_width_at_its_first_batch_size(fused):
+    """Config 3 as `bench.py --batch 64` runs it (all 16 replicas, real widths, b = b0 = 64: the short-batch launch
+    configuration, with the inner products from Gram matrices), plain and with the optimizer step in the
+    weight-gradient epilogue: two local steps from x0, two workers recomputed by the oracle at both steps
+    (free-running: the second step starts from each side's own parameters and heavy-ball state)."""
+    A = _A()
+    w = W.config3()
+    X, y = W.make_dataset(w)
+    x0 = W.make_x0(w)
+    b, sampled = w.b0, (0, 11)
+    rep = A.Replicas.from_workload(w, X, y, x0)
+    orc = _oracle_for(w, X, y, x0, mixed=True)
+    try:
+        if fused:
+            rep.set_fused_update(True)
+        for h in range(2):
+            idx = W.step_indices(w, 0, h, b)
+            rep.local_step(idx, w.lr)
+            g = _gpu_test(rep, w)
+            orc.local_step(idx, w.lr, only=sampled)
+            o = orc.test(w.test, w.eta, w.theta, w.nu)
+            for m in range(w.M):
+                r = g[m]
+                assert r.b == b and np.isfinite([r.sum_sq, r.gbar_sq, r.sum_q, r.sum_q2, r.ratio]).all()
+                assert r.sum_sq >= b * r.gbar_sq                                   # Jensen
+                assert _rel(r.sum_q, b * r.gbar_sq) <= 1e-3                        # sum_i <g_i, gbar> = b ||gbar||^2
+                assert r.sum_q2 * b >= r.sum_q ** 2 * (1 - 1e-6)                   # Cauchy-Schwarz on (q_i)
+            for m in sampled:
+                s = orc.stats[m]
+                for name, got, want in (("S1", g[m].sum_sq, s["S1"]), ("S2", g[m].gbar_sq, s["S2"]),
+                                        ("S3", g[m].sum_q2, s["S3"]), ("S4", g[m].sum_q, s["S4"]),
+                                        ("loss", g[m].loss_sum, s["loss_sum"])):
+                    assert _rel(got, want) <= 2e-3, (h, m, name, got, want)
+                assert _rel(g[m].ratio, o[m]["ratio"]) <= 2e-2
+                _check_decision(g[m], o[m], b, BF16_BAND, ("cfg3 b0", h, m))
+                n, q = rep.get_per_sample(m, b, want_q=True)
+                np.testing.assert_allclose(n, s["n"], rtol=5e-3)
+                assert np.abs(q - s["q"]).max() <= 2e-3 * np.abs(s["q"]).max(), (h, m)
+                if not fused:
+                    grad = rep.get_grad(m).astype(np.float64)
+                    assert np.abs(grad - orc.grads[m]).max() <= 2e-3 * np.abs(orc.grads[m]).max()
+                p = rep.get_params(m).astype(np.float64)
+                assert np.abs(p - orc.x[m]).max() <= 1e-3 * np.abs(orc.x[m]).max(), (h, m)
+                if h == 1:                                   # the heavy-ball state after two steps
+                    v = rep.get_opt_state(m, 0).astype(np.float64)
+                    assert np.abs(v - orc.st[m].v).max() <= 2e-3 * np.abs(orc.st[m].v).max()
+        assert rep.guard_intact()
+    finally:
+        rep.close()
+
+
 @pytest.mark.parametrize("cfg,sampled", [("config3", 5), ("config4", 20)])
 def test_full_size_from_an_evolved_state(cfg, sampled):
     """The configurations at their full sizes away from the initial point: eight local steps at the cap with the
