@@ -48,8 +48,11 @@ def parse():
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     ap.add_argument("--graphs", action="store_true",
                     help="replay captured HIP graphs on the steps that are not bracketed by events (fixed batch size)")
-    ap.add_argument("--fused-update", action="store_true",
-                    help="opt in to the optimizer step inside the weight-gradient epilogue (abs_set_fused_update)")
+    ap.add_argument("--plain-update", action="store_true",
+                    help="store the fp32 gradient and run the optimizer as a kernel of its own "
+                         "(abs_set_fused_update(0)) instead of the library's default for bf16, the step inside the "
+                         "weight-gradient epilogue")
+    ap.add_argument("--fused-update", action="store_true", help="the default; accepted for older command lines")
     ap.add_argument("--gram-ip-max-batch", type=int, default=-1,
                     help="largest local batch whose inner products come from Gram matrices "
                          "(abs_set_gram_ip_max_batch; default: the library's, 256; 0: never)")
@@ -163,8 +166,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     if a.graphs:
         torch.cuda.set_stream(torch.cuda.Stream())     # stream capture needs a created stream (default priority)
     rep = A.Replicas.from_workload(w, X, y, x0)
-    if a.fused_update:
-        rep.set_fused_update(True)
+    if a.plain_update and w.prec == W.PREC_BF16:
+        rep.set_fused_update(False)
     if a.gram_ip_max_batch >= 0:
         rep.set_gram_ip_max_batch(a.gram_ip_max_batch)
     b_fixed = a.batch or w.b_cap
@@ -223,8 +226,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
         torch.cuda.synchronize()
         rep.close()
         rep = A.Replicas.from_workload(w, X, y, x0)
-        if a.fused_update:
-            rep.set_fused_update(True)
+        if a.plain_update and w.prec == W.PREC_BF16:
+            rep.set_fused_update(False)
         if a.gram_ip_max_batch >= 0:
             rep.set_gram_ip_max_batch(a.gram_ip_max_batch)
     b = w.b0 if a.adaptive else b_fixed
@@ -317,7 +320,7 @@ def measure(a, wname, np, torch, A, W, with_cpu):
             # (scaled by the copy kernel) in the committed summary of this same command: a stored profile, not a
             # reading of this run; null when no summary covers the class
             tpath = os.path.join(ROOT, "profiles", "pmc_traffic_%s.json" % wname)
-            if os.path.exists(tpath) and not a.adaptive and not a.batch and not a.fused_update:
+            if os.path.exists(tpath) and not a.adaptive and not a.batch and not a.plain_update:
                 try:
                     tj = json.load(open(tpath)).get("kernels", {})
                     if all(k in tj for k in v["layers"]):
@@ -349,8 +352,8 @@ def measure(a, wname, np, torch, A, W, with_cpu):
     }
     if sustained:
         out.update(sustained)
-    if a.fused_update:
-        out["config"]["fused_update"] = True
+    if w.prec == W.PREC_BF16:
+        out["config"]["update"] = "separate kernel" if a.plain_update else "in the weight-gradient epilogue"
     if a.graphs:
         out["config"]["hip_graphs"] = n_graphs
     if with_cpu:
@@ -438,14 +441,14 @@ def main():
             "local_batch": o2["config"]["local_batch"], "M": o2["config"]["M"],
             "all_gemms_tflops": (o2.get("roofline") or {}).get("all_gemms_tflops")}}
         # the same configuration in its short-batch regime (its first size, where the adaptive run stays): bound by
-        # HBM, plain and with the optimizer step inside the weight-gradient epilogue; and the latter at the cap
+        # HBM; and both sizes with the optimizer as a kernel of its own (abs_set_fused_update(0))
         import copy
-        for key, batch, fused in (("cfg3_b64", 64, False), ("cfg3_b64_fused_update", 64, True),
-                                  ("cfg3_cap_fused_update", 0, True)):
-            if fused and a.fused_update:
+        for key, batch, plain in (("cfg3_b64", 64, False), ("cfg3_b64_plain_update", 64, True),
+                                  ("cfg3_cap_plain_update", 0, True)):
+            if plain and a.plain_update:
                 continue
             a2 = copy.copy(a)
-            a2.batch, a2.fused_update, a2.steps, a2.warmup = batch, fused or a.fused_update, 40 if batch else a.steps, 5
+            a2.batch, a2.plain_update, a2.steps, a2.warmup = batch, plain or a.plain_update, 40 if batch else a.steps, 5
             o3 = measure(a2, "config3", np, torch, A, W, False)
             r3 = o3.get("roofline") or {}
             out["also"][key] = {"value": o3["value"], "unit": o3["unit"], "ms_per_step": o3["ms_per_step"],

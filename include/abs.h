@@ -210,16 +210,19 @@ abs_status abs_next_batch_size(const abs_test_result *res, int M, const int *b_c
 abs_status abs_average_replicas(abs_ctx *ctx);
 
 /*
- * Opt-in: apply the optimizer step of the weights inside the epilogue of the weight-gradient contraction instead
- * of storing the fp32 gradient and streaming it through a separate update (Alg. 1's "local step" fused into
- * "compute the local batch gradient").  At small local batch sizes, where a step is bound by the bytes moved
- * per parameter, this removes 8 of 28 bytes per parameter (heavy ball).  ||gbar||^2 is then summed from
- * per-wavefront partial sums left by the epilogues, the batch gradient of the weights exists only as the bf16
- * copy that the inner products use, and the statistics, tests and parameters are those of the unfused step up to
- * the order of the additions in ||gbar||^2.  While it is on: abs_get_grad and abs_cross_worker_test after such a
- * step and abs_local_step_accumulated return ABS_ESTATE (they need the stored gradient).  A layer whose weight
- * gradient splits its reduction over the batch (few output tiles, long batches) takes its step in the launch that
- * adds the slices.  Needs ABS_PREC_BF16 (ABS_EUNSUPPORTED otherwise).
+ * Where the optimizer step of the weights is applied (ABS_PREC_BF16; on by default): inside the epilogue of the
+ * weight-gradient contraction (Alg. 1's "local step" fused into "compute the local batch gradient"), instead of
+ * storing the fp32 gradient and streaming it through a separate update.  At small local batch sizes, where a step is
+ * bound by the bytes moved per parameter, this removes 8 of 26 bytes per parameter (heavy ball).  ||gbar||^2 is then
+ * summed from per-wavefront partial sums left by the epilogues, and the statistics, tests and parameters are those of
+ * the separate update up to the order of the additions in ||gbar||^2 (parameters: bit for bit).  The fp32 gradient of
+ * the weights is not stored by such a step; abs_get_grad and abs_cross_worker_test form it on demand from the layer
+ * inputs and backprop signals the step left in the workspace (the same contractions with a plain epilogue: the very
+ * entries the step applied), which costs one more pass of the weight-gradient contractions.  A caller that reads the
+ * gradient after every step (Alg. 2 with H = 1) may prefer on = 0.  A layer whose weight gradient splits its
+ * reduction over the batch (few output tiles, long batches) takes its step in the launch that adds the slices;
+ * abs_local_step_accumulated, which keeps the gradient in memory between micro-batches, always updates separately,
+ * as does a net with a layer width that is no multiple of 4.  on != 0 with ABS_PREC_F32: ABS_EUNSUPPORTED.
  */
 abs_status abs_set_fused_update(abs_ctx *ctx, int on);
 

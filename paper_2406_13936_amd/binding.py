@@ -305,7 +305,7 @@ class Replicas:
         return out
 
     def set_fused_update(self, on: bool = True):
-        """Opt in to (or out of) the optimizer step inside the weight-gradient epilogue."""
+        """The optimizer step inside the weight-gradient epilogue (bf16 default) or as a kernel of its own."""
         _check(self._lib.abs_set_fused_update(self._ctx, int(bool(on))), self._ctx)
 
     def set_gram_ip_max_batch(self, b_max: int):

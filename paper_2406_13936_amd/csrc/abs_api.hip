@@ -241,8 +241,8 @@ struct abs_ctx {
   bool last_ragged = false;
   bool have_stats = false;
   int gram_ip_max_b = GRAM_IP_DEFAULT_B;   // abs_set_gram_ip_max_batch: batches up to this size take the Gram form of <g_i, gbar>
-  bool fused_update = false;      // abs_set_fused_update: apply the optimizer step inside the weight-gradient epilogue
-  bool last_fused = false;        // the last step did so (its fp32 gradient was never stored)
+  bool fused_update = true;       // abs_set_fused_update: apply the optimizer step inside the weight-gradient epilogue (bf16 mode)
+  bool last_fused = false;        // the last step did so: the fp32 gradient of its weights is not stored (materialize_grad)
   // captured steps (abs_local_step_graphed): one executable graph per batch size, a few kept
   struct GraphSlot { int b; hipGraphExec_t exec; long long last_use; };
   std::vector<GraphSlot> graphs;
@@ -559,6 +559,7 @@ struct StepPhase {
   float c1 = 1.0f, c2 = 1.0f;   // Adam bias corrections 1 / (1 - beta^t) of this step (set by the caller)
   const float *scal = nullptr;  // device {lr, c1, c2} for replayable launches (then lr / c1 / c2 here are unused)
   long long ps_off = 0;  // offset of this call's samples in the per-sample outputs (-1: not stored)
+  bool whole_launches = false;  // take the split decisions of a step with the update in the epilogue (materialize_grad)
 };
 
 static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, int b, const int *b_host, float lr,
@@ -688,6 +689,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   // Number of slices of layer l's weight-gradient reduction (bf16 mode): few output tiles and a long reduction
   // (small layers, or any layer while b is the long side) are cut into slices so that the launch fills the chip;
   // the slices are added in order afterwards.
+  const bool want_fused = c->fused_update && pl.bf16 && ph.wgrad && ph.update && ph.s2 && !ph.acc_grad;
   auto bf16_ksplit = [&](int l) -> int {
     const int Md = pl.dims[l], Nd = pl.dims[l - 1];
     if (!pl.bf16 || (Nd & 3)) return 1;
@@ -697,12 +699,12 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
     const long long tiles = (long long)((Md + te - 1) / te) * ((Nd + tn_e - 1) / tn_e) * M;
     // with the optimizer step in the epilogue a launch that gives every CU a work-group stays whole (measured on the
     // 100 x 2048 layer of config 3 at b = 8192: 256 tiles un-split take as long as the split launch and its finish)
-    if (c->fused_update && tiles >= 256) return 1;
+    if ((want_fused || ph.whole_launches) && tiles >= 256) return 1;
     return choose_ksplit(sh, tiles, (b + 63) / 64, (double)M * Md * Nd, pl.kpart_floats_l[l]);
   };
   // The optimizer step moves into the weight-gradient epilogue when the caller asked for it and this call both
   // finishes the gradient and updates, no reduction is split and the per-wavefront sums of squares fit their scratch.
-  bool fused = c->fused_update && pl.bf16 && ph.wgrad && ph.update && ph.s2 && !ph.acc_grad;
+  bool fused = want_fused;
   if (fused) {
     long long slots = 0;
     for (int l = 1; l <= L; ++l) {
@@ -948,6 +950,31 @@ static abs_status settle_update(abs_ctx *c, abs_status st) {
   return st;
 }
 
+// Captured steps record which form of the update and of the inner products they took: a change of either setting
+// discards them (the next graphed step captures again).
+static void drop_graphs(abs_ctx *c) {
+  if (c->graphs.empty()) return;
+  (void)hipStreamSynchronize(c->stream);          // one of them may still be running
+  for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.exec);
+  c->graphs.clear();
+}
+
+// After a step that took the optimizer step inside the weight-gradient epilogue the fp32 gradient of the weights was
+// never stored.  The layer inputs and backprop signals of that step are still in the workspace (only the next step
+// overwrites them), so the gradient is formed on demand: the same contractions with the plain epilogue, cut into the
+// same launches, give the very entries the epilogue applied.  Bias gradients were stored by the step itself.
+static abs_status materialize_grad(abs_ctx *c) {
+  if (!c->last_fused) return ABS_OK;
+  StepPhase ph;
+  ph.passes = ph.nstats = ph.s2 = ph.ip = ph.update = false;
+  ph.whole_launches = true;
+  ph.ps_off = -1;
+  abs_status st = local_step_impl(c, nullptr, c->last_b, c->last_b, c->last_ragged ? c->last_bm.data() : nullptr, 0.0f, ph);
+  if (st != ABS_OK) return st;
+  c->last_fused = false;
+  return ABS_OK;
+}
+
 // One more optimizer step is about to be taken: advance the counter and return Adam's bias corrections.
 static void next_update(abs_ctx *c, StepPhase &ph) {
   c->t += 1;
@@ -1041,7 +1068,6 @@ abs_status abs_local_step_accumulated(abs_ctx *c, const int32_t *idx_dev, int b,
   if (!idx_dev) return cfail(c, ABS_EINVAL, "idx_dev is NULL");
   if (!(lr == lr)) return cfail(c, ABS_EINVAL, "lr is NaN");
   const int cap = c->pl.cap;
-  if (c->fused_update) return cfail(c, ABS_ESTATE, "accumulated steps keep the gradient in memory: switch abs_set_fused_update off");
   if (micro_b < 2 || micro_b > cap) return cfail(c, ABS_EINVAL, "micro_b must be in [2, b_cap]");
   if (b < 2) return cfail(c, ABS_EINVAL, "b must be at least 2");
   if (b % micro_b == 1) return cfail(c, ABS_EINVAL, "the last micro-batch would hold a single sample");
@@ -1176,7 +1202,7 @@ abs_status abs_cross_worker_test(abs_ctx *c, double eta, abs_test_result *out) t
   if (c->pl.M < 2) return cfail(c, ABS_EINVAL, "the cross-worker estimator needs M >= 2");
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
   if (c->last_ragged) return cfail(c, ABS_ESTATE, "the cross-worker estimator needs equal local batch sizes");
-  if (c->last_fused) return cfail(c, ABS_ESTATE, "the last step updated inside the weight-gradient epilogue: its gradient was not stored");
+  { abs_status ms = materialize_grad(c); if (ms != ABS_OK) return ms; }
   const Plan &pl = c->pl;
   double *cw = c->at<double>(pl.o_cw);
   HIPCHK(c, launch_cross_worker(c->at<float>(pl.o_grad), pl.M, pl.Ppad, cw + 8, cw, c->stream));
@@ -1228,6 +1254,7 @@ abs_status abs_average_replicas(abs_ctx *c) try {
 abs_status abs_set_fused_update(abs_ctx *c, int on) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (on && !c->pl.bf16) return cfail(c, ABS_EUNSUPPORTED, "the fused update needs ABS_PREC_BF16");
+  if (c->fused_update != (on != 0)) drop_graphs(c);      // captured steps recorded the other form
   c->fused_update = on != 0;
   return ABS_OK;
 } catch (...) { return on_exception(); }
@@ -1235,6 +1262,7 @@ abs_status abs_set_fused_update(abs_ctx *c, int on) try {
 abs_status abs_set_gram_ip_max_batch(abs_ctx *c, int b_max) try {
   if (!c) return fail(ABS_EINVAL, "ctx is NULL");
   if (b_max < 0 || b_max > GRAM_MAX_B) return cfail(c, ABS_EINVAL, "b_max must be in [0, 256]");
+  if (c->gram_ip_max_b != b_max) drop_graphs(c);         // captured steps recorded the other form
   c->gram_ip_max_b = b_max;
   return ABS_OK;
 } catch (...) { return on_exception(); }
@@ -1275,7 +1303,7 @@ abs_status abs_get_grad(abs_ctx *c, int m, float *out_host) try {
   if (!c || !out_host) return fail(ABS_EINVAL, "NULL argument");
   if (m < 0 || m >= c->pl.M) return cfail(c, ABS_EINVAL, "replica index out of range");
   if (!c->have_stats) return cfail(c, ABS_ESTATE, "no local step has been taken yet");
-  if (c->last_fused) return cfail(c, ABS_ESTATE, "the last step updated inside the weight-gradient epilogue: its gradient was not stored");
+  { abs_status ms = materialize_grad(c); if (ms != ABS_OK) return ms; }
   std::vector<float> in(c->pl.Ppad);
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipMemcpy(in.data(), c->at<float>(c->pl.o_grad) + (size_t)m * c->pl.Ppad, c->pl.Ppad * sizeof(float), hipMemcpyDeviceToHost));

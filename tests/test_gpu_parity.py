@@ -96,8 +96,8 @@ def _lockstep(w, rounds, stat_tol, band, resync_params, param_tol=None, mixed=No
     if ratio_tol is None:
         ratio_tol = 2e-2 if w.prec == W.PREC_BF16 else 1e-4      # the target statement's statistic tolerances
     rep = A.Replicas.from_workload(w, X, y, x0)
-    if fused:
-        rep.set_fused_update(True)       # the optimizer step inside the weight-gradient epilogue
+    if w.prec == W.PREC_BF16:
+        rep.set_fused_update(fused)      # the optimizer step inside the weight-gradient epilogue, or the separate update
     orc = _oracle_for(w, X, y, x0, mixed)
     adam_like = w.opt in (W.OPT_ADAMW, W.OPT_ADAGRAD)
     b, exempt, steps, worst, worst_p = w.b0, 0, 0, 0.0, 0.0
@@ -408,8 +408,7 @@ def test_config3_full_width_at_its_first_batch_size(fused):
     rep = A.Replicas.from_workload(w, X, y, x0)
     orc = _oracle_for(w, X, y, x0, mixed=True)
     try:
-        if fused:
-            rep.set_fused_update(True)
+        rep.set_fused_update(fused)
         for h in range(2):
             idx = W.step_indices(w, 0, h, b)
             rep.local_step(idx, w.lr)
@@ -606,7 +605,7 @@ def test_bf16_free_running_twin_with_heavy_ball_and_adamw(opt, lr):
 
 
 # ---------------------------------------------------------------------------------------------
-# optimizer step inside the weight-gradient epilogue (opt-in)
+# optimizer step inside the weight-gradient epilogue (the default of the bf16 path)
 # ---------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("dims,act,bs,opt,hb", [
@@ -624,7 +623,8 @@ def test_bf16_free_running_twin_with_heavy_ball_and_adamw(opt, lr):
 def test_fused_update_step_matches_oracle(dims, act, bs, opt, hb):
     """Two steps with the optimizer step applied inside the weight-gradient epilogue (the second one starts from
     non-zero optimizer state): statistics, per-sample quantities, parameters and optimizer state against the oracle;
-    the calls that need the stored gradient are refused."""
+    the calls that need the fp32 gradient (which such a step never stores) get it formed on demand from the layer
+    inputs and signals the step left; an accumulated step, which keeps its gradient in memory, runs unfused."""
     A = _A()
     M, ragged = len(bs), len(set(bs)) > 1
     w = W.Workload("fused", dims, act, hb, W.PREC_BF16, N=max(2048, max(bs)), M=M, H=1, rounds=1, b0=max(bs), b_cap=max(bs) + 5, opt=opt,
@@ -679,15 +679,30 @@ def test_fused_update_step_matches_oracle(dims, act, bs, opt, hb):
                     orc.st[m].v = rep.get_opt_state(m, 0).astype(np.float64)
                 if opt == W.OPT_ADAMW:
                     orc.st[m].m = rep.get_opt_state(m, 1).astype(np.float64)
-            with pytest.raises(A.AbsError, match="not stored"):
-                rep.get_grad(0)
+            # the gradient of the step, formed after the fact
+            for m in (0, M - 1):
+                grad = rep.get_grad(m).astype(np.float64)
+                assert np.abs(grad - orc.grads[m]).max() <= 2e-3 * np.abs(orc.grads[m]).max(), (step, m)
             if M >= 2 and not ragged:
-                with pytest.raises(A.AbsError, match="not stored"):
-                    rep.cross_worker_test(0.5)
-        with pytest.raises(A.AbsError, match="accumulated"):
-            rep.local_step_accumulated(np.stack([r[:max(bs)] for r in rows]) if not ragged else np.zeros((M, 8), np.int32), 4, w.lr)
-        assert rep.guard_intact()
+                cw, ocw = rep.cross_worker_test(0.5), O.cross_worker_test(orc.grads, bs[0], 0.5)
+                assert _rel(cw.gbar_sq, ocw["S2"]) <= 2e-3 and _rel(cw.sum_sq, ocw["sum_sq"]) <= 2e-3
+            assert rep.inner_product_test(w.theta, w.nu)[0].sum_sq == g[0].sum_sq      # the statistics are untouched
         assert rep.counters() == (0, 2, 2 * sum(bs))
+        if not ragged and bs[0] >= 8:
+            # a third step through the accumulating entry point (two micro-batches): the gradient stays in memory
+            b = bs[0]
+            micro = (b + 1) // 2 + ((b % ((b + 1) // 2)) == 1)
+            rows = [W.batch_indices(w.seed, 2, 0, m, b, w.N) for m in range(M)]
+            rep.local_step_accumulated(np.stack(rows), micro, w.lr)
+            orc.local_step(rows, w.lr)
+            g = rep.inner_product_test(w.theta, w.nu)
+            for m in range(M):
+                st = orc.stats[m]
+                for name, got, want in (("S1", g[m].sum_sq, st["S1"]), ("S2", g[m].gbar_sq, st["S2"]),
+                                        ("S3", g[m].sum_q2, st["S3"]), ("S4", g[m].sum_q, st["S4"])):
+                    assert _rel(got, want) <= 3e-3, ("accumulated", m, name, got, want)
+            assert rep.counters() == (0, 3, 3 * sum(bs))
+        assert rep.guard_intact()
     finally:
         rep.close()
 
@@ -712,11 +727,7 @@ def test_fused_update_equals_the_unfused_step(dims, b):
             r = rep.inner_product_test(w.theta)
             out.append(([rep.get_params(m) for m in range(3)], [(t.sum_sq, t.sum_q, t.sum_q2, t.loss_sum) for t in r],
                         [t.gbar_sq for t in r]))
-            if fused:
-                with pytest.raises(A.AbsError, match="not stored"):
-                    rep.get_grad(1)
-            else:
-                assert np.isfinite(rep.get_grad(1)).all()
+            out[-1] += (rep.get_grad(1),)       # stored by the plain step, formed on demand after the fused one
         finally:
             rep.close()
     assert out[0][1] == out[1][1]
@@ -724,6 +735,7 @@ def test_fused_update_equals_the_unfused_step(dims, b):
         assert _rel(a, b_) <= 1e-6
     for m in range(3):
         assert np.array_equal(out[0][0][m], out[1][0][m])
+    assert np.array_equal(out[0][3], out[1][3])       # the same launches on the same operands: the same entries
 
 
 def test_fused_update_needs_the_bf16_path():
@@ -1517,9 +1529,9 @@ def test_graph_replayed_steps_are_bitwise_the_direct_steps(prec, opt, fused):
     with torch.cuda.stream(side):
         ref = A.Replicas.from_workload(w, X, y, x0)
         rep = A.Replicas.from_workload(w, X, y, x0)
-        if fused:                              # the optimizer step inside the weight-gradient epilogue, replayed
-            ref.set_fused_update(True)
-            rep.set_fused_update(True)
+        if prec == W.PREC_BF16:                # the optimizer step inside the weight-gradient epilogue, replayed, or not
+            ref.set_fused_update(fused)
+            rep.set_fused_update(fused)
         try:
             sizes = [32, 32, 32, 48, 32, 48, 48, 32, 64, 48, 32, 32]
             for s, b in enumerate(sizes):
