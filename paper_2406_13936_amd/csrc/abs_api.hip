@@ -244,7 +244,7 @@ struct abs_ctx {
   bool fused_update = true;       // abs_set_fused_update: apply the optimizer step inside the weight-gradient epilogue (bf16 mode)
   bool last_fused = false;        // the last step did so: the fp32 gradient of its weights is not stored (materialize_grad)
   // captured steps (abs_local_step_graphed): one executable graph per batch size, a few kept
-  struct GraphSlot { int b; hipGraphExec_t exec; long long last_use; };
+  struct GraphSlot { int b; hipGraphExec_t exec; long long last_use; bool fused; };   // fused: the captured step took its update in the weight-gradient epilogue
   std::vector<GraphSlot> graphs;
   std::vector<int> graph_warm;      // batch sizes that ran once eagerly (kernel attributes are set)
   std::string err;
@@ -1044,7 +1044,7 @@ abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, flo
       (void)hipGraphExecDestroy(c->graphs[old].exec);
       c->graphs.erase(c->graphs.begin() + old);
     }
-    c->graphs.push_back({b, exec, 0});
+    c->graphs.push_back({b, exec, 0, c->last_fused});    // (set by the capturing pass)
     slot = &c->graphs.back();
   }
   slot->last_use = c->t;
@@ -1053,6 +1053,7 @@ abs_status abs_local_step_graphed(abs_ctx *c, const int32_t *idx_dev, int b, flo
     hipError_t el = hipGraphLaunch(slot->exec, c->stream);
     if (el != hipSuccess) return settle_update(c, cfail(c, ABS_EHIP, std::string("hipGraphLaunch: ") + hipGetErrorString(el)));
   }
+  c->last_fused = slot->fused;        // whether the replayed step left its fp32 gradient unstored
   note_step(c, b, nullptr);
   return ABS_OK;
 } catch (...) { return on_exception(); }
