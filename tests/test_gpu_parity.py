@@ -331,12 +331,14 @@ def test_config3_real_widths_large_tiles_ragged_batch():
 # trajectories
 # ---------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("cfg,sampled", [("config2", (0, 7)), ("config3", (0, 11)), ("config4", (29,))])
+@pytest.mark.parametrize("cfg,sampled", [("config2", (0, 7)), ("config3", (0, 11)), ("config4", (29,)),
+                                         ("config3:separate update", (5,))])
 def test_full_size_at_the_cap_sampled_replicas(cfg, sampled):
     """The configurations at their full sizes (all M replicas, b = b_cap, full dataset; config 3 is
     the benchmark's own launch configuration): the sampled replicas are recomputed by the oracle on
     their whole batch; all others are checked through properties that hold for any batch."""
     A = _A()
+    cfg, _, form = cfg.partition(":")
     w = getattr(W, cfg)()
     X, y = W.make_dataset(w)
     x0 = W.make_x0(w)
@@ -345,6 +347,8 @@ def test_full_size_at_the_cap_sampled_replicas(cfg, sampled):
     net = O.Net(w.dims, w.act, w.has_bias)
     want_ip = w.test != W.TEST_NORM
     try:
+        if form:                      # what `bench.py --plain-update` times; the default takes the step in the epilogue
+            rep.set_fused_update(False)
         idx = W.step_indices(w, 0, 0, b)
         rep.local_step(idx, w.lr)
         g = _gpu_test(rep, w)
