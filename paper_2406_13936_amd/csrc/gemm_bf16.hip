@@ -268,19 +268,19 @@ gemm_bf16_kernel(const GemmP pin, const int tilesM, const int tilesN, const int 
   // Fused optimizer step (EPI_WGRAD_UPD): the epilogue walks this wave's slices (32 rows x TN columns) in batches of
   // UHB 16-byte chunks per lane, and the loads of batch k + 1 (parameters and optimizer state) are issued before
   // batch k is processed, so that a wave always has a batch of loads in flight while it computes and stores.
-  // (Four chunks for the 128 x 128 tiles: config 3 at b = 64 2.4 % faster than with two, b = 256 unchanged; the
-  // 256 x 256 tile has no registers to spare for more than two.)
+  // (Four chunks for the 128 x 128 and 64 x 256 tiles: config 3 at b = 64 2.4 % faster than with two, b = 256
+  // unchanged; the 256 x 256 tile has no registers to spare for more than two.)
   constexpr bool UPD = EPI == EPI_WGRAD_UPD;
   constexpr int UFCPR = TN / 4;                             // float4 chunks per slice row
   constexpr int UFIT = 32 * UFCPR / 64;                     // chunks per lane per slice
-  constexpr int UHBW = (BM == 128 && BN == 128) ? 4 : 2;
+  constexpr int UHBW = ((BM == 128 && BN == 128) || BM == 64) ? 4 : 2;
   constexpr int UHB = UFIT < UHBW ? UFIT : UHBW;
   constexpr int UBPS = UFIT / UHB;
   static_assert(!UPD || UFIT % UHB == 0, "chunk batches");
-  // The 128 x 128 tiles (short batches: a launch is all epilogue) issue the first batch before the operand loads of
+  // The 128 x 128 and 64 x 256 tiles (short batches: a launch is all epilogue) issue the first batch before the operand loads of
   // the reduction, so that its latency passes behind the main loop; being older than every operand load, these
   // loads do not disturb the counting of the main loop's waits (loads return in order).
-  constexpr bool UPD_EARLY = UPD && BM == 128 && BN == 128;
+  constexpr bool UPD_EARLY = UPD && ((BM == 128 && BN == 128) || BM == 64);
   float4 xq[2][UPD ? UHB : 1], vq[2][UPD ? UHB : 1], mq[2][UPD ? UHB : 1];
   const long long ugoff = UPD ? (long long)g * p.sCg : 0;
   auto upd_where = [&](int bi, int u, int &m, int &n, int &row, int &cc) {
@@ -762,7 +762,7 @@ hipError_t launch_shape(const GemmP &p, hipStream_t s) {
   switch (IS_WGRAD ? gemm_bf16_wgrad_shape(p.Md, p.Nd, p.Kd, p.groups) : gemm_bf16_tile_shape(p.Md, p.Nd, p.groups)) {
     case 0: return launch_cfg<128, 64, 64, 4, 1, 3, AT, BT, EPI, ACT>(p, s);
     case 3:
-      if constexpr (IS_WGRAD) return launch_cfg<128, 128, 32, 2, 2, 2, AT, BT, EPI, ACT>(p, s);
+      if constexpr (IS_WGRAD) return launch_cfg<64, 256, 32, 1, 4, 2, AT, BT, EPI, ACT>(p, s);
       else return hipErrorInvalidValue;
     case 2: return launch_cfg<256, 256, 64, 2, 4, 2, AT, BT, EPI, ACT>(p, s);
     default: {
@@ -817,17 +817,19 @@ int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
 }
 
 // Weight gradients reduce over the local batch (Kd = b).  While the batch is short the launch is all epilogue
-// (one or a few k-tiles, then 4 to 20 bytes of stores and loads per output entry): a 128 x 128 x 32 tile with two
-// 16 KB stages lets four work-groups share a CU, which keeps far more memory requests in flight than one
-// 256 x 256 work-group does.
+// (one or a few k-tiles, then 4 to 20 bytes of stores and loads per output entry): a 64 x 256 x 32 tile with two
+// 20 KB stages lets several work-groups share a CU, which keeps far more memory requests in flight than one
+// 256 x 256 work-group does; its four wavefronts sit side by side, so a work-group touches 1 KB of consecutive
+// bytes in each of its 64 rows (measured against a 128 x 128 tile, 512 bytes in each of 128 rows, on config 3 at
+// b = 64: 2 to 2.5 % faster with the optimizer step in the epilogue, equal at b = 256).
 int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups) {
   const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
-  if (sh != 0 && Kd <= 256) return 3;
+  if (sh != 0 && Kd <= 256) return 3;        // (measured on config 3: at b = 384 and above the large tiles are faster)
   return sh;
 }
 
 int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups) {
-  const int bm[4] = {128, 128, 256, 128}, bn[4] = {64, 128, 256, 128}, nw[4] = {4, 4, 8, 4};
+  const int bm[4] = {128, 128, 256, 64}, bn[4] = {64, 128, 256, 256}, nw[4] = {4, 4, 8, 4};
   const int sh = gemm_bf16_wgrad_shape(Md, Nd, Kd, groups);
   return ((Md + bm[sh] - 1) / bm[sh]) * ((Nd + bn[sh] - 1) / bn[sh]) * nw[sh];
 }
