@@ -311,7 +311,7 @@ struct ProfScope {
 };
 
 hipError_t gemm(abs_ctx *c, const GemmP &p, int epi, int layer) {
-  int shape = !c->pl.bf16 ? 1 : (epi == EPI_WGRAD ? gemm_bf16_wgrad_shape(p.Md, p.Nd, p.Kd, p.groups)
+  int shape = !c->pl.bf16 ? 1 : (epi == EPI_WGRAD ? gemm_bf16_wgrad_shape(p.Md, p.Nd, p.Kd, p.groups, p.upd_x != nullptr)
                                                    : gemm_bf16_tile_shape(p.Md, p.Nd, p.groups));
   // algorithmic bytes of the launch: both operands once, the outputs once, the epilogue's elementwise operand once
   const double e = c->pl.esz, mn = (double)p.Md * p.Nd;
@@ -692,7 +692,7 @@ static abs_status local_step_impl(abs_ctx *c, const int32_t *idx_dev, int ldi, i
   auto bf16_ksplit = [&](int l) -> int {
     const int Md = pl.dims[l], Nd = pl.dims[l - 1];
     if (!pl.bf16 || (Nd & 3)) return 1;
-    const int sh = gemm_bf16_wgrad_shape(Md, Nd, b, M);
+    const int sh = gemm_bf16_wgrad_shape(Md, Nd, b, M, want_fused);
     if (sh == 3) return 1;                      // short batches: never split
     const int te = sh == 2 ? 256 : 128, tn_e = sh == 0 ? 64 : te;
     const long long tiles = (long long)((Md + te - 1) / te) * ((Nd + tn_e - 1) / tn_e) * M;

@@ -80,8 +80,10 @@ int gemm_bf16_col_parts(int Md, int Nd, int groups);
 // Tile shape the bf16 family uses for an Md x Nd output over `groups` replicas: 0 = 128x64, 1 = 128x128, 2 = 256x256.
 int gemm_bf16_tile_shape(int Md, int Nd, int groups);
 // Tile shape of an EPI_WGRAD launch whose reduction runs over Kd samples: as above, or 3 = 64x256 with a k-step of
-// 32 and several work-groups per CU while the batch is short and the launch is bound by its epilogue's memory traffic.
-int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups);
+// 32 and several work-groups per CU while the batch is short and the launch is bound by its epilogue's memory traffic;
+// fused != 0: the launch carries the optimizer step in its epilogue (GemmP::upd_x), which keeps medium batches on
+// 128x128 tiles.
+int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups, int fused);
 // Number of upd_sq slots an EPI_WGRAD launch with an in-epilogue optimizer step writes per group.
 int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups);
 // fp32 SIMT family (gemm_f32.hip); EPI_IPDOT is not offered (U is materialised instead).

@@ -759,7 +759,7 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
 template <bool AT, bool BT, int EPI, int ACT>
 hipError_t launch_shape(const GemmP &p, hipStream_t s) {
   constexpr bool IS_WGRAD = EPI == EPI_WGRAD || EPI == EPI_WGRAD_UPD;
-  switch (IS_WGRAD ? gemm_bf16_wgrad_shape(p.Md, p.Nd, p.Kd, p.groups) : gemm_bf16_tile_shape(p.Md, p.Nd, p.groups)) {
+  switch (IS_WGRAD ? gemm_bf16_wgrad_shape(p.Md, p.Nd, p.Kd, p.groups, p.upd_x != nullptr) : gemm_bf16_tile_shape(p.Md, p.Nd, p.groups)) {
     case 0: return launch_cfg<128, 64, 64, 4, 1, 3, AT, BT, EPI, ACT>(p, s);
     case 3:
       if constexpr (IS_WGRAD) return launch_cfg<64, 256, 32, 1, 4, 2, AT, BT, EPI, ACT>(p, s);
@@ -822,15 +822,19 @@ int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
 // 256 x 256 work-group does; its four wavefronts sit side by side, so a work-group touches 1 KB of consecutive
 // bytes in each of its 64 rows (measured against a 128 x 128 tile, 512 bytes in each of 128 rows, on config 3 at
 // b = 64: 2 to 2.5 % faster with the optimizer step in the epilogue, equal at b = 256).
-int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups) {
+int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups, int fused) {
   const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
+  // with the optimizer step in the epilogue a medium batch is still mostly epilogue: two or three 128 x 128
+  // work-groups per CU stream it better than one 256 x 256 work-group (config 3: b = 384 1.92 -> 1.87 ms per step,
+  // b = 512 2.02 -> 2.00; from b = 768 on the large tile wins)
+  if (fused && sh == 2 && Kd <= 512) return 1;
   if (sh != 0 && Kd <= 256) return 3;        // (measured on config 3: at b = 384 and above the large tiles are faster)
   return sh;
 }
 
-int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups) {
+int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups) {   // (always with the step in the epilogue)
   const int bm[4] = {128, 128, 256, 64}, bn[4] = {64, 128, 256, 256}, nw[4] = {4, 4, 8, 4};
-  const int sh = gemm_bf16_wgrad_shape(Md, Nd, Kd, groups);
+  const int sh = gemm_bf16_wgrad_shape(Md, Nd, Kd, groups, 1);
   return ((Md + bm[sh] - 1) / bm[sh]) * ((Nd + bn[sh] - 1) / bn[sh]) * nw[sh];
 }
 
