@@ -824,11 +824,11 @@ int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
 // b = 64: 2 to 2.5 % faster with the optimizer step in the epilogue, equal at b = 256).
 int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups, int fused) {
   const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
+  if (sh != 0 && Kd <= 256) return 3;        // (measured on config 3: at b = 384 and above the large tiles are faster)
   // with the optimizer step in the epilogue a medium batch is still mostly epilogue: two or three 128 x 128
   // work-groups per CU stream it better than one 256 x 256 work-group (config 3: b = 384 1.92 -> 1.87 ms per step,
   // b = 512 2.02 -> 2.00; from b = 768 on the large tile wins)
   if (fused && sh == 2 && Kd <= 512) return 1;
-  if (sh != 0 && Kd <= 256) return 3;        // (measured on config 3: at b = 384 and above the large tiles are faster)
   return sh;
 }
 
