@@ -200,17 +200,17 @@ int choose_ksplit(int shape, long long tiles, int KT, double outputs, size_t kpa
 // Event-timed launch classes (abs_profile_*): one entry per kernel symbol of interest.
 enum {
   T_GATHER = 0, T_SOFTMAX, T_ROWNORM, T_COLSUM, T_STATS, T_UPDATE, T_AVERAGE, T_ROWDOT, T_GRAM,
-  T_GEMM0,                       // + epi * 4 + tile shape (bf16) ; fp32 family uses shape 1
-  T_GEMM_KINDS = 5 * 4, T_LAYERS = 17,   // GEMM classes are resolved per layer
+  T_GEMM0,                       // + epi * 5 + tile shape (bf16) ; fp32 family uses shape 1
+  T_GEMM_KINDS = 5 * 5, T_LAYERS = 17,   // GEMM classes are resolved per layer
   T_COUNT = T_GEMM0 + T_GEMM_KINDS * T_LAYERS
 };
 static const char *const kTagNames[T_GEMM0 + T_GEMM_KINDS] = {
   "gather_rows", "softmax_ce", "row_sqnorm", "col_sum", "stats", "update", "average", "rowdot", "gram_ip",
-  "gemm_fwd_128x64", "gemm_fwd_128x128", "gemm_fwd_256x256", "gemm_fwd_64x256",
-  "gemm_logits_128x64", "gemm_logits_128x128", "gemm_logits_256x256", "gemm_logits_64x256",
-  "gemm_bwd_128x64", "gemm_bwd_128x128", "gemm_bwd_256x256", "gemm_bwd_64x256",
-  "gemm_wgrad_128x64", "gemm_wgrad_128x128", "gemm_wgrad_256x256", "gemm_wgrad_64x256",
-  "gemm_ipdot_128x64", "gemm_ipdot_128x128", "gemm_ipdot_256x256", "gemm_ipdot_64x256"};
+  "gemm_fwd_128x64", "gemm_fwd_128x128", "gemm_fwd_256x256", "gemm_fwd_64x256", "gemm_fwd_64x128",
+  "gemm_logits_128x64", "gemm_logits_128x128", "gemm_logits_256x256", "gemm_logits_64x256", "gemm_logits_64x128",
+  "gemm_bwd_128x64", "gemm_bwd_128x128", "gemm_bwd_256x256", "gemm_bwd_64x256", "gemm_bwd_64x128",
+  "gemm_wgrad_128x64", "gemm_wgrad_128x128", "gemm_wgrad_256x256", "gemm_wgrad_64x256", "gemm_wgrad_64x128",
+  "gemm_ipdot_128x64", "gemm_ipdot_128x128", "gemm_ipdot_256x256", "gemm_ipdot_64x256", "gemm_ipdot_64x128"};
 
 struct ProfRec { int tag; hipEvent_t e0, e1; double flops, bytes; };
 
@@ -322,7 +322,7 @@ hipError_t gemm(abs_ctx *c, const GemmP &p, int epi, int layer) {
   else if (epi == EPI_IPDOT) bytes += mn * e;
   else if (p.upd_x) bytes += mn * (8 + (p.upd_v ? 8 : 0) + (p.upd_m ? 8 : 0) + (p.upd_shadow ? 2 : 0) + (p.C2 ? 2 : 0));
   else bytes += mn * (4 + (p.C2 ? 2 : 0) + (p.accumulate ? 4 : 0));
-  ProfScope ps(c, T_GEMM0 + (epi * 4 + shape) * T_LAYERS + layer, 2.0 * p.Md * p.Nd * p.Kd * p.groups, bytes * p.groups);
+  ProfScope ps(c, T_GEMM0 + (epi * 5 + shape) * T_LAYERS + layer, 2.0 * p.Md * p.Nd * p.Kd * p.groups, bytes * p.groups);
   return c->pl.bf16 ? launch_gemm_bf16(p, epi, c->stream) : launch_gemm_f32(p, epi, c->stream);
 }
 

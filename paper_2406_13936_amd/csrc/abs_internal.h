@@ -77,7 +77,8 @@ int gemm_bf16_ipdot_parts(int Nd);
 // wave rows) that the bf16 family writes for an Md x Nd output.
 int gemm_bf16_row_parts(int Md, int Nd, int groups);
 int gemm_bf16_col_parts(int Md, int Nd, int groups);
-// Tile shape the bf16 family uses for an Md x Nd output over `groups` replicas: 0 = 128x64, 1 = 128x128, 2 = 256x256.
+// Tile shape the bf16 family uses for an Md x Nd output over `groups` replicas: 0 = 128x64, 1 = 128x128, 2 = 256x256,
+// 4 = 64x128 with a six-stage ring (outputs of at most 64 rows; 3 is a weight-gradient shape, see below).
 int gemm_bf16_tile_shape(int Md, int Nd, int groups);
 // Tile shape of an EPI_WGRAD launch whose reduction runs over Kd samples: as above, or 3 = 64x256 with a k-step of
 // 32 and several work-groups per CU while the batch is short and the launch is bound by its epilogue's memory traffic;

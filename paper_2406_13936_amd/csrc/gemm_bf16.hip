@@ -755,7 +755,7 @@ hipError_t launch_cfg(const GemmP &p, hipStream_t s) {
 }
 
 // Tile shape by problem size: the large shape when both output extents fill it,
-// otherwise a 128x128 (or 128x64 for narrow outputs) tile.
+// otherwise a 128x128 (or 128x64 for narrow outputs, 64x128 for outputs of at most 64 rows) tile.
 template <bool AT, bool BT, int EPI, int ACT>
 hipError_t launch_shape(const GemmP &p, hipStream_t s) {
   constexpr bool IS_WGRAD = EPI == EPI_WGRAD || EPI == EPI_WGRAD_UPD;
@@ -765,6 +765,9 @@ hipError_t launch_shape(const GemmP &p, hipStream_t s) {
       if constexpr (IS_WGRAD) return launch_cfg<64, 256, 32, 1, 4, 2, AT, BT, EPI, ACT>(p, s);
       else return hipErrorInvalidValue;
     case 2: return launch_cfg<256, 256, 64, 2, 4, 2, AT, BT, EPI, ACT>(p, s);
+    case 4:
+      if constexpr (!IS_WGRAD) return launch_cfg<64, 128, 64, 2, 2, 6, AT, BT, EPI, ACT>(p, s);
+      else return hipErrorInvalidValue;
     default: {
       // Two stages (64 KB) let two work-groups share a CU; a deeper ring keeps one work-group fed through a long
       // reduction.  Two when the reduction is short or the launch has more blocks than CUs (measured: 2048-wide
@@ -804,6 +807,11 @@ hipError_t launch_act(const GemmP &p, hipStream_t s) {
 
 int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
   if (Nd <= 64) return 0;
+  // up to 64 rows (the first local batch sizes): the launch streams its B operand (the weights) once and is bound by
+  // that stream; a 64-row tile leaves LDS for a ring of six stages, five k-tiles of B in flight per work-group
+  // (config 3 at b = 64 against the 128 x 128 tile with four stages: forward 4.1 -> 4.3 TB/s of weight bytes,
+  // backward-data 4.5 -> 5.0-5.1, the step 1.17 -> 1.155 ms)
+  if (Md <= 64) return 4;
   if (Md >= 1024 && Nd >= 1024) return 2;
   // mid-sized outputs: the large tile only if it still gives every CU a work-group and its last row of tiles is
   // not mostly padding (measured on 2048-wide layers, 16 groups: b = 384 and 512 faster with 256 x 256 tiles,
@@ -823,7 +831,8 @@ int gemm_bf16_tile_shape(int Md, int Nd, int groups) {
 // bytes in each of its 64 rows (measured against a 128 x 128 tile, 512 bytes in each of 128 rows, on config 3 at
 // b = 64: 2 to 2.5 % faster with the optimizer step in the epilogue, equal at b = 256).
 int gemm_bf16_wgrad_shape(int Md, int Nd, int Kd, int groups, int fused) {
-  const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
+  int sh = gemm_bf16_tile_shape(Md, Nd, groups);
+  if (sh == 4) sh = 1;                       // (the short-batch tile of the other contractions)
   if (sh != 0 && Kd <= 256) return 3;        // (measured on config 3: at b = 384 and above the large tiles are faster)
   // with the optimizer step in the epilogue a medium batch is still mostly epilogue: two or three 128 x 128
   // work-groups per CU stream it better than one 256 x 256 work-group (config 3: b = 384 1.92 -> 1.87 ms per step,
@@ -839,19 +848,19 @@ int gemm_bf16_upd_slots(int Md, int Nd, int Kd, int groups) {   // (always with 
 }
 
 int gemm_bf16_row_parts(int Md, int Nd, int groups) {
-  const int bn[3] = {64, 128, 256};
+  const int bn[5] = {64, 128, 256, 0, 128};
   const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
   return (Nd + bn[sh] - 1) / bn[sh];
 }
 
 int gemm_bf16_col_parts(int Md, int Nd, int groups) {
-  const int bm[3] = {128, 128, 256}, wm[3] = {4, 2, 2};
+  const int bm[5] = {128, 128, 256, 0, 64}, wm[5] = {4, 2, 2, 0, 2};
   const int sh = gemm_bf16_tile_shape(Md, Nd, groups);
   return (Md + bm[sh] - 1) / bm[sh] * wm[sh];
 }
 
 void gemm_bf16_col_part_shape(int shape, int *tile_m, int *parts_per_tile) {
-  const int bm[3] = {128, 128, 256}, wm[3] = {4, 2, 2};
+  const int bm[5] = {128, 128, 256, 0, 64}, wm[5] = {4, 2, 2, 0, 2};
   *tile_m = bm[shape];
   *parts_per_tile = wm[shape];
 }
